@@ -1,0 +1,277 @@
+"""CPU oracle for the unit-scaled linear / FFN hot path -- TEST INFRASTRUCTURE ONLY.
+
+Thin numpy front-end over ``us_oracle.c`` (plain C, double arithmetic, index-order sums; see the
+header of that file for the passages of the paper each function follows).  Only the tests, the
+smoke check and the benchmark's ``cpu_baseline`` leg may import this package; the HIP library
+and its Python binding never do, and this package imports nothing from them.
+
+Array conventions: FP32 -> ``np.float32``, FP16 -> ``np.float16``, FP8 -> ``np.uint8`` codes
+(OCP E4M3 / E5M2 = rows "E4 (b)" / "E5 (b)" of Table A.1).  All matrices are row-major:
+X[b,m], W[m,n], G[b,n].
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+import subprocess
+
+import numpy as np
+
+F32, F16, E4M3, E5M2 = 0, 1, 2, 3
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "us_oracle.c")
+_LIB = os.path.join(_HERE, "libus_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile us_oracle.c with gcc (-O2, OpenMP, no FP contraction). Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               _SRC, "-o", _LIB, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    lib = ctypes.CDLL(build())
+    vp, i, l, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_float, ctypes.c_size_t
+    lib.uso_decode_bits.argtypes = [ctypes.c_uint32, i]
+    lib.uso_decode_bits.restype = ctypes.c_double
+    lib.uso_encode_f64.argtypes = [ctypes.c_double, i, i]
+    lib.uso_encode_f64.restype = ctypes.c_uint32
+    lib.uso_decode.argtypes = [vp, i, sz, vp]
+    lib.uso_decode.restype = None
+    lib.uso_encode.argtypes = [vp, sz, i, i, vp]
+    lib.uso_encode.restype = None
+    lib.uso_cast_fp8.argtypes = [vp, i, vp, i, sz, f, vp]
+    lib.uso_cast_fp8.restype = None
+    for name in ("uso_linear_fwd", "uso_linear_bwd_dx", "uso_linear_bwd_dw"):
+        fn = getattr(lib, name)
+        fn.argtypes = [vp, i, vp, i, vp, i, l, l, l, f]
+        fn.restype = i
+    lib.uso_gelu_fwd.argtypes = [vp, vp, sz, i, f]
+    lib.uso_gelu_fwd.restype = None
+    lib.uso_gelu_bwd.argtypes = [vp, vp, vp, sz, i, f]
+    lib.uso_gelu_bwd.restype = None
+    lib.uso_linear_scales.argtypes = [l, l, l, i, vp, vp, vp]
+    lib.uso_linear_scales.restype = None
+    _lib = lib
+    return lib
+
+
+_NP = {F32: np.float32, F16: np.float16, E4M3: np.uint8, E5M2: np.uint8}
+
+
+def _dt_of(a: np.ndarray, dt):
+    """Storage type id of an array: explicit for uint8 codes, inferred for float arrays."""
+    if dt is not None:
+        if a.dtype != _NP[dt]:
+            raise TypeError(f"array dtype {a.dtype} does not match storage type {dt}")
+        return dt
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.float16:
+        return F16
+    raise TypeError("FP8 code arrays (uint8) need an explicit E4M3/E5M2 type")
+
+
+def _c(a: np.ndarray) -> np.ndarray:
+    return np.ascontiguousarray(a)
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def cpu_threads() -> int:
+    """Threads the OpenMP loops use (OMP_NUM_THREADS if set, else the visible cores)."""
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env and env.isdigit() and int(env) > 0:
+        return int(env)
+    try:
+        return len(os.sched_getaffinity(0))
+    except AttributeError:
+        return os.cpu_count() or 1
+
+
+# ---- formats ---------------------------------------------------------------------------------
+def decode(a: np.ndarray, dt=None) -> np.ndarray:
+    """Exact value (float64) of every stored element (Sec. 3.1 value formula)."""
+    a = _c(a)
+    dt = _dt_of(a, dt)
+    out = np.empty(a.shape, np.float64)
+    _load().uso_decode(_p(a), dt, a.size, _p(out))
+    return out
+
+
+def encode(v: np.ndarray, dt: int, saturate: bool) -> np.ndarray:
+    """Nearest representable value of each float64 (ties to even); clip or IEEE overflow."""
+    v = _c(np.asarray(v, np.float64))
+    out = np.empty(v.shape, _NP[dt])
+    _load().uso_encode(_p(v), v.size, dt, int(saturate), _p(out))
+    return out
+
+
+def decode_scalar(bits: int, dt: int) -> float:
+    return float(_load().uso_decode_bits(bits, dt))
+
+
+def encode_scalar(v: float, dt: int, saturate: bool) -> int:
+    return int(_load().uso_encode_f64(v, dt, int(saturate)))
+
+
+# ---- scaled saturating cast --------------------------------------------------------------------
+STAT_NAMES = ("n_sat", "n_flush0", "n_subnormal", "n_nan")
+
+
+def cast_fp8(src: np.ndarray, dst_dt: int, scale: float = 1.0, src_dt=None):
+    """codes = nearest-FP8(fp32(src*scale)), clipped at +-max.  Returns (codes, stats dict)."""
+    src = _c(src)
+    src_dt = _dt_of(src, src_dt)
+    out = np.empty(src.shape, np.uint8)
+    stats = np.zeros(4, np.uint64)
+    _load().uso_cast_fp8(_p(src), src_dt, _p(out), dst_dt, src.size, float(np.float32(scale)), _p(stats))
+    return out, {k: int(v) for k, v in zip(STAT_NAMES, stats)}
+
+
+# ---- scaled matmuls ------------------------------------------------------------------------------
+def linear_scales(b: int, m: int, n: int, mode: int = 0):
+    """(alpha, beta_x, beta_w) as float32 (Table A.2 "Linear"; mode 1 = geometric-mean constraint)."""
+    a, bx, bw = (ctypes.c_float() for _ in range(3))
+    _load().uso_linear_scales(b, m, n, mode, ctypes.byref(a), ctypes.byref(bx), ctypes.byref(bw))
+    return np.float32(a.value), np.float32(bx.value), np.float32(bw.value)
+
+
+def _check(rc):
+    if rc != 0:
+        raise MemoryError("oracle could not allocate its temporaries")
+
+
+def linear_fwd(X, W, alpha, x_dt=None, w_dt=None, out_dt=F16):
+    """Y[b,n] = round(alpha * X[b,m] W[m,n])."""
+    X, W = _c(X), _c(W)
+    b, m = X.shape
+    m2, n = W.shape
+    assert m == m2
+    Y = np.empty((b, n), _NP[out_dt])
+    _check(_load().uso_linear_fwd(_p(X), _dt_of(X, x_dt), _p(W), _dt_of(W, w_dt), _p(Y), out_dt,
+                                  b, m, n, float(np.float32(alpha))))
+    return Y
+
+
+def linear_bwd_dx(G, W, beta_x, g_dt=None, w_dt=None, out_dt=F16):
+    """dX[b,m] = round(beta_x * G[b,n] W[m,n]^T)."""
+    G, W = _c(G), _c(W)
+    b, n = G.shape
+    m, n2 = W.shape
+    assert n == n2
+    dX = np.empty((b, m), _NP[out_dt])
+    _check(_load().uso_linear_bwd_dx(_p(G), _dt_of(G, g_dt), _p(W), _dt_of(W, w_dt), _p(dX), out_dt,
+                                     b, m, n, float(np.float32(beta_x))))
+    return dX
+
+
+def linear_bwd_dw(X, G, beta_w, x_dt=None, g_dt=None, out_dt=F16):
+    """dW[m,n] = round(beta_w * X[b,m]^T G[b,n])."""
+    X, G = _c(X), _c(G)
+    b, m = X.shape
+    b2, n = G.shape
+    assert b == b2
+    dW = np.empty((m, n), _NP[out_dt])
+    _check(_load().uso_linear_bwd_dw(_p(X), _dt_of(X, x_dt), _p(G), _dt_of(G, g_dt), _p(dW), out_dt,
+                                     b, m, n, float(np.float32(beta_w))))
+    return dW
+
+
+# ---- unit-scaled GELU ----------------------------------------------------------------------------
+def gelu_scales():
+    """(alpha_g, beta_g) for gelu(x) = x*Phi(x) under z ~ N(0,1) (Table A.2 prints 1.701, 1.481).
+
+    Rule of Sec. 5.2 "Selecting scaling factors": alpha = 1/std(gelu(z)), beta = 1/std of the
+    gradient gelu'(z)*g for an independent unit-variance g, i.e. 1/rms(gelu'(z)).  Closed forms
+    (Gaussian integrals):  E[gelu^2] = 1/3 + 1/(2 pi sqrt 3),  E[gelu] = 1/(2 sqrt pi),
+    E[gelu'^2] = 1/3 + 2/(3 pi sqrt 3).
+    """
+    e2 = 1.0 / 3.0 + 1.0 / (2.0 * math.pi * math.sqrt(3.0))
+    e1 = 1.0 / (2.0 * math.sqrt(math.pi))
+    d2 = 1.0 / 3.0 + 2.0 / (3.0 * math.pi * math.sqrt(3.0))
+    return np.float32(1.0 / math.sqrt(e2 - e1 * e1)), np.float32(1.0 / math.sqrt(d2))
+
+
+def gelu_fwd(z, alpha_g):
+    """h = round(alpha_g * z * Phi(z)), same storage type as z (FP16 or FP32)."""
+    z = _c(z)
+    dt = _dt_of(z, None)
+    h = np.empty_like(z)
+    _load().uso_gelu_fwd(_p(z), _p(h), z.size, dt, float(np.float32(alpha_g)))
+    return h
+
+
+def gelu_bwd(z, gh, beta_g):
+    """gz = round(beta_g * (Phi(z) + z*phi(z)) * gh)."""
+    z, gh = _c(z), _c(gh)
+    dt = _dt_of(z, None)
+    assert gh.dtype == z.dtype and gh.shape == z.shape
+    gz = np.empty_like(z)
+    _load().uso_gelu_bwd(_p(z), _p(gh), _p(gz), z.size, dt, float(np.float32(beta_g)))
+    return gz
+
+
+# ---- FFN chain: Linear -> unit-scaled GELU -> Linear, forward and backward -----------------------
+def ffn_fwd(X16, W1_16, W2_16, fp8: bool, alpha_g=None):
+    """Stage-by-stage forward pass with every stored intermediate kept (all roundings included).
+
+    FP8 mode quantises only the matmul inputs (X, W1, H, W2 -> E4M3); Z, H, Y stay FP16.
+    """
+    if alpha_g is None:
+        alpha_g = gelu_scales()[0]
+    T, d = X16.shape
+    f = W1_16.shape[1]
+    a1 = linear_scales(T, d, f)[0]
+    a2 = linear_scales(T, f, d)[0]
+    r = {}
+    if fp8:
+        r["X8"], _ = cast_fp8(X16, E4M3)
+        r["W1_8"], _ = cast_fp8(W1_16, E4M3)
+        r["W2_8"], _ = cast_fp8(W2_16, E4M3)
+        r["Z"] = linear_fwd(r["X8"], r["W1_8"], a1, E4M3, E4M3)
+        r["H"] = gelu_fwd(r["Z"], alpha_g)
+        r["H8"], _ = cast_fp8(r["H"], E4M3)
+        r["Y"] = linear_fwd(r["H8"], r["W2_8"], a2, E4M3, E4M3)
+    else:
+        r["Z"] = linear_fwd(X16, W1_16, a1)
+        r["H"] = gelu_fwd(r["Z"], alpha_g)
+        r["Y"] = linear_fwd(r["H"], W2_16, a2)
+    return r
+
+
+def ffn_bwd(X16, W1_16, W2_16, G16, fwd: dict, fp8: bool, beta_g=None):
+    """Backward pass given the forward intermediates; gradients are E5M2 matmul inputs in FP8 mode."""
+    if beta_g is None:
+        beta_g = gelu_scales()[1]
+    T, d = X16.shape
+    f = W1_16.shape[1]
+    _, bx2, bw2 = linear_scales(T, f, d)   # layer 2: H[T,f] W2[f,d]
+    _, bx1, bw1 = linear_scales(T, d, f)   # layer 1: X[T,d] W1[d,f]
+    r = {}
+    if fp8:
+        r["G8"], _ = cast_fp8(G16, E5M2)
+        r["dH"] = linear_bwd_dx(r["G8"], fwd["W2_8"], bx2, E5M2, E4M3)
+        r["dW2"] = linear_bwd_dw(fwd["H8"], r["G8"], bw2, E4M3, E5M2)
+        r["dZ"] = gelu_bwd(fwd["Z"], r["dH"], beta_g)
+        r["dZ8"], _ = cast_fp8(r["dZ"], E5M2)
+        r["dX"] = linear_bwd_dx(r["dZ8"], fwd["W1_8"], bx1, E5M2, E4M3)
+        r["dW1"] = linear_bwd_dw(fwd["X8"], r["dZ8"], bw1, E4M3, E5M2)
+    else:
+        r["dH"] = linear_bwd_dx(G16, W2_16, bx2)
+        r["dW2"] = linear_bwd_dw(fwd["H"], G16, bw2)
+        r["dZ"] = gelu_bwd(fwd["Z"], r["dH"], beta_g)
+        r["dX"] = linear_bwd_dx(r["dZ"], W1_16, bx1)
+        r["dW1"] = linear_bwd_dw(X16, r["dZ"], bw1)
+    return r
