@@ -1,0 +1,163 @@
+/*
+ * us.h -- C ABI of the unit-scaled linear / FFN library for AMD MI355X (gfx950).
+ *
+ * The operations are the scaled ops of "Unit Scaling: Out-of-the-Box Low-Precision Training":
+ * every op carries a fixed forward scale alpha and fixed backward scales beta_i (Sec. 5.1 "Scaled
+ * ops"), chosen so that outputs and gradients have unit variance at initialisation (Sec. 5.2), which
+ * lets all tensors live in FP16 and all matmul inputs in FP8 without a loss scale (Sec. 3.2, App. J.2).
+ *
+ * Conventions common to every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library never allocates,
+ *     frees or keeps a pointer.  Matrices are dense row-major: X[b,m], W[m,n] (fan_in x fan_out),
+ *     G[b,n].  `b` is the number of tokens (batch x sequence, flattened).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
+ *     and return; there is no host synchronisation inside.
+ *   - Errors are reported by status code only and are detected on the host before anything is
+ *     launched: a failing call has no effect on device memory.
+ *   - Tensor pointers must be 16-byte aligned; matrix dimensions must be multiples of 16.  Element
+ *     counts of the element-wise calls are arbitrary.
+ *   - Storage types: US_F16 = IEEE binary16; US_E4M3 / US_E5M2 = the 8-bit formats of Table A.1
+ *     rows "E4 (b)" / "E5 (b)" (bias 7, max 448, one NaN, no infinity / bias 15, max 57344, IEEE
+ *     specials); US_F32 = IEEE binary32.  Subnormals are honoured everywhere.
+ *   - Rounding is to nearest, ties to even.  FP16/FP32 outputs overflow to infinity (IEEE); FP8
+ *     outputs clip at the largest finite value.
+ *   - Results are bit-identical from run to run.
+ */
+#ifndef US_H_
+#define US_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  US_OK = 0,
+  US_ERR_NULL = 1,       /* a required pointer is NULL                                   */
+  US_ERR_SHAPE = 2,      /* negative dimension, or a matrix dimension not a multiple of 16 */
+  US_ERR_ALIGN = 3,      /* a pointer is not 16-byte aligned                              */
+  US_ERR_DTYPE = 4,      /* unsupported storage-type combination                          */
+  US_ERR_WORKSPACE = 5,  /* workspace missing or smaller than us_workspace_bytes()        */
+  US_ERR_LAUNCH = 6      /* the HIP runtime refused a launch                              */
+} us_status;
+
+typedef enum { US_F32 = 0, US_F16 = 1, US_E4M3 = 2, US_E5M2 = 3 } us_dtype;
+
+typedef enum {
+  US_EPI_NONE = 0,
+  US_EPI_GELU = 1,       /* forward: also emit the unit-scaled GELU of the output            */
+  US_EPI_GELU_GRAD = 2   /* grad_X: multiply by the unit-scaled GELU derivative of Zpre     */
+} us_epilogue;
+
+/* Counters of the scaled cast; device memory; added to, never cleared, by us_cast_fp8. */
+typedef struct {
+  unsigned long long n_sat;        /* |x*scale| above the largest finite value (inf included) */
+  unsigned long long n_flush0;     /* x*scale != 0 but the code is +-0                        */
+  unsigned long long n_subnormal;  /* non-zero code below the smallest normal value           */
+  unsigned long long n_nan;        /* x*scale is NaN                                          */
+} us_cast_stats;
+
+const char* us_status_string(us_status s);
+
+/*
+ * Scale selection for matmul(X[b,m], W[m,n]) (Table A.2 "Linear"; Sec. 5.5 "Example").  Host only.
+ *   mode 0: unconstrained  alpha = m^-1/2, beta_x = n^-1/2, beta_w = b^-1/2
+ *   mode 1: X is not a cut-edge, so alpha and beta_x are tied to their geometric mean (m*n)^-1/4
+ *           (Sec. 5.2 step 2); beta_w = b^-1/2.
+ * Outputs are host pointers.  US_ERR_SHAPE if a dimension is < 1 or mode is not 0/1.
+ */
+us_status us_linear_scales(long b, long m, long n, int mode, float* alpha, float* beta_x, float* beta_w);
+
+/*
+ * Scaled saturating cast to FP8 (Sec. 3.1 "Quantisation error"; App. J.2: FP8 training quantises the
+ * FP16 tensor to the nearest FP8 value, E4 for activations and weights, E5 for gradients).
+ *   dst[i] = nearest_fp8( fp32(src[i] * scale) ), clipped to +-max finite; NaN -> NaN code.
+ * src: n elements of src_dt (US_F16 or US_F32); dst: n bytes (US_E4M3 or US_E5M2).  The scale is
+ * applied in FP32 before the single rounding.  stats may be NULL; otherwise the four counters are
+ * incremented (device memory, caller clears).  n = 0 is a no-op.
+ */
+us_status us_cast_fp8(const void* src, us_dtype src_dt, void* dst, us_dtype dst_dt, size_t n,
+                      float scale, us_cast_stats* stats, void* stream);
+
+/*
+ * Forward of the scaled projection (Sec. 5.5):  Y[b,n] = alpha * X[b,m] W[m,n].
+ * Operand types (x_dt, w_dt): (F16, F16) or (E4M3, E4M3).  FP32 accumulation; y_dt = F16 or F32.
+ * alpha <= 0 selects m^-1/2.
+ * epi = US_EPI_GELU (y_dt must be F16) additionally computes, from the ROUNDED FP16 value of Y,
+ *   H = fp16( epi_scale * gelu(Y) ),  gelu(x) = x*Phi(x)   (Table A.2 "Activations"),
+ * stores H to aux16 (FP16 [b,n]) if aux16 != NULL and the E4M3 cast of that FP16 H (scale 1) to aux8
+ * ([b,n] bytes) if aux8 != NULL; at least one of them must be given.  epi_scale <= 0 selects the
+ * unit-scaling factor 1.7009.  Y itself is always written (the backward pass needs it).
+ * workspace is unused by the forward pass and may be NULL.
+ */
+us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, long n,
+                        us_dtype x_dt, us_dtype w_dt, us_dtype y_dt, float alpha,
+                        us_epilogue epi, float epi_scale, void* aux16, void* aux8,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Backward of the scaled projection (Sec. 5.5):
+ *   dX[b,m] = beta_x * G[b,n] W[m,n]^T      (skipped when dX == NULL)
+ *   dW[m,n] = beta_w * X[b,m]^T G[b,n]      (skipped when dW == NULL)
+ * No transposed copy of any operand is made.  Operand types: all F16, or x_dt = w_dt = E4M3 with
+ * g_dt = E5M2.  out_dt = F16 or F32 for both outputs.  beta_x <= 0 selects n^-1/2, beta_w <= 0
+ * selects b^-1/2.  X is only read for dW and W only for dX; the unused one may be NULL.
+ * epi = US_EPI_GELU_GRAD applies to dX only (out_dt must be F16): with Zpre[b,m] (FP16, the
+ * pre-activation saved by the forward pass),
+ *   dX = fp16( epi_scale * gelu'(Zpre) * fp16(beta_x * G W^T) ),  gelu'(z) = Phi(z) + z*phi(z),
+ * i.e. the scaled-GELU backward of Sec. 5.1 applied to the FP16-rounded matmul gradient; if aux8 !=
+ * NULL the E5M2 cast of the stored FP16 dX is written there.  epi_scale <= 0 selects 1.4811.
+ * dW is reduced over the b tokens in slices; when us_workspace_bytes(b, m, n) is non-zero the
+ * caller must pass a workspace of at least that many bytes (16-byte aligned, contents undefined
+ * on entry and exit).
+ */
+us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, void* dW,
+                        long b, long m, long n, us_dtype x_dt, us_dtype w_dt, us_dtype g_dt,
+                        us_dtype out_dt, float beta_x, float beta_w, us_epilogue epi, float epi_scale,
+                        const void* Zpre, void* aux8, void* workspace, size_t workspace_bytes,
+                        void* stream);
+
+/* Bytes of workspace us_linear_bwd needs for the dW of a [b,m] x [b,n] problem (0 if none). */
+size_t us_workspace_bytes(long b, long m, long n);
+
+/*
+ * Stand-alone unit-scaled GELU (Table A.2 "Activations"; backward by the f_grad rule of Sec. 5.1).
+ *   fwd: h[i]  = round( alpha_g * z[i] * Phi(z[i]) )
+ *   bwd: gz[i] = round( beta_g * (Phi(z[i]) + z[i]*phi(z[i])) * gh[i] )
+ * dt = US_F16 or US_F32 for all arrays of a call.  alpha_g / beta_g <= 0 select 1.7009 / 1.4811.
+ * In-place use (h == z, gz == gh) is allowed.
+ */
+us_status us_gelu_fwd(const void* z, void* h, size_t n, us_dtype dt, float alpha_g, void* stream);
+us_status us_gelu_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtype dt, float beta_g,
+                      void* stream);
+
+/*
+ * The FFN of Fig. 3 without its residual: Linear -> unit-scaled GELU -> Linear, as one call per
+ * direction, composed of the operations above with the scales of Table A.2 (alpha = fan_in^-1/2,
+ * beta_x = fan_out^-1/2, beta_w = tokens^-1/2, GELU 1.7009 / 1.4811).
+ *
+ * fp8 == 0: operands are the FP16 tensors.  fp8 != 0: X8, W1_8, W2_8 are E4M3 and G8 is E5M2 (made
+ * by us_cast_fp8), H8 / dZ8 are written by the fused epilogues.
+ *
+ * us_ffn_fwd:  Z[T,f] = fp16(d^-1/2 X W1);  H = fp16(1.7009 gelu(Z));  Y[T,d] = fp16(f^-1/2 H W2)
+ *   X [T,d], W1 [d,f], W2 [f,d]: F16 (fp8 == 0) or E4M3 (fp8 != 0)
+ *   Z [T,f] F16 out;  H [T,f] out: F16 when fp8 == 0, E4M3 codes when fp8 != 0;  Y [T,d] F16 out
+ * us_ffn_bwd:  dH = fp16(d^-1/2 G W2^T);  dZ = fp16(1.4811 gelu'(Z) dH);  dW2 = fp16(T^-1/2 H^T G);
+ *              dX = fp16(f^-1/2 dZ W1^T);  dW1 = fp16(T^-1/2 X^T dZ)
+ *   G [T,d]: F16 or E5M2;  dZ16 [T,f] F16 out;  dZ8 [T,f] E5M2 out (fp8 != 0 only, else ignored)
+ *   dX [T,d], dW1 [d,f], dW2 [f,d] F16 out
+ *   workspace: at least us_ffn_workspace_bytes(T, d, f) bytes.
+ */
+us_status us_ffn_fwd(const void* X, const void* W1, const void* W2, void* Z, void* H, void* Y,
+                     long T, long d, long f, int fp8, void* stream);
+us_status us_ffn_bwd(const void* X, const void* W1, const void* W2, const void* Z, const void* H,
+                     const void* G, void* dZ16, void* dZ8, void* dX, void* dW1, void* dW2,
+                     long T, long d, long f, int fp8, void* workspace, size_t workspace_bytes,
+                     void* stream);
+size_t us_ffn_workspace_bytes(long T, long d, long f);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* US_H_ */

@@ -1,0 +1,11 @@
+"""Unit-scaled linear / FFN forward and backward for AMD MI355X (gfx950).
+
+The work is done by hand-written HIP kernels behind a C ABI (``include/us.h``, built into
+``libus_mi355x.so``); this package is only the ctypes binding with the same names.  PyTorch is
+used by callers for device memory and streams; the binding takes raw device pointers.
+"""
+from .binding import (  # noqa: F401
+    E4M3, E5M2, F16, F32, EPI_GELU, EPI_GELU_GRAD, EPI_NONE, STATUS, UsError, cast_fp8, ffn_bwd, ffn_fwd,
+    ffn_workspace_bytes, gelu_bwd, gelu_fwd, lib, library_path, linear_bwd, linear_fwd, linear_scales,
+    status_string, workspace_bytes,
+)

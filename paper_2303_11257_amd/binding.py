@@ -1,0 +1,116 @@
+"""ctypes binding of the C ABI declared in ``include/us.h``.
+
+Argument marshalling only: every function takes raw device addresses (``tensor.data_ptr()``) and a
+HIP stream handle, forwards them unchanged and raises :class:`UsError` on a non-zero status.  There
+is no fallback: if the shared library has not been built, importing it fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+F32, F16, E4M3, E5M2 = 0, 1, 2, 3
+EPI_NONE, EPI_GELU, EPI_GELU_GRAD = 0, 1, 2
+STATUS = {0: "US_OK", 1: "US_ERR_NULL", 2: "US_ERR_SHAPE", 3: "US_ERR_ALIGN", 4: "US_ERR_DTYPE",
+          5: "US_ERR_WORKSPACE", 6: "US_ERR_LAUNCH"}
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libus_mi355x.so")
+_lib = None
+
+
+class UsError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {STATUS.get(status, status)} ({status_string(status)})")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libus_mi355x.so (built by ``paper_2303_11257_amd.build``); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(f"{_LIB_PATH} not built: run `python -m paper_2303_11257_amd.build`")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i, l, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_float, ctypes.c_size_t
+    fp = ctypes.POINTER(ctypes.c_float)
+    L.us_status_string.argtypes = [i]
+    L.us_status_string.restype = ctypes.c_char_p
+    L.us_linear_scales.argtypes = [l, l, l, i, fp, fp, fp]
+    L.us_cast_fp8.argtypes = [vp, i, vp, i, sz, f, vp, vp]
+    L.us_linear_fwd.argtypes = [vp, vp, vp, l, l, l, i, i, i, f, i, f, vp, vp, vp, sz, vp]
+    L.us_linear_bwd.argtypes = [vp, vp, vp, vp, vp, l, l, l, i, i, i, i, f, f, i, f, vp, vp, vp, sz, vp]
+    L.us_workspace_bytes.argtypes = [l, l, l]
+    L.us_workspace_bytes.restype = sz
+    L.us_gelu_fwd.argtypes = [vp, vp, sz, i, f, vp]
+    L.us_gelu_bwd.argtypes = [vp, vp, vp, sz, i, f, vp]
+    L.us_ffn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, l, l, l, i, vp]
+    L.us_ffn_bwd.argtypes = [vp] * 11 + [l, l, l, i, vp, sz, vp]
+    L.us_ffn_workspace_bytes.argtypes = [l, l, l]
+    L.us_ffn_workspace_bytes.restype = sz
+    for name in ("us_linear_scales", "us_cast_fp8", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd",
+                 "us_ffn_fwd", "us_ffn_bwd"):
+        getattr(L, name).restype = i
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().us_status_string(status).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise UsError(status, where)
+
+
+def linear_scales(b: int, m: int, n: int, mode: int = 0):
+    a, bx, bw = ctypes.c_float(), ctypes.c_float(), ctypes.c_float()
+    _check(lib().us_linear_scales(b, m, n, mode, ctypes.byref(a), ctypes.byref(bx), ctypes.byref(bw)), "us_linear_scales")
+    return a.value, bx.value, bw.value
+
+
+def cast_fp8(src, src_dt, dst, dst_dt, n, scale=1.0, stats=None, stream=None):
+    _check(lib().us_cast_fp8(src, src_dt, dst, dst_dt, n, scale, stats, stream), "us_cast_fp8")
+
+
+def linear_fwd(X, W, Y, b, m, n, x_dt, w_dt, y_dt=F16, alpha=0.0, epi=EPI_NONE, epi_scale=0.0, aux16=None, aux8=None,
+               workspace=None, workspace_bytes=0, stream=None):
+    _check(lib().us_linear_fwd(X, W, Y, b, m, n, x_dt, w_dt, y_dt, alpha, epi, epi_scale, aux16, aux8, workspace,
+                               workspace_bytes, stream), "us_linear_fwd")
+
+
+def linear_bwd(X, W, G, dX, dW, b, m, n, x_dt, w_dt, g_dt, out_dt=F16, beta_x=0.0, beta_w=0.0, epi=EPI_NONE,
+               epi_scale=0.0, Zpre=None, aux8=None, workspace=None, workspace_bytes=0, stream=None):
+    _check(lib().us_linear_bwd(X, W, G, dX, dW, b, m, n, x_dt, w_dt, g_dt, out_dt, beta_x, beta_w, epi, epi_scale, Zpre,
+                               aux8, workspace, workspace_bytes, stream), "us_linear_bwd")
+
+
+def workspace_bytes(b: int, m: int, n: int) -> int:
+    return int(lib().us_workspace_bytes(b, m, n))
+
+
+def gelu_fwd(z, h, n, dt=F16, alpha_g=0.0, stream=None):
+    _check(lib().us_gelu_fwd(z, h, n, dt, alpha_g, stream), "us_gelu_fwd")
+
+
+def gelu_bwd(z, gh, gz, n, dt=F16, beta_g=0.0, stream=None):
+    _check(lib().us_gelu_bwd(z, gh, gz, n, dt, beta_g, stream), "us_gelu_bwd")
+
+
+def ffn_fwd(X, W1, W2, Z, H, Y, T, d, f, fp8, stream=None):
+    _check(lib().us_ffn_fwd(X, W1, W2, Z, H, Y, T, d, f, int(fp8), stream), "us_ffn_fwd")
+
+
+def ffn_bwd(X, W1, W2, Z, H, G, dZ16, dZ8, dX, dW1, dW2, T, d, f, fp8, workspace=None, workspace_bytes=0, stream=None):
+    _check(lib().us_ffn_bwd(X, W1, W2, Z, H, G, dZ16, dZ8, dX, dW1, dW2, T, d, f, int(fp8), workspace, workspace_bytes,
+                            stream), "us_ffn_bwd")
+
+
+def ffn_workspace_bytes(T: int, d: int, f: int) -> int:
+    return int(lib().us_ffn_workspace_bytes(T, d, f))

@@ -1,0 +1,199 @@
+// C-ABI entry points: argument checks on the host, then launches.  Nothing here allocates memory
+// or synchronises with the device.
+#include <math.h>
+#include <stdint.h>
+
+#include "us_device.h"
+#include "us_launch.h"
+
+using namespace us;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool mult16(long v) { return (v & 15) == 0; }
+inline bool is_fp8(us_dtype d) { return d == US_E4M3 || d == US_E5M2; }
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+inline us_status from_hip(hipError_t e) { return e == hipSuccess ? US_OK : US_ERR_LAUNCH; }
+
+}  // namespace
+
+extern "C" {
+
+const char* us_status_string(us_status s) {
+  switch (s) {
+    case US_OK: return "ok";
+    case US_ERR_NULL: return "a required pointer is NULL";
+    case US_ERR_SHAPE: return "bad shape: dimensions must be non-negative multiples of 16";
+    case US_ERR_ALIGN: return "pointer not 16-byte aligned";
+    case US_ERR_DTYPE: return "unsupported storage-type combination";
+    case US_ERR_WORKSPACE: return "workspace missing or too small";
+    case US_ERR_LAUNCH: return "HIP launch failed";
+  }
+  return "unknown status";
+}
+
+us_status us_linear_scales(long b, long m, long n, int mode, float* alpha, float* beta_x, float* beta_w) {
+  if (!alpha || !beta_x || !beta_w) return US_ERR_NULL;
+  if (b < 1 || m < 1 || n < 1 || (mode != 0 && mode != 1)) return US_ERR_SHAPE;
+  double a = 1.0 / sqrt((double)m), bx = 1.0 / sqrt((double)n), bw = 1.0 / sqrt((double)b);
+  if (mode == 1) a = bx = sqrt(a * bx);
+  *alpha = (float)a;
+  *beta_x = (float)bx;
+  *beta_w = (float)bw;
+  return US_OK;
+}
+
+us_status us_cast_fp8(const void* src, us_dtype src_dt, void* dst, us_dtype dst_dt, size_t n, float scale,
+                      us_cast_stats* stats, void* stream) {
+  if ((src_dt != US_F16 && src_dt != US_F32) || !is_fp8(dst_dt)) return US_ERR_DTYPE;
+  if (n == 0) return US_OK;
+  if (!src || !dst) return US_ERR_NULL;
+  if (!aligned16(src) || !aligned16(dst) || (reinterpret_cast<uintptr_t>(stats) & 7u)) return US_ERR_ALIGN;
+  return from_hip(launch_cast(src, src_dt, dst, dst_dt, n, scale, stats, as_stream(stream)));
+}
+
+us_status us_gelu_fwd(const void* z, void* h, size_t n, us_dtype dt, float alpha_g, void* stream) {
+  if (dt != US_F16 && dt != US_F32) return US_ERR_DTYPE;
+  if (n == 0) return US_OK;
+  if (!z || !h) return US_ERR_NULL;
+  if (!aligned16(z) || !aligned16(h)) return US_ERR_ALIGN;
+  if (!(alpha_g > 0.0f)) alpha_g = kGeluAlpha;
+  return from_hip(launch_gelu_fwd(z, h, n, dt, alpha_g, as_stream(stream)));
+}
+
+us_status us_gelu_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtype dt, float beta_g, void* stream) {
+  if (dt != US_F16 && dt != US_F32) return US_ERR_DTYPE;
+  if (n == 0) return US_OK;
+  if (!z || !gh || !gz) return US_ERR_NULL;
+  if (!aligned16(z) || !aligned16(gh) || !aligned16(gz)) return US_ERR_ALIGN;
+  if (!(beta_g > 0.0f)) beta_g = kGeluBeta;
+  return from_hip(launch_gelu_bwd(z, gh, gz, n, dt, beta_g, as_stream(stream)));
+}
+
+size_t us_workspace_bytes(long b, long m, long n) {
+  if (b < 1 || m < 1 || n < 1) return 0;
+  return gemm_workspace_bytes(m, n, b);
+}
+
+us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, long n, us_dtype x_dt, us_dtype w_dt,
+                        us_dtype y_dt, float alpha, us_epilogue epi, float epi_scale, void* aux16, void* aux8,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  const bool f16 = (x_dt == US_F16 && w_dt == US_F16);
+  const bool fp8 = (x_dt == US_E4M3 && w_dt == US_E4M3);
+  if (!f16 && !fp8) return US_ERR_DTYPE;
+  if (y_dt != US_F16 && y_dt != US_F32) return US_ERR_DTYPE;
+  if (epi != US_EPI_NONE && epi != US_EPI_GELU) return US_ERR_DTYPE;
+  if (epi == US_EPI_GELU && y_dt != US_F16) return US_ERR_DTYPE;
+  if (b < 0 || m < 0 || n < 0 || !mult16(b) || !mult16(m) || !mult16(n)) return US_ERR_SHAPE;
+  if (b == 0 || n == 0) return US_OK;
+  if (!Y || (m > 0 && (!X || !W))) return US_ERR_NULL;
+  if (epi == US_EPI_GELU && !aux16 && !aux8) return US_ERR_NULL;
+  if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || !aligned16(aux16) || !aligned16(aux8)) return US_ERR_ALIGN;
+  GemmProblem p{};
+  p.A = X; p.B = W; p.C = Y;
+  p.M = b; p.N = n; p.K = m;
+  p.lda = m; p.ldb = n; p.ldc = n;
+  p.a_kc = true; p.b_kc = false;
+  p.a_dt = x_dt; p.b_dt = w_dt; p.c_dt = y_dt;
+  p.scale = (alpha > 0.0f) ? alpha : (float)(1.0 / sqrt((double)(m > 0 ? m : 1)));
+  p.epi = epi;
+  p.epi_scale = (epi_scale > 0.0f) ? epi_scale : kGeluAlpha;
+  p.aux16 = (epi == US_EPI_GELU) ? aux16 : nullptr;
+  p.aux8 = (epi == US_EPI_GELU) ? aux8 : nullptr;
+  return from_hip(launch_gemm(p, as_stream(stream)));
+}
+
+us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, void* dW, long b, long m, long n,
+                        us_dtype x_dt, us_dtype w_dt, us_dtype g_dt, us_dtype out_dt, float beta_x, float beta_w,
+                        us_epilogue epi, float epi_scale, const void* Zpre, void* aux8, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  const bool f16 = (x_dt == US_F16 && w_dt == US_F16 && g_dt == US_F16);
+  const bool fp8 = (x_dt == US_E4M3 && w_dt == US_E4M3 && g_dt == US_E5M2);
+  if (!f16 && !fp8) return US_ERR_DTYPE;
+  if (out_dt != US_F16 && out_dt != US_F32) return US_ERR_DTYPE;
+  if (epi != US_EPI_NONE && epi != US_EPI_GELU_GRAD) return US_ERR_DTYPE;
+  if (epi == US_EPI_GELU_GRAD && out_dt != US_F16) return US_ERR_DTYPE;
+  if (b < 0 || m < 0 || n < 0 || !mult16(b) || !mult16(m) || !mult16(n)) return US_ERR_SHAPE;
+  const bool do_dx = dX && b > 0 && m > 0;
+  const bool do_dw = dW && m > 0 && n > 0;
+  if (!do_dx && !do_dw) return US_OK;
+  if (do_dx && n > 0 && (!G || !W)) return US_ERR_NULL;
+  if (do_dw && b > 0 && (!G || !X)) return US_ERR_NULL;
+  if (do_dx && epi == US_EPI_GELU_GRAD && !Zpre) return US_ERR_NULL;
+  if (!aligned16(X) || !aligned16(W) || !aligned16(G) || !aligned16(dX) || !aligned16(dW) || !aligned16(Zpre) ||
+      !aligned16(aux8) || !aligned16(workspace))
+    return US_ERR_ALIGN;
+  if (do_dw) {
+    const size_t need = gemm_workspace_bytes(m, n, b);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return US_ERR_WORKSPACE;
+  }
+  hipStream_t st = as_stream(stream);
+  if (do_dx) {
+    GemmProblem p{};
+    p.A = G; p.B = W; p.C = dX;
+    p.M = b; p.N = m; p.K = n;
+    p.lda = n; p.ldb = n; p.ldc = m;
+    p.a_kc = true; p.b_kc = true;
+    p.a_dt = g_dt; p.b_dt = w_dt; p.c_dt = out_dt;
+    p.scale = (beta_x > 0.0f) ? beta_x : (float)(1.0 / sqrt((double)(n > 0 ? n : 1)));
+    p.epi = epi;
+    p.epi_scale = (epi_scale > 0.0f) ? epi_scale : kGeluBeta;
+    p.Zpre = (epi == US_EPI_GELU_GRAD) ? Zpre : nullptr;
+    p.aux8 = (epi == US_EPI_GELU_GRAD) ? aux8 : nullptr;
+    hipError_t e = launch_gemm(p, st);
+    if (e != hipSuccess) return US_ERR_LAUNCH;
+  }
+  if (do_dw) {
+    GemmProblem p{};
+    p.A = X; p.B = G; p.C = dW;
+    p.M = m; p.N = n; p.K = b;
+    p.lda = m; p.ldb = n; p.ldc = n;
+    p.a_kc = false; p.b_kc = false;
+    p.a_dt = x_dt; p.b_dt = g_dt; p.c_dt = out_dt;
+    p.scale = (beta_w > 0.0f) ? beta_w : (float)(1.0 / sqrt((double)(b > 0 ? b : 1)));
+    p.epi = US_EPI_NONE;
+    p.workspace = gemm_workspace_bytes(m, n, b) > 0 ? workspace : nullptr;
+    p.workspace_bytes = workspace_bytes;
+    hipError_t e = launch_gemm(p, st);
+    if (e != hipSuccess) return US_ERR_LAUNCH;
+  }
+  return US_OK;
+}
+
+size_t us_ffn_workspace_bytes(long T, long d, long f) {
+  const size_t a = us_workspace_bytes(T, f, d);  // dW2: H[T,f]^T G[T,d]
+  const size_t b = us_workspace_bytes(T, d, f);  // dW1: X[T,d]^T dZ[T,f]
+  return a > b ? a : b;
+}
+
+us_status us_ffn_fwd(const void* X, const void* W1, const void* W2, void* Z, void* H, void* Y, long T, long d, long f,
+                     int fp8, void* stream) {
+  const us_dtype op = fp8 ? US_E4M3 : US_F16;
+  // layer 1 with the GELU fused: Z = d^-1/2 X W1 (FP16), H = 1.7009 gelu(Z) as FP16 or as E4M3 codes
+  us_status s = us_linear_fwd(X, W1, Z, T, d, f, op, op, US_F16, 0.0f, US_EPI_GELU, 0.0f, fp8 ? nullptr : H,
+                              fp8 ? H : nullptr, nullptr, 0, stream);
+  if (s != US_OK) return s;
+  // layer 2: Y = f^-1/2 H W2
+  return us_linear_fwd(H, W2, Y, T, f, d, op, op, US_F16, 0.0f, US_EPI_NONE, 0.0f, nullptr, nullptr, nullptr, 0, stream);
+}
+
+us_status us_ffn_bwd(const void* X, const void* W1, const void* W2, const void* Z, const void* H, const void* G,
+                     void* dZ16, void* dZ8, void* dX, void* dW1, void* dW2, long T, long d, long f, int fp8,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+  const us_dtype op = fp8 ? US_E4M3 : US_F16;
+  const us_dtype gr = fp8 ? US_E5M2 : US_F16;
+  if (!dZ16 || (fp8 && !dZ8)) return US_ERR_NULL;
+  // layer 2 backward: dH = d^-1/2 G W2^T, fused with GELU' -> dZ (FP16 + E5M2 copy); dW2 = T^-1/2 H^T G
+  us_status s = us_linear_bwd(H, W2, G, dZ16, dW2, T, f, d, op, op, gr, US_F16, 0.0f, 0.0f, US_EPI_GELU_GRAD, 0.0f, Z,
+                              fp8 ? dZ8 : nullptr, workspace, workspace_bytes, stream);
+  if (s != US_OK) return s;
+  // layer 1 backward: dX = f^-1/2 dZ W1^T; dW1 = T^-1/2 X^T dZ
+  const void* dZ = fp8 ? dZ8 : dZ16;
+  return us_linear_bwd(X, W1, dZ, dX, dW1, T, d, f, op, op, gr, US_F16, 0.0f, 0.0f, US_EPI_NONE, 0.0f, nullptr, nullptr,
+                       workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"

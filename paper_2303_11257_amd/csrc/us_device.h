@@ -1,0 +1,90 @@
+// Device-side helpers shared by the gfx950 kernels: vector types, FP8/FP16 conversion, GELU math.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/us.h"
+
+namespace us {
+
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef short v4s __attribute__((ext_vector_type(4)));
+
+// Unit-scaling factors of gelu(x) = x*Phi(x) for x ~ N(0,1) (Table A.2 prints 1.701 / 1.481):
+// alpha = 1/std(gelu), beta = 1/rms(gelu'), closed forms
+//   E[gelu^2] = 1/3 + 1/(2 pi sqrt3), E[gelu] = 1/(2 sqrt pi), E[gelu'^2] = 1/3 + 2/(3 pi sqrt3).
+constexpr float kGeluAlpha = 1.7009261846542358f;
+constexpr float kGeluBeta = 1.481114387512207f;
+
+// ---- FP32 -> FP8 (E4M3: max 448, one NaN, no inf; E5M2: max 57344) -------------------------------
+// The hardware converter rounds to nearest-even and handles subnormals; it turns overflow into
+// NaN/inf, so the value is first clipped to the finite range (that also maps +-inf to +-max).
+// v_med3 drops a NaN operand, so NaN inputs get their NaN code put back afterwards.
+// Returns code(a) | code(b) << 8.
+template <int FMT>
+__device__ __forceinline__ uint32_t cvt_pk_fp8(float a, float b) {
+  constexpr float kMax = (FMT == US_E4M3) ? 448.0f : 57344.0f;
+  float ca = __builtin_amdgcn_fmed3f(a, -kMax, kMax);
+  float cb = __builtin_amdgcn_fmed3f(b, -kMax, kMax);
+  uint32_t r = (FMT == US_E4M3) ? (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(ca, cb, 0, false)
+                                : (uint32_t)__builtin_amdgcn_cvt_pk_bf8_f32(ca, cb, 0, false);
+  r &= 0xffffu;
+  if (a != a) r |= 0x007fu;
+  if (b != b) r |= 0x7f00u;
+  return r;
+}
+
+template <int FMT>
+__device__ __forceinline__ uint32_t cvt4_fp8(float a, float b, float c, float d) {
+  return cvt_pk_fp8<FMT>(a, b) | (cvt_pk_fp8<FMT>(c, d) << 16);
+}
+
+// ---- Gaussian tail for GELU -------------------------------------------------------------------------
+// Q(x) = P(N(0,1) > x) for x >= 0 is evaluated as exp(-x^2/2) * t*(c0 + c1 t + ... + c5 t^5) with
+// t = 1/(1 + p x): a fit of the scaled complementary error function erfcx(x/sqrt2)/2 whose relative
+// error stays below 4e-6 on [0, 14], so Phi keeps relative accuracy in the negative tail too
+// (fitted offline by reweighted least squares against a double-precision erfcx).
+struct GaussTerms {
+  float Phi;  // standard normal CDF at z
+  float pdf;  // standard normal density at z
+};
+
+__device__ __forceinline__ GaussTerms gauss_terms(float z) {
+  constexpr float p = 0.308158117f;
+  constexpr float c0 = 0.12318376f, c1 = 0.11897348f, c2 = 0.136421f, c3 = 0.00767712f,
+                  c4 = 0.18914684f, c5 = -0.07540414f;
+  float az = __builtin_fabsf(z);
+  float t = __builtin_amdgcn_rcpf(__builtin_fmaf(p, az, 1.0f));
+  float e = __builtin_amdgcn_exp2f(-0.7213475204444817f * (z * z));  // exp(-z^2/2) = 2^(-z^2 * log2(e)/2)
+  float poly = __builtin_fmaf(c5, t, c4);
+  poly = __builtin_fmaf(poly, t, c3);
+  poly = __builtin_fmaf(poly, t, c2);
+  poly = __builtin_fmaf(poly, t, c1);
+  poly = __builtin_fmaf(poly, t, c0);
+  float q = (poly * t) * e;
+  GaussTerms g;
+  g.Phi = (z < 0.0f) ? q : 1.0f - q;
+  g.pdf = 0.3989422804014327f * e;
+  return g;
+}
+
+// h = alpha_g * z * Phi(z)
+__device__ __forceinline__ float gelu_scaled(float z, float alpha_g) {
+  GaussTerms g = gauss_terms(z);
+  return alpha_g * (z * g.Phi);
+}
+// d/dz gelu(z) * beta_g * gh
+__device__ __forceinline__ float gelu_grad_scaled(float z, float gh, float beta_g) {
+  GaussTerms g = gauss_terms(z);
+  return (beta_g * __builtin_fmaf(z, g.pdf, g.Phi)) * gh;
+}
+
+}  // namespace us

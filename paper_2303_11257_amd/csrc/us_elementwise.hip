@@ -1,0 +1,169 @@
+// Element-wise kernels of the unit-scaled FFN path for gfx950: the scaled saturating cast to FP8
+// and the stand-alone unit-scaled GELU forward / backward.  All three are bound by HBM traffic:
+// every thread moves 128-bit vectors and the arithmetic is kept to a few VALU operations per element.
+#include "us_device.h"
+#include "us_launch.h"
+
+namespace us {
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ void load16(const _Float16* src, size_t i, float (&x)[16]) {
+  v8h a = *reinterpret_cast<const v8h*>(src + i);
+  v8h b = *reinterpret_cast<const v8h*>(src + i + 8);
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    x[k] = (float)a[k];
+    x[8 + k] = (float)b[k];
+  }
+}
+__device__ __forceinline__ void load16(const float* src, size_t i, float (&x)[16]) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    v4f a = *reinterpret_cast<const v4f*>(src + i + 4 * q);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) x[4 * q + k] = a[k];
+  }
+}
+
+struct Counts {
+  uint32_t sat = 0, flush0 = 0, subn = 0, nan = 0;
+};
+
+template <int FMT>
+__device__ __forceinline__ void count_one(float p, uint32_t code, Counts& c) {
+  constexpr float kMax = (FMT == US_E4M3) ? 448.0f : 57344.0f;
+  constexpr uint32_t kFirstNormal = (FMT == US_E4M3) ? 0x08u : 0x04u;
+  uint32_t mag = code & 0x7fu;
+  c.sat += (__builtin_fabsf(p) > kMax) ? 1u : 0u;
+  c.nan += (p != p) ? 1u : 0u;
+  c.flush0 += (p != 0.0f && mag == 0u) ? 1u : 0u;       // NaN has a non-zero code, so it is not counted here
+  c.subn += (mag != 0u && mag < kFirstNormal) ? 1u : 0u;
+}
+
+// dst[i] = fp8( fp32(src[i] * scale) ): 16 elements per thread per step (two or four 128-bit loads,
+// one 128-bit store), grid-stride; the last n % 16 elements are handled one per thread.
+template <typename SrcT, int FMT, bool STATS>
+__global__ void __launch_bounds__(kThreads) cast_kernel(const SrcT* __restrict__ src, uint8_t* __restrict__ dst,
+                                                        size_t n, float scale, us_cast_stats* stats) {
+  const size_t nvec = n / 16;
+  const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  const size_t nthr = (size_t)gridDim.x * kThreads;
+  Counts c;
+  for (size_t v = tid; v < nvec; v += nthr) {
+    float x[16];
+    load16(src, v * 16, x);
+    v4i out;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float p0 = x[4 * q] * scale, p1 = x[4 * q + 1] * scale, p2 = x[4 * q + 2] * scale, p3 = x[4 * q + 3] * scale;
+      uint32_t w = cvt4_fp8<FMT>(p0, p1, p2, p3);
+      out[q] = (int)w;
+      if (STATS) {
+        count_one<FMT>(p0, w, c);
+        count_one<FMT>(p1, w >> 8, c);
+        count_one<FMT>(p2, w >> 16, c);
+        count_one<FMT>(p3, w >> 24, c);
+      }
+    }
+    *reinterpret_cast<v4i*>(dst + v * 16) = out;
+  }
+  const size_t tail0 = nvec * 16;
+  if (tid < n - tail0) {
+    float p = (float)src[tail0 + tid] * scale;
+    uint32_t w = cvt_pk_fp8<FMT>(p, 0.0f) & 0xffu;
+    dst[tail0 + tid] = (uint8_t)w;
+    if (STATS) count_one<FMT>(p, w, c);
+  }
+  if (STATS) {
+    __shared__ uint32_t s[4];
+    if (threadIdx.x < 4) s[threadIdx.x] = 0;
+    __syncthreads();
+    if (c.sat) atomicAdd(&s[0], c.sat);
+    if (c.flush0) atomicAdd(&s[1], c.flush0);
+    if (c.subn) atomicAdd(&s[2], c.subn);
+    if (c.nan) atomicAdd(&s[3], c.nan);
+    __syncthreads();
+    if (threadIdx.x < 4 && s[threadIdx.x]) {
+      unsigned long long* g = reinterpret_cast<unsigned long long*>(stats);
+      atomicAdd(&g[threadIdx.x], (unsigned long long)s[threadIdx.x]);
+    }
+  }
+}
+
+// h = fp16/fp32( alpha_g * z * Phi(z) ), eight (FP16) or four (FP32) elements per 128-bit access.
+template <typename T, bool BWD>
+__global__ void __launch_bounds__(kThreads) gelu_kernel(const T* __restrict__ z, const T* gh, T* out, size_t n,
+                                                        float s) {
+  constexpr int V = 16 / sizeof(T);
+  typedef T vec_t __attribute__((ext_vector_type(V)));
+  const size_t nvec = n / V;
+  const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  const size_t nthr = (size_t)gridDim.x * kThreads;
+  for (size_t v = tid; v < nvec; v += nthr) {
+    vec_t zv = *reinterpret_cast<const vec_t*>(z + v * V);
+    vec_t gv;
+    if (BWD) gv = *reinterpret_cast<const vec_t*>(gh + v * V);
+    vec_t o;
+#pragma unroll
+    for (int k = 0; k < V; ++k)
+      o[k] = (T)(BWD ? gelu_grad_scaled((float)zv[k], (float)gv[k], s) : gelu_scaled((float)zv[k], s));
+    *reinterpret_cast<vec_t*>(out + v * V) = o;
+  }
+  const size_t tail0 = nvec * V;
+  if (tid < n - tail0) {
+    float zi = (float)z[tail0 + tid];
+    out[tail0 + tid] = (T)(BWD ? gelu_grad_scaled(zi, (float)gh[tail0 + tid], s) : gelu_scaled(zi, s));
+  }
+}
+
+inline int grid_for(size_t nvec) {
+  // enough blocks to fill 256 CUs several times over, capped so the grid-stride loop amortises launch cost
+  size_t blocks = (nvec + kThreads - 1) / kThreads;
+  if (blocks < 1) blocks = 1;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  return (int)blocks;
+}
+
+template <typename SrcT, int FMT>
+hipError_t cast_dispatch(const void* src, void* dst, size_t n, float scale, us_cast_stats* stats, hipStream_t st) {
+  int grid = grid_for(n / 16);
+  if (stats)
+    cast_kernel<SrcT, FMT, true><<<grid, kThreads, 0, st>>>((const SrcT*)src, (uint8_t*)dst, n, scale, stats);
+  else
+    cast_kernel<SrcT, FMT, false><<<grid, kThreads, 0, st>>>((const SrcT*)src, (uint8_t*)dst, n, scale, nullptr);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_cast(const void* src, us_dtype src_dt, void* dst, us_dtype dst_dt, size_t n, float scale,
+                       us_cast_stats* stats, hipStream_t st) {
+  if (src_dt == US_F16)
+    return dst_dt == US_E4M3 ? cast_dispatch<_Float16, US_E4M3>(src, dst, n, scale, stats, st)
+                             : cast_dispatch<_Float16, US_E5M2>(src, dst, n, scale, stats, st);
+  return dst_dt == US_E4M3 ? cast_dispatch<float, US_E4M3>(src, dst, n, scale, stats, st)
+                           : cast_dispatch<float, US_E5M2>(src, dst, n, scale, stats, st);
+}
+
+hipError_t launch_gelu_fwd(const void* z, void* h, size_t n, us_dtype dt, float alpha_g, hipStream_t st) {
+  if (dt == US_F16) {
+    gelu_kernel<_Float16, false><<<grid_for(n / 8), kThreads, 0, st>>>((const _Float16*)z, nullptr, (_Float16*)h, n, alpha_g);
+  } else {
+    gelu_kernel<float, false><<<grid_for(n / 4), kThreads, 0, st>>>((const float*)z, nullptr, (float*)h, n, alpha_g);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_gelu_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtype dt, float beta_g,
+                           hipStream_t st) {
+  if (dt == US_F16) {
+    gelu_kernel<_Float16, true><<<grid_for(n / 8), kThreads, 0, st>>>((const _Float16*)z, (const _Float16*)gh, (_Float16*)gz, n, beta_g);
+  } else {
+    gelu_kernel<float, true><<<grid_for(n / 4), kThreads, 0, st>>>((const float*)z, (const float*)gh, (float*)gz, n, beta_g);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace us

@@ -1,0 +1,57 @@
+// Routing of a GEMM problem to its kernel family, and the split-K policy of the grad_W reduction.
+#include "us_gemm_dispatch.h"
+
+namespace us {
+
+// out[m][n] = round( scale * sum_s partial[s][m][n] ), slices added in order (deterministic).
+__global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restrict__ partial, void* out, long total,
+                                                            int splits, float scale, int out_is_f32) {
+  const long i4 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i4 >= total) return;
+  v4f s = *reinterpret_cast<const v4f*>(partial + i4);
+  for (int k = 1; k < splits; ++k) s += *reinterpret_cast<const v4f*>(partial + (size_t)k * total + i4);
+  s *= scale;
+  if (out_is_f32) {
+    *reinterpret_cast<v4f*>((float*)out + i4) = s;
+  } else {
+    v4h o = {(_Float16)s.x, (_Float16)s.y, (_Float16)s.z, (_Float16)s.w};
+    *reinterpret_cast<v4h*>((_Float16*)out + i4) = o;
+  }
+}
+
+hipError_t launch_splitk_reduce(const float* partial, void* out, long total, int splits, float scale, bool out_is_f32,
+                                hipStream_t st) {
+  splitk_reduce_kernel<<<(unsigned)((total / 4 + 255) / 256), 256, 0, st>>>(partial, out, total, splits, scale,
+                                                                          out_is_f32 ? 1 : 0);
+  return hipGetLastError();
+}
+
+// grad_W has a small output (fan_in x fan_out) and a long reduction (tokens): when its 256x256
+// tiles cannot occupy the 256 CUs, the token range is cut into slices of whole 128-token stages.
+int gemm_splits(long M, long N, long K) {
+  const long tiles = ((M + 255) / 256) * ((N + 255) / 256);
+  if (tiles >= 192 || K < 1024) return 1;
+  long s = 256 / tiles;
+  const long max_by_k = K / 512;          // at least four stages per slice
+  if (s > max_by_k) s = max_by_k;
+  if (s > 16) s = 16;
+  if (s < 1) s = 1;
+  const long unit = 128;
+  const long k_per_split = ((K + s - 1) / s + unit - 1) / unit * unit;
+  return (int)((K + k_per_split - 1) / k_per_split);
+}
+
+size_t gemm_workspace_bytes(long M, long N, long K) {
+  const int s = gemm_splits(M, N, K);
+  return s <= 1 ? 0 : (size_t)s * (size_t)M * (size_t)N * sizeof(float);
+}
+
+hipError_t launch_gemm(const GemmProblem& p, hipStream_t st) {
+  const bool fp8 = (p.a_dt != US_F16);
+  if (p.a_kc && !p.b_kc) return fp8 ? gemm_nn_fp8(p, st) : gemm_nn_f16(p, st);
+  if (p.a_kc && p.b_kc) return fp8 ? gemm_nt_fp8(p, st) : gemm_nt_f16(p, st);
+  if (!p.a_kc && !p.b_kc) return fp8 ? gemm_tn_fp8(p, st) : gemm_tn_f16(p, st);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace us

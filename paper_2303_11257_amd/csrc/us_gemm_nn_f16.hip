@@ -1,0 +1,11 @@
+// GEMM family: forward product Y = X W: activations K-contiguous, weights K-strided.
+#include "us_gemm_dispatch.h"
+
+namespace us {
+
+hipError_t gemm_nn_f16(const GemmProblem& p, hipStream_t st) {
+  if (p.epi == US_EPI_GELU) return launch_sized<false, 0, 0, true, false, EPI_GELU>(p, 1, p.K, st);
+  return launch_sized<false, 0, 0, true, false, EPI_STORE>(p, 1, p.K, st);
+}
+
+}  // namespace us

@@ -1,0 +1,11 @@
+// GEMM family: grad_X product dX = G W^T: both operands K-contiguous.
+#include "us_gemm_dispatch.h"
+
+namespace us {
+
+hipError_t gemm_nt_fp8(const GemmProblem& p, hipStream_t st) {
+  if (p.epi == US_EPI_GELU_GRAD) return launch_sized<true, 1, 0, true, true, EPI_GELU_GRAD>(p, 1, p.K, st);
+  return launch_sized<true, 1, 0, true, true, EPI_STORE>(p, 1, p.K, st);
+}
+
+}  // namespace us

@@ -1,0 +1,49 @@
+// Host-side launch functions implemented by the kernel translation units.  Arguments are already
+// validated by the C-ABI layer; every function only enqueues work on `stream`.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+
+#include "../../include/us.h"
+
+namespace us {
+
+hipError_t launch_cast(const void* src, us_dtype src_dt, void* dst, us_dtype dst_dt, size_t n, float scale,
+                       us_cast_stats* stats, hipStream_t stream);
+hipError_t launch_gelu_fwd(const void* z, void* h, size_t n, us_dtype dt, float alpha_g, hipStream_t stream);
+hipError_t launch_gelu_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtype dt, float beta_g,
+                           hipStream_t stream);
+
+// One GEMM problem  C[M,N] = epilogue( scale * sum_k A(m,k) B(n,k) ).
+//   a_kc / b_kc: operand is K-contiguous (element (r,k) at base[r*ld + k]) or K-strided
+//   (element (r,k) at base[k*ld + r]).  The three layer-level products map to
+//     forward  Y  = X W      : A = X (K-contig),  B = W (K-strided)
+//     grad_X   dX = G W^T    : A = G (K-contig),  B = W (K-contig)
+//     grad_W   dW = X^T G    : A = X (K-strided), B = G (K-strided)
+struct GemmProblem {
+  const void* A;
+  const void* B;
+  void* C;
+  long M, N, K;
+  long lda, ldb, ldc;      // in elements
+  bool a_kc, b_kc;
+  us_dtype a_dt, b_dt;     // F16/F16, or two FP8 types
+  us_dtype c_dt;           // F16 or F32
+  float scale;
+  us_epilogue epi;
+  float epi_scale;
+  const void* Zpre;        // GELU_GRAD: FP16 [M,N], leading dimension ldc
+  void* aux16;             // GELU: FP16 [M,N] or NULL
+  void* aux8;              // GELU: E4M3 [M,N]; GELU_GRAD: E5M2 [M,N]; or NULL
+  void* workspace;         // split-K partial sums (FP32), or NULL
+  size_t workspace_bytes;
+};
+
+// Number of K slices the dW reduction is cut into, and the scratch it needs (0 when 1 slice).
+int gemm_splits(long M, long N, long K);
+size_t gemm_workspace_bytes(long M, long N, long K);
+
+hipError_t launch_gemm(const GemmProblem& p, hipStream_t stream);
+
+}  // namespace us

@@ -1,0 +1,74 @@
+"""The C-ABI library loads and exports every entry point declared in include/us.h; host-side
+argument checks answer before anything is launched (no GPU needed for any of this)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2303_11257_amd as us
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "us.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(us_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    assert {"us_cast_fp8", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd", "us_linear_scales",
+            "us_workspace_bytes", "us_status_string", "us_ffn_fwd", "us_ffn_bwd"} <= set(names)
+    L = ctypes.CDLL(us.library_path())
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_scales_and_status_strings():
+    assert us.linear_scales(256, 256, 1024) == (1 / 16, 1 / 32, 1 / 16)
+    a, bx, bw = us.linear_scales(8192, 1024, 4096, 1)
+    assert a == bx and abs(a - (1024 * 4096) ** -0.25) < 1e-9 and abs(bw - 8192 ** -0.5) < 1e-9
+    with pytest.raises(us.UsError) as e:
+        us.linear_scales(0, 4, 4)
+    assert e.value.status == 2
+    for code in range(7):
+        assert us.status_string(code)
+
+
+def test_workspace_rule():
+    assert us.workspace_bytes(32768, 4096, 16384) == 0              # output alone fills the chip
+    wb = us.workspace_bytes(8192, 1024, 4096)
+    assert wb > 0 and wb % (1024 * 4096 * 4) == 0                   # whole FP32 slices of the output
+    assert us.ffn_workspace_bytes(8192, 1024, 4096) >= wb
+
+
+def test_argument_errors_are_detected_on_the_host():
+    F16, F32, E4, E5 = us.F16, us.F32, us.E4M3, us.E5M2
+    cases = [
+        (lambda: us.cast_fp8(16, F16, 32, F16, 4), 4),               # destination must be FP8
+        (lambda: us.cast_fp8(None, F16, 32, E4, 4), 1),
+        (lambda: us.cast_fp8(24, F16, 32, E4, 4), 3),
+        (lambda: us.gelu_fwd(16, 32, 8, E4), 4),
+        (lambda: us.gelu_bwd(16, None, 32, 8, F16), 1),
+        (lambda: us.linear_fwd(16, 16, 16, 16, 16, 24, F16, F16), 2),
+        (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, F16, E4), 4),
+        (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, E4, E4, E4), 4),        # FP8 output of a matmul
+        (lambda: us.linear_fwd(16, 16, None, 16, 16, 16, F16, F16), 1),
+        (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, F16, F16, F16, 0.0, us.EPI_GELU), 1),   # no aux buffer
+        (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, F16, F16, F32, 0.0, us.EPI_GELU, 0.0, 16), 4),
+        (lambda: us.linear_bwd(16, 16, 16, 16, 16, 16, 16, 16, E4, E4, E4), 4),   # gradients are E5M2
+        (lambda: us.linear_bwd(16, 16, 16, 16, 16, 8192, 1024, 4096, F16, F16, F16), 5),  # workspace missing
+        (lambda: us.linear_bwd(16, 16, 16, 16, None, 16, 16, 16, F16, F16, F16, F16, 0, 0, us.EPI_GELU_GRAD), 1),
+        (lambda: us.linear_bwd(16, 16, 8, 16, 16, 16, 16, 16, F16, F16, F16), 3),
+    ]
+    for fn, status in cases:
+        with pytest.raises(us.UsError) as e:
+            fn()
+        assert e.value.status == status, (status, e.value)
+    # empty problems are accepted without touching any pointer
+    us.cast_fp8(None, F16, None, E4, 0)
+    us.gelu_fwd(None, None, 0)
+    us.linear_fwd(None, None, None, 0, 16, 16, F16, F16)
+    us.linear_bwd(None, None, None, None, None, 0, 0, 0, F16, F16, F16)

@@ -1,0 +1,156 @@
+"""GPU parity: us_linear_fwd / us_linear_bwd against the oracle on the same stored operands."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2303_11257_amd as us
+import synth
+from gpu_util import assert_close, cast_fp8, linear_bwd, linear_fwd, rel_err
+
+pytestmark = pytest.mark.gpu
+
+O = oracle
+
+
+def _operands(b, m, n, seed, fp8):
+    X, W, G = synth.linear_inputs(b, m, n, seed)
+    if not fp8:
+        return (X, W, G), (us.F16, us.F16, us.F16), (O.F16, O.F16, O.F16)
+    ops = (cast_fp8(X, us.E4M3), cast_fp8(W, us.E4M3), cast_fp8(G, us.E5M2))      # made by the GPU cast
+    assert np.array_equal(ops[0], O.cast_fp8(X, O.E4M3)[0])
+    return ops, (us.E4M3, us.E4M3, us.E5M2), (O.E4M3, O.E4M3, O.E5M2)
+
+
+@pytest.mark.parametrize("fp8", [False, True])
+def test_c1_linear_fwd_bwd(fp8):
+    """Config 1: X[256,256], W[256,1024], G[256,1024], scales 1/16, 1/32, 1/16; variance within 5 % of 1."""
+    b, m, n = 256, 256, 1024
+    (X, W, G), gdt, odt = _operands(b, m, n, synth.CONFIGS["C1"]["seed"], fp8)
+    a, bx, bw = us.linear_scales(b, m, n)
+    assert (a, bx, bw) == (1 / 16, 1 / 32, 1 / 16)
+    Y = linear_fwd(X, W, gdt[0], gdt[1])                               # default alpha = m^-1/2
+    dX, dW, _ = linear_bwd(X, W, G, *gdt)
+    assert_close(Y, O.linear_fwd(X, W, a, odt[0], odt[1]), "Y")
+    assert_close(dX, O.linear_bwd_dx(G, W, bx, odt[2], odt[1]), "dX")
+    assert_close(dW, O.linear_bwd_dw(X, G, bw, odt[0], odt[2]), "dW")
+    for t in (Y, dX, dW):
+        assert abs(np.var(t.astype(np.float64)) - 1.0) < 0.05
+
+
+@pytest.mark.parametrize("fp8", [False, True])
+@pytest.mark.parametrize("shape", [(16, 16, 16), (272, 144, 400), (48, 1040, 16), (528, 16, 272), (1040, 272, 528)])
+def test_ragged_shapes(fp8, shape):
+    """Dimensions that are not multiples of any tile: several tiles plus a ragged tail in M, N and K."""
+    b, m, n = shape
+    (X, W, G), gdt, odt = _operands(b, m, n, 101 + b, fp8)
+    a, bx, bw = us.linear_scales(b, m, n)
+    assert_close(linear_fwd(X, W, gdt[0], gdt[1]), O.linear_fwd(X, W, a, odt[0], odt[1]), "Y")
+    dX, dW, _ = linear_bwd(X, W, G, *gdt)
+    assert_close(dX, O.linear_bwd_dx(G, W, bx, odt[2], odt[1]), "dX")
+    assert_close(dW, O.linear_bwd_dw(X, G, bw, odt[0], odt[2]), "dW")
+
+
+@pytest.mark.parametrize("fp8", [False, True])
+def test_exact_integer_products(fp8):
+    """Inputs in {-2..2} and power-of-two scales: every partial sum is an exact integer in FP32, so the
+    GPU must equal the oracle exactly, for FP32 and FP16 outputs."""
+    b, m, n = 272, 528, 400
+    X = synth.small_ints(103, 1, (b, m))
+    W = synth.small_ints(103, 2, (m, n))
+    G = synth.small_ints(103, 4, (b, n))
+    if fp8:
+        X, W, G = cast_fp8(X, us.E4M3), cast_fp8(W, us.E4M3), cast_fp8(G, us.E5M2)
+        gdt, odt = (us.E4M3, us.E4M3, us.E5M2), (O.E4M3, O.E4M3, O.E5M2)
+    else:
+        gdt, odt = (us.F16,) * 3, (O.F16,) * 3
+    for out_g, out_o in ((us.F32, O.F32), (us.F16, O.F16)):
+        Y = linear_fwd(X, W, gdt[0], gdt[1], alpha=0.25, out_dt=out_g)
+        assert np.array_equal(Y, O.linear_fwd(X, W, 0.25, odt[0], odt[1], out_o))
+        dX, dW, _ = linear_bwd(X, W, G, *gdt, beta_x=0.5, beta_w=0.125, out_dt=out_g)
+        assert np.array_equal(dX, O.linear_bwd_dx(G, W, 0.5, odt[2], odt[1], out_o))
+        assert np.array_equal(dW, O.linear_bwd_dw(X, G, 0.125, odt[0], odt[2], out_o))
+
+
+def test_index_coded_operands_no_transposed_indexing():
+    b, m, n = 64, 48, 80
+    i, k = np.meshgrid(np.arange(b), np.arange(m), indexing="ij")
+    X = (((i + 2 * k) % 5) - 2).astype(np.float16)
+    perm = (np.arange(m) * 7) % m
+    W = np.zeros((m, n), np.float16)
+    W[np.arange(m), perm] = 1.0
+    Y = linear_fwd(X, W, us.F16, us.F16, alpha=1.0, out_dt=us.F32)
+    assert np.array_equal(Y[:, perm], X.astype(np.float32)) and np.all(Y[:, m:] == 0)
+    ii, jj = np.meshgrid(np.arange(b), np.arange(n), indexing="ij")
+    G = (((3 * ii + jj) % 5) - 2).astype(np.float16)
+    dX, dW, _ = linear_bwd(X, W, G, us.F16, us.F16, us.F16, beta_x=1.0, beta_w=1.0, out_dt=us.F32)
+    assert np.array_equal(dX, G[:, perm].astype(np.float32))
+    assert np.array_equal(dW, (X.astype(np.float64).T @ G.astype(np.float64)).astype(np.float32))
+
+
+def test_split_k_reduction_of_grad_w():
+    """A long token dimension with a small output takes the sliced reduction path (workspace in use)."""
+    b, m, n = 4096, 272, 144
+    assert us.workspace_bytes(b, m, n) > 0
+    for fp8 in (False, True):
+        (X, W, G), gdt, odt = _operands(b, m, n, 107, fp8)
+        _, dW, _ = linear_bwd(X, None, G, *gdt, do_dx=False)
+        assert_close(dW, O.linear_bwd_dw(X, G, b ** -0.5, odt[0], odt[2]), "dW split")
+        _, dW2, _ = linear_bwd(X, None, G, *gdt, do_dx=False)
+        assert np.array_equal(dW, dW2)                          # run-to-run bit identical
+
+
+@pytest.mark.parametrize("fp8", [False, True])
+def test_fused_gelu_epilogues(fp8):
+    """Stage-wise: Z vs the oracle matmul; H vs oracle GELU of the GPU's own stored Z; the FP8 copy vs the
+    oracle cast of the GPU's own stored H (bit exact); the same for GELU' in the grad_X epilogue."""
+    b, m, n = 272, 144, 400
+    (X, W, G), gdt, odt = _operands(b, m, n, 109, fp8)
+    ag, bg = O.gelu_scales()
+    a, bx, _ = us.linear_scales(b, m, n)
+    Z, H16, H8 = linear_fwd(X, W, gdt[0], gdt[1], epi=us.EPI_GELU, want16=True, want8=True)
+    assert_close(Z, O.linear_fwd(X, W, a, odt[0], odt[1]), "Z")
+    assert np.array_equal(Z, linear_fwd(X, W, gdt[0], gdt[1]))             # same Z with and without the epilogue
+    assert_close(H16, O.gelu_fwd(Z, ag), "H")
+    assert np.array_equal(H8, O.cast_fp8(H16, O.E4M3)[0])
+    # FP8-only output (the fast path) carries the same codes
+    _, none16, H8b = linear_fwd(X, W, gdt[0], gdt[1], epi=us.EPI_GELU, want16=False, want8=True)
+    assert none16 is None and np.array_equal(H8b, H8)
+    # grad_X with GELU': Zpre has the shape of dX, i.e. [b, m]
+    Zpre = synth.normal(113, 7, (b, m))
+    dH, _, _ = linear_bwd(None, W, G, *gdt, do_dw=False)
+    assert_close(dH, O.linear_bwd_dx(G, W, bx, odt[2], odt[1]), "dH")
+    dZ, _, dZ8 = linear_bwd(None, W, G, *gdt, epi=us.EPI_GELU_GRAD, Zpre=Zpre, want8=True, do_dw=False)
+    assert_close(dZ, O.gelu_bwd(Zpre, dH, bg), "dZ")
+    assert np.array_equal(dZ8, O.cast_fp8(dZ, O.E5M2)[0])
+
+
+def test_zero_reduction_length_writes_zeros():
+    import torch
+    from gpu_util import DEV, ptr, stream, to_np
+    Y = torch.full((32, 48), 7.0, dtype=torch.float16, device=DEV)
+    us.linear_fwd(None, None, ptr(Y), 32, 0, 48, us.F16, us.F16, us.F16, 1.0, us.EPI_NONE, 0.0, None, None, None, 0, stream())
+    assert np.all(to_np(Y) == 0)
+
+
+def test_subnormal_operands_are_honoured():
+    """FP16 and FP8 subnormal inputs contribute their exact value (no flush to zero in the matrix core)."""
+    b, m, n = 16, 16, 16
+    X = np.zeros((b, m), np.float16)
+    W = np.zeros((m, n), np.float16)
+    X[:, 0] = np.float16(2.0 ** -24)
+    W[0, :] = np.float16(1024.0)
+    Y = linear_fwd(X, W, us.F16, us.F16, alpha=1.0, out_dt=us.F32)
+    assert np.all(Y == np.float32(2.0 ** -14))
+    X8 = np.zeros((b, m), np.uint8)
+    W8 = np.zeros((m, n), np.uint8)
+    X8[:, 0] = 0x01                       # E4M3 2^-9
+    W8[0, :] = 0x38                       # E4M3 1.0
+    Y = linear_fwd(X8, W8, us.E4M3, us.E4M3, alpha=1.0, out_dt=us.F32)
+    assert np.all(Y == np.float32(2.0 ** -9))
+
+
+def test_fp16_output_overflows_to_infinity():
+    X = np.full((16, 16), 300.0, np.float16)
+    Y = linear_fwd(X, X, us.F16, us.F16, alpha=1.0)
+    assert np.all(np.isinf(Y.astype(np.float32)))
+    assert rel_err(Y, O.linear_fwd(X, X, 1.0)) == 0.0
