@@ -1,0 +1,230 @@
+#!/usr/bin/env python3
+"""Benchmark of the unit-scaled FFN forward + backward on one MI355X.
+
+One step = one pass of the whole hot path over one batch that is already resident in HBM:
+FP8 casts of X, W1, W2 (E4M3) and G (E5M2), Linear+GELU, Linear, and the four backward products
+(grad_X with GELU' fused, grad_W twice).  The headline workload is the FP8 BERT-large FFN
+(tokens 8192 = 64 x 128, d_model 1024, d_ff 4096); the FP16 BERT-base FFN and the cast kernel's
+bandwidth are reported beside it.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3|C2|C5] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"fp8": 5000.0, "f16": 2500.0}   # dense MFMA peaks of MI355X
+PEAK_HBM_GBS = 8000.0
+
+WORKLOADS = {
+    "C2": dict(T=4096, d=768, f=3072, fp8=False, desc="unit-scaled FFN fwd+bwd, FP16, BERT-base shape"),
+    "C3": dict(T=8192, d=1024, f=4096, fp8=True, desc="unit-scaled FFN fwd+bwd, FP8 (E4M3 fwd / E5M2 grads), BERT-large shape"),
+    "C5": dict(T=32768, d=4096, f=16384, fp8=True, desc="unit-scaled FFN fwd+bwd, FP8, LLM-size shape"),
+}
+
+
+class Ffn:
+    """Device buffers for one workload and the calls of one step."""
+
+    def __init__(self, torch, us, synth, T, d, f, fp8, seed):
+        self.torch, self.us = torch, us
+        self.T, self.d, self.f, self.fp8 = T, d, f, fp8
+        dev = "cuda:0"
+        self.X = synth.normal_on_device(seed, synth.T_X, (T, d), dev)
+        self.W1 = synth.normal_on_device(seed, synth.T_W1, (d, f), dev)
+        self.W2 = synth.normal_on_device(seed, synth.T_W2, (f, d), dev)
+        self.G = synth.normal_on_device(seed, synth.T_G, (T, d), dev)
+        e = lambda shape, dt=torch.float16: torch.empty(shape, dtype=dt, device=dev)
+        u8 = torch.uint8
+        if fp8:
+            self.X8, self.W1_8, self.W2_8, self.G8 = e((T, d), u8), e((d, f), u8), e((f, d), u8), e((T, d), u8)
+        self.Z, self.Y = e((T, f)), e((T, d))
+        self.H = e((T, f), u8 if fp8 else torch.float16)
+        self.dZ16, self.dX, self.dW1, self.dW2 = e((T, f)), e((T, d)), e((d, f)), e((f, d))
+        self.dZ8 = e((T, f), u8) if fp8 else None
+        self.wsb = us.ffn_workspace_bytes(T, d, f)
+        self.ws = torch.empty(max(self.wsb, 16), dtype=u8, device=dev)
+        self.flop = 12.0 * T * d * f
+
+    def p(self, t):
+        return None if t is None else t.data_ptr()
+
+    def calls(self):
+        """The step as a list of (name, kind, flop, bytes, thunk) using the fine-grained entry points."""
+        us, p, st = self.us, self.p, self.torch.cuda.current_stream().cuda_stream
+        T, d, f = self.T, self.d, self.f
+        gemm = 2.0 * T * d * f
+        out = []
+        if self.fp8:
+            op, gr = us.E4M3, us.E5M2
+            X, W1, W2, G = self.X8, self.W1_8, self.W2_8, self.G8
+            for name, src, dst, fmt in (("cast_X", self.X, X, op), ("cast_W1", self.W1, W1, op), ("cast_W2", self.W2, W2, op),
+                                        ("cast_G", self.G, G, gr)):
+                n = src.numel()
+                out.append((name, "cast", 0.0, 3.0 * n,
+                            lambda src=src, dst=dst, fmt=fmt, n=n: us.cast_fp8(p(src), us.F16, p(dst), fmt, n, 1.0, None, st)))
+        else:
+            op = gr = us.F16
+            X, W1, W2, G = self.X, self.W1, self.W2, self.G
+        a16, a8 = (None, self.H) if self.fp8 else (self.H, None)
+        out.append(("fwd1_gelu", "gemm", gemm, 0.0, lambda: us.linear_fwd(p(X), p(W1), p(self.Z), T, d, f, op, op, us.F16, 0.0,
+                                                                         us.EPI_GELU, 0.0, p(a16), p(a8), None, 0, st)))
+        out.append(("fwd2", "gemm", gemm, 0.0, lambda: us.linear_fwd(p(self.H), p(W2), p(self.Y), T, f, d, op, op, us.F16, 0.0,
+                                                                    us.EPI_NONE, 0.0, None, None, None, 0, st)))
+        out.append(("dx2_gelugrad", "gemm", gemm, 0.0,
+                    lambda: us.linear_bwd(None, p(W2), p(G), p(self.dZ16), None, T, f, d, op, op, gr, us.F16, 0.0, 0.0,
+                                          us.EPI_GELU_GRAD, 0.0, p(self.Z), p(self.dZ8), None, 0, st)))
+        out.append(("dw2", "gemm", gemm, 0.0,
+                    lambda: us.linear_bwd(p(self.H), None, p(G), None, p(self.dW2), T, f, d, op, op, gr, us.F16, 0.0, 0.0,
+                                          us.EPI_NONE, 0.0, None, None, p(self.ws), self.wsb, st)))
+        dZ = self.dZ8 if self.fp8 else self.dZ16
+        out.append(("dx1", "gemm", gemm, 0.0,
+                    lambda: us.linear_bwd(None, p(W1), p(dZ), p(self.dX), None, T, d, f, op, op, gr, us.F16, 0.0, 0.0,
+                                          us.EPI_NONE, 0.0, None, None, None, 0, st)))
+        out.append(("dw1", "gemm", gemm, 0.0,
+                    lambda: us.linear_bwd(p(X), None, p(dZ), None, p(self.dW1), T, d, f, op, op, gr, us.F16, 0.0, 0.0,
+                                          us.EPI_NONE, 0.0, None, None, p(self.ws), self.wsb, st)))
+        return out
+
+    def step(self):
+        """The step through the two FFN entry points (what `value` times)."""
+        us, p, st = self.us, self.p, self.torch.cuda.current_stream().cuda_stream
+        T, d, f = self.T, self.d, self.f
+        if self.fp8:
+            us.cast_fp8(p(self.X), us.F16, p(self.X8), us.E4M3, self.X.numel(), 1.0, None, st)
+            us.cast_fp8(p(self.W1), us.F16, p(self.W1_8), us.E4M3, self.W1.numel(), 1.0, None, st)
+            us.cast_fp8(p(self.W2), us.F16, p(self.W2_8), us.E4M3, self.W2.numel(), 1.0, None, st)
+            us.cast_fp8(p(self.G), us.F16, p(self.G8), us.E5M2, self.G.numel(), 1.0, None, st)
+            X, W1, W2, G = self.X8, self.W1_8, self.W2_8, self.G8
+        else:
+            X, W1, W2, G = self.X, self.W1, self.W2, self.G
+        us.ffn_fwd(p(X), p(W1), p(W2), p(self.Z), p(self.H), p(self.Y), T, d, f, self.fp8, st)
+        us.ffn_bwd(p(X), p(W1), p(W2), p(self.Z), p(self.H), p(G), p(self.dZ16), p(self.dZ8), p(self.dX), p(self.dW1),
+                   p(self.dW2), T, d, f, self.fp8, p(self.ws), self.wsb, st)
+
+
+def time_steps(torch, fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def time_calls(torch, calls, steps):
+    """Average duration of each call of the step, from HIP events on the launch stream, over `steps` passes."""
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in calls] for _ in range(steps)]
+    torch.cuda.synchronize()
+    for s in range(steps):
+        for (name, kind, flop, nbytes, thunk), (e0, e1) in zip(calls, ev[s]):
+            e0.record()
+            thunk()
+            e1.record()
+    torch.cuda.synchronize()
+    res = []
+    for i, (name, kind, flop, nbytes, _) in enumerate(calls):
+        ms = sum(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(steps)) / steps
+        res.append(dict(name=name, kind=kind, ms=ms, flop=flop, bytes=nbytes))
+    return res
+
+
+def cpu_baseline(ffn, sample_tokens):
+    """The oracle, as it stands, on the first `sample_tokens` tokens of the same tensors (all of d and f)."""
+    import numpy as np
+    import oracle
+    n = sample_tokens
+    X = ffn.X[:n].cpu().numpy()
+    G = ffn.G[:n].cpu().numpy()
+    W1, W2 = ffn.W1.cpu().numpy(), ffn.W2.cpu().numpy()
+    t0 = time.perf_counter()
+    fw = oracle.ffn_fwd(X, W1, W2, ffn.fp8)
+    oracle.ffn_bwd(X, W1, W2, G, fw, ffn.fp8)
+    dt = time.perf_counter() - t0
+    flop = 12.0 * n * ffn.d * ffn.f
+    return dict(value=flop / dt * 1e-12, unit="TFLOP/s", cores=oracle.cpu_threads(), kind="oracle", seconds=dt,
+                sample=f"first {n} of {ffn.T} tokens, full d_model and d_ff, every stage (casts, 6 matmuls, GELU fwd/bwd)")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="C3", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true", help="skip the FP16 BERT-base side measurement")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=512)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the path shards over tokens; see DESIGN.md); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2303_11257_amd as us
+    import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    us.lib()   # fails loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+
+    w = WORKLOADS[args.workload]
+    ffn = Ffn(torch, us, synth, w["T"], w["d"], w["f"], w["fp8"], synth.BASE_SEED + 2)
+    ms_step = time_steps(torch, ffn.step, args.steps, args.warmup)
+    tflops = ffn.flop / (ms_step * 1e-3) * 1e-12
+    dt_key = "fp8" if w["fp8"] else "f16"
+
+    per_call = time_calls(torch, ffn.calls(), args.steps)
+    gemms = [c for c in per_call if c["kind"] == "gemm"]
+    casts = [c for c in per_call if c["kind"] == "cast"]
+    dom = max(gemms, key=lambda c: c["ms"])
+    gemm_ms = sum(c["ms"] for c in gemms)
+    roof = dict(bound="mfma", kernel=dom["name"], achieved=dom["flop"] / (dom["ms"] * 1e-3) * 1e-12,
+                peak=PEAK_TFLOPS[dt_key], unit="TFLOP/s", traffic=None)
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["ms"] = dom["ms"]
+    roof["all_gemms_achieved"] = sum(c["flop"] for c in gemms) / (gemm_ms * 1e-3) * 1e-12
+    out = {
+        "metric": "unit-scaled FFN fwd+bwd TFLOP/s",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp8" if w["fp8"] else "f16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {w['desc']}", "tokens": w["T"], "d_model": w["d"], "d_ff": w["f"],
+                   "step": "casts of X,W1,W2,G + Linear+GELU + Linear + 4 backward matmuls (GELU' fused)" if w["fp8"]
+                           else "Linear+GELU + Linear + 4 backward matmuls (GELU' fused)"},
+        "frac_of_mfma_peak": tflops / PEAK_TFLOPS[dt_key],
+        "roofline": roof,
+        "calls_ms": {c["name"]: round(c["ms"], 5) for c in per_call},
+        "calls_tflops": {c["name"]: round(c["flop"] / (c["ms"] * 1e-3) * 1e-12, 1) for c in gemms},
+    }
+    if casts:
+        cb, cm = sum(c["bytes"] for c in casts), sum(c["ms"] for c in casts)
+        out["cast"] = {"GBps": cb / (cm * 1e-3) * 1e-9, "frac_of_hbm_peak": cb / (cm * 1e-3) * 1e-9 / PEAK_HBM_GBS,
+                       "bytes_per_elem": 3}
+    if not args.no_secondary and args.workload != "C2":
+        w2 = WORKLOADS["C2"]
+        f2 = Ffn(torch, us, synth, w2["T"], w2["d"], w2["f"], False, synth.BASE_SEED + 1)
+        ms2 = time_steps(torch, f2.step, args.steps, args.warmup)
+        t2 = f2.flop / (ms2 * 1e-3) * 1e-12
+        out["fp16_bert_base"] = {"workload": "C2: " + w2["desc"], "ms_per_step": ms2, "TFLOPs": t2,
+                                 "frac_of_mfma_peak": t2 / PEAK_TFLOPS["f16"]}
+        del f2
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(ffn, min(args.cpu_sample_tokens, w["T"]))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

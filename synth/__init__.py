@@ -113,3 +113,15 @@ def ffn_inputs(T: int, d: int, f: int, seed: int):
     """X[T,d], W1[d,f], W2[f,d], G[T,d], all FP16 N(0,1) (unit-scaled initialisation)."""
     return (normal(seed, T_X, (T, d)), normal(seed, T_W1, (d, f)), normal(seed, T_W2, (f, d)),
             normal(seed, T_G, (T, d)))
+
+
+def normal_on_device(seed: int, tensor: int, shape, device="cuda:0"):
+    """FP16 N(0,1) drawn on the GPU by PyTorch's seeded Philox generator.
+
+    For the largest workload only (hundreds of millions of elements), where the numpy generator above
+    would take minutes; slabs of the result are copied back for the oracle.  Returns a torch tensor.
+    """
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(seed * 1000003 + tensor)
+    return torch.randn(shape, generator=g, device=device, dtype=torch.float32).to(torch.float16)

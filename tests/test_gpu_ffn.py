@@ -1,0 +1,156 @@
+"""GPU parity for the whole FFN path (cast -> Linear+GELU -> Linear, and its backward) through
+us_ffn_fwd / us_ffn_bwd: full comparison on a small ragged shape, sampled rows / columns at the
+benchmark shapes.  Every stage is compared with the oracle applied to the GPU's own stored inputs of
+that stage."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2303_11257_amd as us
+import synth
+from gpu_util import DEV, assert_close, ptr, stream, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+class FfnRun:
+    """Device buffers of one FFN forward + backward; `dev` tensors stay on the GPU."""
+
+    def __init__(self, X, W1, W2, G, fp8):
+        self.fp8 = fp8
+        T, d = X.shape
+        f = W1.shape[1]
+        self.T, self.d, self.f = T, d, f
+        dev = {k: (v if isinstance(v, torch.Tensor) else to_dev(v)) for k, v in dict(X=X, W1=W1, W2=W2, G=G).items()}
+        st = stream()
+        if fp8:
+            for k, fmt in (("X", us.E4M3), ("W1", us.E4M3), ("W2", us.E4M3), ("G", us.E5M2)):
+                dst = torch.empty(dev[k].shape, dtype=torch.uint8, device=DEV)
+                us.cast_fp8(ptr(dev[k]), us.F16, ptr(dst), fmt, dev[k].numel(), 1.0, None, st)
+                dev[k + "op"] = dst
+        else:
+            for k in ("X", "W1", "W2", "G"):
+                dev[k + "op"] = dev[k]
+        e = lambda shape, dt=torch.float16: torch.empty(shape, dtype=dt, device=DEV)
+        dev["Z"], dev["Y"] = e((T, f)), e((T, d))
+        dev["H"] = e((T, f), torch.uint8 if fp8 else torch.float16)
+        dev["dZ16"], dev["dX"], dev["dW1"], dev["dW2"] = e((T, f)), e((T, d)), e((d, f)), e((f, d))
+        dev["dZ8"] = e((T, f), torch.uint8) if fp8 else None
+        wsb = us.ffn_workspace_bytes(T, d, f)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=DEV)
+        us.ffn_fwd(ptr(dev["Xop"]), ptr(dev["W1op"]), ptr(dev["W2op"]), ptr(dev["Z"]), ptr(dev["H"]), ptr(dev["Y"]),
+                   T, d, f, fp8, st)
+        us.ffn_bwd(ptr(dev["Xop"]), ptr(dev["W1op"]), ptr(dev["W2op"]), ptr(dev["Z"]), ptr(dev["H"]), ptr(dev["Gop"]),
+                   ptr(dev["dZ16"]), ptr(dev["dZ8"]), ptr(dev["dX"]), ptr(dev["dW1"]), ptr(dev["dW2"]), T, d, f, fp8,
+                   ptr(ws), wsb, st)
+        torch.cuda.synchronize()
+        self.dev = dev
+
+    def rows(self, name, idx):
+        return self.dev[name][torch.as_tensor(idx, device=DEV)].cpu().numpy()
+
+    def cols(self, name, idx):
+        return self.dev[name][:, torch.as_tensor(idx, device=DEV)].contiguous().cpu().numpy()
+
+    def full(self, name):
+        return self.dev[name].cpu().numpy()
+
+
+def check_ffn(run: FfnRun, rows, cols_f, cols_d):
+    """rows: sampled token rows; cols_f / cols_d: sampled indices in the f and d dimensions."""
+    fp8, T, d, f = run.fp8, run.T, run.d, run.f
+    act, grad = (O.E4M3, O.E5M2) if fp8 else (O.F16, O.F16)
+    ag, bg = O.gelu_scales()
+    a1, bx1, bw1 = O.linear_scales(T, d, f)
+    a2, bx2, bw2 = O.linear_scales(T, f, d)
+    W1, W2 = run.full("W1op"), run.full("W2op")
+    X_r, G_r = run.rows("Xop", rows), run.rows("Gop", rows)
+    if fp8:   # operands were produced by the GPU cast: bit exact against the oracle cast of the FP16 tensors
+        assert np.array_equal(X_r, O.cast_fp8(run.rows("X", rows), O.E4M3)[0])
+        assert np.array_equal(G_r, O.cast_fp8(run.rows("G", rows), O.E5M2)[0])
+        assert np.array_equal(W1, O.cast_fp8(run.full("W1"), O.E4M3)[0])
+    errs = {}
+    # forward, layer 1 + fused GELU
+    Z_r = run.rows("Z", rows)
+    errs["Z"] = assert_close(Z_r, O.linear_fwd(X_r, W1, a1, act, act), "Z")
+    H_ref16 = O.gelu_fwd(Z_r, ag)
+    H_r = run.rows("H", rows)
+    if fp8:
+        # only the codes are stored: they may differ from cast(oracle GELU of the stored Z) by one code
+        # where the FP32 GELU moved the FP16 value across an FP8 rounding boundary
+        ref8 = O.cast_fp8(H_ref16, O.E4M3)[0]
+        diff = np.abs(H_r.astype(np.int32) - ref8.astype(np.int32))
+        assert diff.max() <= 1 and np.mean(diff != 0) < 1e-3
+    else:
+        errs["H"] = assert_close(H_r, H_ref16, "H")
+    # forward, layer 2 (its operand is the GPU's own stored H)
+    errs["Y"] = assert_close(run.rows("Y", rows), O.linear_fwd(H_r, W2, a2, act, act), "Y")
+    # backward, layer 2: dH (not stored) -> dZ
+    dH_ref = O.linear_bwd_dx(G_r, W2, bx2, grad, act)
+    dZ_r = run.rows("dZ16", rows)
+    errs["dZ"] = assert_close(dZ_r, O.gelu_bwd(Z_r, dH_ref, bg), "dZ")
+    if fp8:
+        dZ8_r = run.rows("dZ8", rows)
+        assert np.array_equal(dZ8_r, O.cast_fp8(dZ_r, O.E5M2)[0])         # FP8 copy of the stored FP16 dZ: bit exact
+    dZop_r = run.rows("dZ8", rows) if fp8 else dZ_r
+    errs["dX"] = assert_close(run.rows("dX", rows), O.linear_bwd_dx(dZop_r, W1, bx1, grad, act), "dX")
+    # weight gradients: all tokens, sampled output rows (= sampled columns of the left operand)
+    H_c = run.cols("H", cols_f)                                            # [T, |cols_f|]
+    G_all = run.full("Gop")
+    errs["dW2"] = assert_close(run.rows("dW2", cols_f), O.linear_bwd_dw(H_c, G_all, bw2, act, grad), "dW2")
+    X_c = run.cols("Xop", cols_d)
+    dZ_all = run.full("dZ8" if fp8 else "dZ16")
+    errs["dW1"] = assert_close(run.rows("dW1", cols_d), O.linear_bwd_dw(X_c, dZ_all, bw1, act, grad), "dW1")
+    return errs
+
+
+@pytest.mark.parametrize("fp8", [False, True])
+def test_small_ragged_ffn_full_comparison(fp8):
+    T, d, f = 272, 144, 400
+    X, W1, W2, G = synth.ffn_inputs(T, d, f, seed=127)
+    run = FfnRun(X, W1, W2, G, fp8)
+    check_ffn(run, np.arange(T), np.arange(f), np.arange(d))
+
+
+def _sample(n, k, seed):
+    rng = np.random.default_rng(seed)
+    return np.sort(rng.choice(n, size=min(k, n), replace=False))
+
+
+def _variances(run):
+    v = lambda name: float(torch.var(run.dev[name].float()).item())
+    eh2 = float(O.gelu_scales()[0]) ** 2 * (1 / 3 + 1 / (2 * np.pi * np.sqrt(3)))
+    for name in ("Z", "dZ16", "dX", "dW1"):
+        assert abs(v(name) - 1.0) < 0.05, (name, v(name))
+    for name in ("Y", "dW2"):
+        assert abs(v(name) / eh2 - 1.0) < 0.05, (name, v(name))
+
+
+def test_c2_bert_base_fp16():
+    c = synth.CONFIGS["C2"]
+    X, W1, W2, G = synth.ffn_inputs(c["T"], c["d"], c["f"], c["seed"])
+    run = FfnRun(X, W1, W2, G, fp8=False)
+    check_ffn(run, _sample(c["T"], 48, 1), _sample(c["f"], 24, 2), _sample(c["d"], 24, 3))
+    _variances(run)
+
+
+def test_c3_bert_large_fp8():
+    c = synth.CONFIGS["C3"]
+    X, W1, W2, G = synth.ffn_inputs(c["T"], c["d"], c["f"], c["seed"])
+    run = FfnRun(X, W1, W2, G, fp8=True)
+    check_ffn(run, _sample(c["T"], 48, 4), _sample(c["f"], 24, 5), _sample(c["d"], 24, 6))
+    _variances(run)
+
+
+def test_c5_llm_size_fp8_sampled():
+    """T=32768, d=4096, f=16384: inputs drawn on the GPU, oracle on a few rows / columns."""
+    c = synth.CONFIGS["C5"]
+    T, d, f = c["T"], c["d"], c["f"]
+    X = synth.normal_on_device(c["seed"], synth.T_X, (T, d))
+    W1 = synth.normal_on_device(c["seed"], synth.T_W1, (d, f))
+    W2 = synth.normal_on_device(c["seed"], synth.T_W2, (f, d))
+    G = synth.normal_on_device(c["seed"], synth.T_G, (T, d))
+    run = FfnRun(X, W1, W2, G, fp8=True)
+    check_ffn(run, _sample(T, 6, 7), _sample(f, 3, 8), _sample(d, 3, 9))
+    _variances(run)
