@@ -26,19 +26,24 @@ hipError_t launch_splitk_reduce(const float* partial, void* out, long total, int
   return hipGetLastError();
 }
 
-// grad_W has a small output (fan_in x fan_out) and a long reduction (tokens): when its 256x256
-// tiles cannot occupy the 256 CUs, the token range is cut into slices of whole 128-token stages.
-int gemm_splits(long M, long N, long K) {
-  const long tiles = ((M + 255) / 256) * ((N + 255) / 256);
-  if (tiles >= 192 || K < 1024) return 1;
-  long s = 256 / tiles;
-  const long max_by_k = K / 512;          // at least four stages per slice
-  if (s > max_by_k) s = max_by_k;
-  if (s > 16) s = 16;
-  if (s < 1) s = 1;
+// grad_W has a small output (fan_in x fan_out) and a long reduction (tokens).  When its large tiles
+// cannot occupy the chip the small tile is used (two workgroups per CU, 512 slots), and if even those
+// are too few the token range is cut into slices of whole 128-token stages, at least 512 tokens each.
+long gemm_k_per_split(long K, int splits) {
   const long unit = 128;
-  const long k_per_split = ((K + s - 1) / s + unit - 1) / unit * unit;
-  return (int)((K + k_per_split - 1) / k_per_split);
+  return ((K + splits - 1) / splits + unit - 1) / unit * unit;
+}
+
+int gemm_splits(long M, long N, long K) {
+  if (use_big_tile(M, N, 1) || K < 1024) return 1;
+  const long tiles = ceil_div(M, 128) * ceil_div(N, 128);
+  long s = 512 / tiles;
+  const long max_by_k = K / 512;
+  if (s > max_by_k) s = max_by_k;
+  if (s > 8) s = 8;
+  if (s < 1) s = 1;
+  const long kps = gemm_k_per_split(K, (int)s);
+  return (int)((K + kps - 1) / kps);
 }
 
 size_t gemm_workspace_bytes(long M, long N, long K) {

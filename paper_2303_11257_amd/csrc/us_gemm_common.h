@@ -1,0 +1,182 @@
+// Pieces shared by the two GEMM kernels of the gfx950 library: argument block, tile configuration,
+// matrix-core wrappers, workgroup -> tile mapping, and the epilogue that turns a wave's accumulator
+// block into scaled FP16 / FP32 rows (optionally through GELU or GELU') with 128-bit global stores.
+#pragma once
+
+#include "us_device.h"
+
+namespace us {
+
+enum GemmEpi : int { EPI_STORE = 0, EPI_GELU = 1, EPI_GELU_GRAD = 2, EPI_PARTIAL = 3 };
+
+//   C[M,N] = epilogue( scale * sum_k A(m,k) * B(n,k) )
+// An operand is K-contiguous (element (r,k) at base[r*ld + k]) or K-strided (element (r,k) at
+// base[k*ld + r]).
+struct GemmArgs {
+  const uint8_t* A;
+  const uint8_t* B;
+  void* C;
+  long M, N, K;          // K = full reduction length
+  long lda, ldb, ldc;    // elements
+  long k_per_split;      // reduction range of one slice (blockIdx.y); a multiple of 128 elements
+  float scale, epi_scale;
+  const _Float16* Zpre;  // EPI_GELU_GRAD: saved pre-activation [M,N], leading dimension ldc
+  _Float16* aux16;       // EPI_GELU: optional FP16 activation output
+  uint8_t* aux8;         // optional FP8 copy of the epilogue's FP16 result
+  float* partial;        // EPI_PARTIAL: [splits][M][N] FP32
+  int xcd_gm, xcd_gn;    // XCD rectangle split of the tile grid (0,0 = linear order)
+};
+
+// Tile configuration.  BKB = bytes of K per row and pipeline stage; NST = LDS stage buffers;
+// MINB = workgroups per CU the register allocation should allow.
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int BKB_, int NST_, int MINB_>
+struct GemmCfg {
+  static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, BKB = BKB_, NST = NST_, MINB = MINB_;
+  static constexpr int WAVES = WAVES_M * WAVES_N;
+  static constexpr int THREADS = 64 * WAVES;
+  static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  static constexpr int FM = WM / 32, FN = WN / 32;   // 32x32 accumulator blocks per wave
+};
+
+#define US_LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+template <int FA, int FB>
+__device__ __forceinline__ v16f mfma_fp8(v8i a, v8i b, v16f c) {
+  // format codes of the instruction: 0 = E4M3, 1 = E5M2; unit block scales
+  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, FA, FB, 0, 0, 0, 0);
+}
+
+// ---- workgroup -> output tile ------------------------------------------------------------------------
+// Workgroups are handed to the 8 XCDs round-robin by linear id, and every XCD has its own L2.  When
+// the tile grid divides evenly (host: choose_xcd_grid), XCD x gets a compact rectangle of
+// (tiles_m/gm) x (tiles_n/gn) tiles, so the A and B panels it touches are shared inside one L2, and
+// walks it M-fastest; with gm == 0 the plain M-fastest order is used.
+__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int gm, int gn, int& tm, int& tn) {
+  if (gm == 0) {
+    tm = bid % tiles_m;
+    tn = bid / tiles_m;
+    return;
+  }
+  const int xcd = bid & 7, idx = bid >> 3;
+  const int rm = tiles_m / gm, rn = tiles_n / gn;
+  tm = (xcd % gm) * rm + idx % rm;
+  tn = (xcd / gm) * rn + idx / rm;
+}
+
+// Host side: the split gm x gn = 8 that divides the tile grid and minimises the number of operand
+// panels one XCD touches; gm = gn = 0 when the grid does not divide.
+inline void choose_xcd_grid(long tiles_m, long tiles_n, int& gm, int& gn) {
+  gm = gn = 0;
+  if ((tiles_m * tiles_n) % 8 != 0) return;
+  long best = -1;
+  for (int c = 1; c <= 8; c <<= 1) {
+    const int cm = c, cn = 8 / c;
+    if (tiles_m % cm || tiles_n % cn) continue;
+    const long cost = tiles_m / cm + tiles_n / cn;
+    if (best < 0 || cost < best) { best = cost; gm = cm; gn = cn; }
+  }
+}
+
+// ---- epilogue on eight consecutive columns of one row (FP16 strip) ---------------------------------
+template <int EPI, int AUX_FMT>
+__device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y) {
+  if (EPI == EPI_STORE) {
+    *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = y;
+    return;
+  }
+  v8h r;
+  if (EPI == EPI_GELU) {
+    *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = y;   // the FP16 matmul result, kept for backward
+#pragma unroll
+    for (int k = 0; k < 8; ++k) r[k] = (_Float16)gelu_scaled((float)y[k], g.epi_scale);
+    if (g.aux16) *reinterpret_cast<v8h*>(g.aux16 + idx) = r;
+  } else {  // EPI_GELU_GRAD: y is the FP16-rounded matmul gradient
+    v8h z = *reinterpret_cast<const v8h*>(g.Zpre + idx);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) r[k] = (_Float16)gelu_grad_scaled((float)z[k], (float)y[k], g.epi_scale);
+    *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = r;
+  }
+  if (g.aux8) {
+    // FP8 copy of the FP16 value just stored: identical to casting the stored tensor afterwards
+    v2i w;
+    w.x = (int)cvt4_fp8<AUX_FMT>((float)r[0], (float)r[1], (float)r[2], (float)r[3]);
+    w.y = (int)cvt4_fp8<AUX_FMT>((float)r[4], (float)r[5], (float)r[6], (float)r[7]);
+    *reinterpret_cast<v2i*>(g.aux8 + idx) = w;
+  }
+}
+
+// Strip geometry: every wave owns 32 rows x WN values of LDS (FP16, or FP32 when WIDE).
+template <class Cfg, bool WIDE>
+struct EpiStrip {
+  static constexpr int ES = WIDE ? 4 : 2;
+  static constexpr int PITCH = Cfg::WN * ES + 16;
+  static constexpr int BYTES = 32 * PITCH * Cfg::WAVES;
+};
+
+// The matrix core is fed with the N-side fragment as first operand, so register 4q+e of lane l of a
+// 32x32 accumulator block holds (row l%32, column 8q + 4(l/32) + e).  Each wave pushes 32 rows of
+// its block at a time through its LDS strip and reads them back row-contiguously: all global stores
+// (and the read of the saved pre-activation) are 128-bit accesses sweeping whole rows.
+// Must be entered by all waves after a workgroup barrier (the strips overlay the operand tiles).
+template <class Cfg, int EPI, bool WIDE>
+__device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&acc)[Cfg::FM][Cfg::FN], uint8_t* lds,
+                                                     long m0, long n0, long split) {
+  static_assert(WIDE ? (EPI == EPI_STORE || EPI == EPI_PARTIAL) : (EPI != EPI_PARTIAL), "");
+  using S = EpiStrip<Cfg, WIDE>;
+  constexpr int AUX_FMT = (EPI == EPI_GELU_GRAD) ? US_E5M2 : US_E4M3;
+  constexpr int EP = S::PITCH;
+  const int wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wm0 = (wave % Cfg::WAVES_M) * Cfg::WM;
+  const int wn0 = (wave / Cfg::WAVES_M) * Cfg::WN;
+  uint8_t* strip = lds + wave * (32 * EP);
+  const float scale = (EPI == EPI_PARTIAL) ? 1.0f : g.scale;
+#pragma unroll
+  for (int i = 0; i < Cfg::FM; ++i) {
+#pragma unroll
+    for (int j = 0; j < Cfg::FN; ++j) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = j * 32 + 8 * q + 4 * (lane >> 5);
+        const float v0 = acc[i][j][4 * q] * scale, v1 = acc[i][j][4 * q + 1] * scale;
+        const float v2 = acc[i][j][4 * q + 2] * scale, v3 = acc[i][j][4 * q + 3] * scale;
+        uint8_t* p = strip + (lane & 31) * EP + col * S::ES;
+        if (WIDE) {
+          v4f o = {v0, v1, v2, v3};
+          *US_LDS_PTR(v4f, p) = o;
+        } else {
+          v4h o = {(_Float16)v0, (_Float16)v1, (_Float16)v2, (_Float16)v3};
+          *US_LDS_PTR(v4h, p) = o;
+        }
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    constexpr int CPR = Cfg::WN * S::ES / 16;          // 16-byte chunks per strip row
+    constexpr int PER_LANE = 32 * CPR / 64;
+#pragma unroll
+    for (int u = 0; u < PER_LANE; ++u) {
+      const int c = lane + u * 64;
+      const int row = c / CPR, cc = c % CPR;
+      const long m = m0 + wm0 + i * 32 + row;
+      const long n = n0 + wn0 + cc * (16 / S::ES);
+      const uint8_t* p = strip + row * EP + cc * 16;
+      if (m < g.M && n < g.N) {
+        if (WIDE) {
+          v4f v = *US_LDS_PTR(const v4f, p);
+          if (EPI == EPI_PARTIAL)
+            *reinterpret_cast<v4f*>(g.partial + (size_t)split * g.M * g.N + m * g.N + n) = v;
+          else
+            *reinterpret_cast<v4f*>((float*)g.C + m * g.ldc + n) = v;
+        } else {
+          v8h y = *US_LDS_PTR(const v8h, p);
+          epilogue_row8<EPI, AUX_FMT>(g, m * g.ldc + n, y);
+        }
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+}  // namespace us

@@ -1,0 +1,309 @@
+// Direct-to-LDS pipelined GEMM kernel for gfx950 (the fast path: reduction length a multiple of the
+// stage, everything else may be ragged).
+//
+// Operand tiles travel HBM/L2 -> LDS with global_load_lds_dwordx4 (no register staging, no LDS
+// store instructions): a wave instruction deposits 64 x 16 B contiguously, so tiles are unpadded and
+// bank conflicts are removed by an XOR swizzle of the 16-byte chunk index instead; the swizzle is
+// applied to the *global* address each lane fetches and again when fragments are read.
+// NST stage buffers form a ring.  Matrix-core fragments are double-buffered in registers: while the
+// MFMAs of one k-step run, the LDS reads of the next k-step are already in flight, also across the
+// stage boundary.  At that boundary a wave waits for its own LDS reads of stage s, then for its own
+// loads of stage s+1 (explicit s_waitcnt vmcnt(n): younger stages stay in flight), then meets the
+// other waves at one bare s_barrier; after it the buffer of stage s is free and receives the loads
+// of stage s+NST, so NST stages of HBM latency are covered by MFMAs.
+//
+// Tile layouts in LDS (pitch P bytes, chunk = 16 B, c' = c ^ swz(row)):
+//   K-contiguous operand: [row][BKB bytes]        fragments: ds_read_b128
+//   K-strided operand:    [k][rows * elem size]   fragments: ds_read_b64_tr_b8 / _tr_b16 (transposing)
+// Rows / columns beyond the matrix are never loaded; their LDS slots are zeroed once up front.
+#pragma once
+
+#include <type_traits>
+
+#include "us_gemm_common.h"
+
+namespace us {
+
+template <class Cfg, bool FP8, bool A_KC, bool B_KC, bool WIDE>
+struct DirectTile {
+  static constexpr int ES = FP8 ? 1 : 2;
+  static constexpr int BK = Cfg::BKB / ES;                      // elements of K per stage
+  static constexpr int PA = A_KC ? Cfg::BKB : Cfg::BM * ES;     // LDS pitch of the A / B tile
+  static constexpr int PB = B_KC ? Cfg::BKB : Cfg::BN * ES;
+  static constexpr int A_BYTES = Cfg::BM * Cfg::BKB;
+  static constexpr int B_BYTES = Cfg::BN * Cfg::BKB;
+  static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+  static constexpr int A_LOADS = A_BYTES / 16 / Cfg::THREADS;   // 16-byte loads per thread and stage
+  static constexpr int B_LOADS = B_BYTES / 16 / Cfg::THREADS;
+  static constexpr int RING_BYTES = Cfg::NST * STAGE_BYTES;
+  static constexpr int EPI_BYTES = EpiStrip<Cfg, WIDE>::BYTES;
+  static constexpr int LDS_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
+  static_assert(A_BYTES % (16 * Cfg::THREADS) == 0 && B_BYTES % (16 * Cfg::THREADS) == 0, "whole wave loads only");
+  static_assert(Cfg::NST >= 2 && Cfg::NST <= 4, "");
+  static_assert((FP8 ? Cfg::BKB / 64 : Cfg::BKB / 32) % 2 == 0, "an even number of k-steps per stage (register double buffer)");
+};
+
+// XOR mask on the 16-byte chunk index of LDS row `row` (see the bank analysis in the file header of the
+// design notes: 64 banks x 4 B; b128 reads are served 16 lanes at a time, b64 reads 32 lanes).
+template <bool KC, bool FP8, int PITCH>
+__device__ __forceinline__ int swz(int row) {
+  if constexpr (KC) {
+    static_assert(PITCH == 64 || PITCH == 128, "K-contiguous pitch");
+    return PITCH == 64 ? ((row >> 2) & 3) : ((row >> 1) & 7);
+  } else if constexpr (FP8) {
+    static_assert(PITCH == 128 || PITCH == 256, "K-strided FP8 pitch");
+    return PITCH == 256 ? ((row & 7) << 1) : (((row >> 1) & 3) << 1);
+  } else {
+    static_assert(PITCH == 256 || PITCH == 512, "K-strided FP16 pitch");
+    return (row & 3) << 2;
+  }
+}
+
+// Global source pointers of this thread's loads for stage 0 (pointer is null for slots outside the
+// matrix), for one operand tile of ROWS rows starting at row0.
+template <int THREADS, int ROWS, int BKB, bool KC, bool FP8, int PITCH, int NL>
+__device__ __forceinline__ void direct_sources(const uint8_t* base, long ld, long row0, long extent_r, long k0,
+                                               const uint8_t* (&src)[NL]) {
+  constexpr int ES = FP8 ? 1 : 2;
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int j = 0; j < NL; ++j) {
+    const int off = (j * THREADS + t) * 16;
+    const int row = off / PITCH;
+    const int cc = ((off % PITCH) >> 4) ^ swz<KC, FP8, PITCH>(row);
+    long r, k;
+    if (KC) { r = row0 + row; k = k0 + cc * (16 / ES); }
+    else    { k = k0 + row;   r = row0 + cc * (16 / ES); }
+    const uint8_t* p = KC ? base + (r * ld + k) * ES : base + (k * ld + r) * ES;
+    src[j] = (r < extent_r) ? p : nullptr;
+  }
+}
+
+template <int THREADS, int NL>
+__device__ __forceinline__ void direct_issue(const uint8_t* const (&src)[NL], long byte_advance, uint8_t* tile) {
+  const int wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int j = 0; j < NL; ++j) {
+    uint8_t* dst = tile + (j * THREADS + wave * 64) * 16;      // wave-uniform; lane l lands at dst + 16 l
+    if (src[j])
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + byte_advance),
+                                       US_LDS_PTR(void, dst), 16, 0, 0);
+  }
+}
+
+// LDS byte address of a pointer into the workgroup's LDS allocation.
+__device__ __forceinline__ uint32_t lds_addr(const uint8_t* p) {
+  return (uint32_t)(uintptr_t)US_LDS_PTR(const uint8_t, p);
+}
+
+// The transposing LDS reads are issued through inline assembly: the compiler cannot see what they
+// read and would otherwise order them after ALL pending direct-to-LDS loads (s_waitcnt vmcnt(0)),
+// which would serialise the pipeline.  It therefore does not count them either: every consumer of a
+// fragment first passes through frag_ready() below.
+template <int OFFSET>
+__device__ __forceinline__ v2i ds_read_tr8(uint32_t addr) {
+  v2i v;
+  asm volatile("ds_read_b64_tr_b8 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET));
+  return v;
+}
+template <int OFFSET>
+__device__ __forceinline__ v2i ds_read_tr16(uint32_t addr) {
+  v2i v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET));
+  return v;
+}
+// Wait for every LDS read issued so far and tie the fragment registers to that wait, so that no use
+// of them can be scheduled above it.
+__device__ __forceinline__ void lds_reads_done() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+template <class F, int N>
+__device__ __forceinline__ void frag_ready(F (&f)[N]) {
+#pragma unroll
+  for (int i = 0; i < N; ++i) asm volatile("" : "+v"(f[i]));
+}
+
+// Fragment = 32 rows (r0..r0+31) x one MFMA's worth of k, number `kstep` within the stage.  Lane l
+// supplies row r0 + l%32 and the k-half l/32 (FP8: 32 consecutive k; FP16: 8 consecutive k).
+template <bool KC, int PITCH>
+__device__ __forceinline__ v8i direct_frag_fp8(const uint8_t* tile, int r0, int kstep) {
+  const int l = threadIdx.x & 63;
+  v8i f;
+  if constexpr (KC) {
+    const int r = r0 + (l & 31);
+    const int c = kstep * 4 + (l >> 5) * 2;
+    const int x = swz<true, true, PITCH>(r);
+    const uint8_t* p = tile + r * PITCH;
+    v4i lo = *US_LDS_PTR(const v4i, p + ((c ^ x) << 4));
+    v4i hi = *US_LDS_PTR(const v4i, p + (((c + 1) ^ x) << 4));
+    f = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+  } else {
+    // 16 lanes cooperate on an 8(k) x 16(row) byte block: lane i points at k-row i/2, row-half i%2,
+    // and receives the 8 k values of row (group base + i).  The swizzle only depends on k mod 8
+    // (or (k/2) mod 4), which the four reads of a lane share.
+    const int i = l & 15;
+    const int krow = kstep * 64 + (l >> 5) * 32 + (i >> 1);
+    const int col = r0 + ((l >> 4) & 1) * 16 + (i & 1) * 8;
+    const uint32_t a = lds_addr(tile + krow * PITCH + (((col >> 4) ^ swz<false, true, PITCH>(krow)) << 4) + (col & 15));
+    const v2i v0 = ds_read_tr8<0>(a), v1 = ds_read_tr8<8 * PITCH>(a), v2 = ds_read_tr8<16 * PITCH>(a),
+              v3 = ds_read_tr8<24 * PITCH>(a);
+    f = {v0.x, v0.y, v1.x, v1.y, v2.x, v2.y, v3.x, v3.y};
+  }
+  return f;
+}
+
+template <bool KC, int PITCH>
+__device__ __forceinline__ v8h direct_frag_f16(const uint8_t* tile, int r0, int kstep) {
+  const int l = threadIdx.x & 63;
+  if constexpr (KC) {
+    const int r = r0 + (l & 31);
+    const int c = kstep * 2 + (l >> 5);
+    return *US_LDS_PTR(const v8h, tile + r * PITCH + ((c ^ swz<true, false, PITCH>(r)) << 4));
+  } else {
+    // 16 lanes cooperate on a 4(k) x 16(row) block of halves: lane i points at k-row i/4, row quarter
+    // i%4, and receives the 4 k values of row (group base + i).
+    const int i = l & 15;
+    const int krow = kstep * 16 + (l >> 5) * 8 + (i >> 2);
+    const int colb = (r0 + ((l >> 4) & 1) * 16 + (i & 3) * 4) * 2;
+    const uint32_t a = lds_addr(tile + krow * PITCH + (((colb >> 4) ^ swz<false, false, PITCH>(krow)) << 4) + (colb & 15));
+    const v2i lo = ds_read_tr16<0>(a), hi = ds_read_tr16<4 * PITCH>(a);
+    v4i w = {lo.x, lo.y, hi.x, hi.y};
+    v8h h;
+    __builtin_memcpy(&h, &w, 16);
+    return h;
+  }
+}
+
+// s_waitcnt vmcnt(N) alone (lgkmcnt / expcnt fields left at "no wait")
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+template <class Cfg, bool FP8, int FA, int FB, bool A_KC, bool B_KC, int EPI, bool WIDE>
+__global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_direct_kernel(GemmArgs g) {
+  using T = DirectTile<Cfg, FP8, A_KC, B_KC, WIDE>;
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, THREADS = Cfg::THREADS, BKB = Cfg::BKB, NST = Cfg::NST;
+  constexpr int FM = Cfg::FM, FN = Cfg::FN;
+  constexpr int ES = T::ES;
+  constexpr int KSTEPS = FP8 ? BKB / 64 : BKB / 32;
+  constexpr int PA = T::PA, PB = T::PB;
+  constexpr int LOADS = T::A_LOADS + T::B_LOADS;       // per thread and stage
+
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+  const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
+  int tm, tn;
+  tile_of_block((int)blockIdx.x, tiles_m, tiles_n, g.xcd_gm, g.xcd_gn, tm, tn);
+  const long m0 = (long)tm * BM, n0 = (long)tn * BN;
+  const long split = blockIdx.y;
+  const long k_begin = split * g.k_per_split;
+  const long k_end = (k_begin + g.k_per_split < g.K) ? k_begin + g.k_per_split : g.K;
+  const int nstages = (k_end > k_begin) ? (int)((k_end - k_begin) / T::BK) : 0;   // host guarantees divisibility
+
+  const int wave = threadIdx.x >> 6;
+  const int wm0 = (wave % Cfg::WAVES_M) * Cfg::WM;
+  const int wn0 = (wave / Cfg::WAVES_M) * Cfg::WN;
+
+  // edge tiles: slots that are never loaded must read as zero
+  const bool edge = (m0 + BM > g.M || n0 + BN > g.N);
+  if (edge) {
+    const v4i z = {0, 0, 0, 0};
+    for (int o = threadIdx.x * 16; o < T::RING_BYTES; o += THREADS * 16) *US_LDS_PTR(v4i, lds + o) = z;
+    __syncthreads();
+  }
+
+  const uint8_t* srcA[T::A_LOADS];
+  const uint8_t* srcB[T::B_LOADS];
+  direct_sources<THREADS, BM, BKB, A_KC, FP8, PA>(g.A, g.lda, m0, g.M, k_begin, srcA);
+  direct_sources<THREADS, BN, BKB, B_KC, FP8, PB>(g.B, g.ldb, n0, g.N, k_begin, srcB);
+  const long advA = A_KC ? (long)BKB : (long)T::BK * g.lda * ES;   // bytes per stage
+  const long advB = B_KC ? (long)BKB : (long)T::BK * g.ldb * ES;
+
+  v16f acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  // fragment registers, two sets: one feeds the MFMAs while the other is being filled
+  using FragT = typename std::conditional<FP8, v8i, v8h>::type;
+  FragT fa[2][FM], fb[2][FN];
+  auto load_frags = [&](FragT (&a)[FM], FragT (&b)[FN], int slot, int ks) {
+    const uint8_t* ta = lds + slot * T::STAGE_BYTES;
+    const uint8_t* tb = ta + T::A_BYTES;
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      if constexpr (FP8) b[j] = direct_frag_fp8<B_KC, PB>(tb, wn0 + j * 32, ks);
+      else b[j] = direct_frag_f16<B_KC, PB>(tb, wn0 + j * 32, ks);
+    }
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      if constexpr (FP8) a[i] = direct_frag_fp8<A_KC, PA>(ta, wm0 + i * 32, ks);
+      else a[i] = direct_frag_f16<A_KC, PA>(ta, wm0 + i * 32, ks);
+    }
+  };
+  auto issue_stage = [&](int stage, int slot) {
+    direct_issue<THREADS>(srcA, (long)stage * advA, lds + slot * T::STAGE_BYTES);
+    direct_issue<THREADS>(srcB, (long)stage * advB, lds + slot * T::STAGE_BYTES + T::A_BYTES);
+  };
+
+  // prologue: fill the ring, open stage 0, fetch its first fragments
+#pragma unroll
+  for (int s = 0; s < NST; ++s)
+    if (s < nstages) issue_stage(s, s);
+  if (nstages > 0) {
+    // (on edge tiles a wave may skip loads whose lanes all lie outside the matrix, so the number of
+    // younger loads is not fixed there: wait for everything)
+    if (!edge && nstages >= NST) wait_vmcnt<(NST - 1) * LOADS>();
+    else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    load_frags(fa[0], fb[0], 0, 0);
+  }
+
+  int slot = 0;            // ring slot of stage s
+  for (int s = 0; s < nstages; ++s) {
+    int next_slot = slot + 1;
+    if (next_slot == NST) next_slot = 0;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      FragT (&ca)[FM] = fa[ks & 1];
+      FragT (&cb)[FN] = fb[ks & 1];
+      FragT (&na)[FM] = fa[(ks + 1) & 1];
+      FragT (&nb)[FN] = fb[(ks + 1) & 1];
+      // the fragments of this k-step were requested one k-step ago
+      lds_reads_done();
+      frag_ready(ca);
+      frag_ready(cb);
+      if (ks + 1 < KSTEPS) {
+        load_frags(na, nb, slot, ks + 1);
+      } else {
+        // stage boundary: this wave holds all of stage s in registers
+        if (s + 1 < nstages) {
+          // own loads of stage s+1 have landed once only the NST-2 younger stages are pending
+          if (!edge && s + NST <= nstages) wait_vmcnt<(NST - 2) * LOADS>();
+          else wait_vmcnt<0>();
+        }
+        __builtin_amdgcn_s_barrier();   // stage s+1 complete for everyone; nobody reads stage s any more
+        if (s + NST < nstages) issue_stage(s + NST, slot);
+        if (s + 1 < nstages) load_frags(na, nb, next_slot, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);   // keep the LDS requests ahead of the MFMAs they overlap with
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+          if constexpr (FP8) acc[i][j] = mfma_fp8<FB, FA>(cb[j], ca[i], acc[i][j]);
+          else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(cb[j], ca[i], acc[i][j], 0, 0, 0);
+        }
+      __builtin_amdgcn_sched_barrier(0);   // ... and the MFMAs ahead of the next k-step's wait
+    }
+    slot = next_slot;
+  }
+
+  __syncthreads();       // every wave is past its last fragment read before the strips overlay the ring
+  store_block_epilogue<Cfg, EPI, WIDE>(g, acc, lds, m0, n0, split);
+}
+
+}  // namespace us

@@ -1,14 +1,29 @@
-// Host-side selection of tile shape and epilogue for one (operand layout, operand type) family.
-// Each family is instantiated in its own translation unit to keep compile times short.
+// Host-side selection of kernel, tile shape and epilogue for one (operand layout, operand type)
+// family.  Each family is instantiated in its own translation unit to keep compile times short.
 #pragma once
 
-#include "us_gemm_kernel.h"
+#include "us_gemm_direct.h"
+#include "us_gemm_staged.h"
 #include "us_launch.h"
 
 namespace us {
 
-inline GemmArgs make_args(const GemmProblem& p, long k_per_split) {
-  GemmArgs g;
+// Tile configurations  <BM, BN, WAVES_M, WAVES_N, BKB, NST, MINB>
+//   D256: 8 waves (2 x 4, 128 x 64 accumulators per wave), one workgroup per CU, 128 KB of LDS ring
+//   D128: 4 waves (2 x 2, 64 x 64 per wave), two workgroups per CU, 64 KB ring
+//   S128: the register-staged kernel for reduction lengths that are not a multiple of the stage
+using CfgD256 = GemmCfg<256, 256, 2, 4, 128, 2, 1>;
+using CfgD128 = GemmCfg<128, 128, 2, 2, 128, 2, 2>;
+using CfgS128 = GemmCfg<128, 128, 2, 2, 128, 2, 2>;
+
+inline long ceil_div(long a, long b) { return (a + b - 1) / b; }
+
+// The large tile needs the output to cover the 256 CUs about one and a half times; below that the
+// small tile (two workgroups per CU, four times as many tiles) keeps more of the chip busy.
+inline bool use_big_tile(long M, long N, int splits) { return ceil_div(M, 256) * ceil_div(N, 256) * splits >= 384; }
+
+inline GemmArgs make_args(const GemmProblem& p, long k_per_split, int BM, int BN) {
+  GemmArgs g{};
   g.A = (const uint8_t*)p.A;
   g.B = (const uint8_t*)p.B;
   g.C = p.C;
@@ -17,41 +32,48 @@ inline GemmArgs make_args(const GemmProblem& p, long k_per_split) {
   g.k_per_split = k_per_split;
   g.scale = p.scale;
   g.epi_scale = p.epi_scale;
-  g.c_is_f32 = (p.c_dt == US_F32) ? 1 : 0;
   g.Zpre = (const _Float16*)p.Zpre;
   g.aux16 = (_Float16*)p.aux16;
   g.aux8 = (uint8_t*)p.aux8;
   g.partial = (float*)p.workspace;
+  choose_xcd_grid(ceil_div(p.M, BM), ceil_div(p.N, BN), g.xcd_gm, g.xcd_gn);
   return g;
 }
 
-template <int BM, int BN, bool FP8, int FA, int FB, bool A_KC, bool B_KC, int EPI>
-hipError_t launch_one(const GemmArgs& g, int splits, hipStream_t st) {
-  using T = GemmTile<BM, BN, FP8, A_KC, B_KC>;
-  auto kern = gemm_kernel<BM, BN, 2, 2, FP8, FA, FB, A_KC, B_KC, EPI>;
+template <bool DIRECT, class Cfg, bool FP8, int FA, int FB, bool A_KC, bool B_KC, int EPI, bool WIDE>
+hipError_t launch_one(const GemmProblem& p, int splits, long k_per_split, hipStream_t st) {
+  constexpr int LDS = DIRECT ? DirectTile<Cfg, FP8, A_KC, B_KC, WIDE>::LDS_BYTES
+                             : StagedTile<Cfg, FP8, A_KC, B_KC, WIDE>::LDS_BYTES;
+  auto kern = DIRECT ? gemm_direct_kernel<Cfg, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>
+                     : gemm_staged_kernel<Cfg, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>;
   static bool configured = false;  // raising the dynamic-LDS limit is a per-function, once-only call
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  const long tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  const GemmArgs g = make_args(p, k_per_split, Cfg::BM, Cfg::BN);
+  const long tiles = ceil_div(p.M, Cfg::BM) * ceil_div(p.N, Cfg::BN);
   dim3 grid((unsigned)tiles, (unsigned)splits, 1);
-  kern<<<grid, kGemmThreads, T::LDS_BYTES, st>>>(g);
+  kern<<<grid, Cfg::THREADS, LDS, st>>>(g);
   return hipGetLastError();
 }
 
-// Large tiles once they fill the 256 CUs; small tiles for small problems.
-inline bool use_big_tile(long M, long N, int splits) {
-  const long big = ((M + 255) / 256) * ((N + 255) / 256) * splits;
-  return big >= 192;
+template <bool FP8, int FA, int FB, bool A_KC, bool B_KC, int EPI, bool WIDE>
+hipError_t launch_sized(const GemmProblem& p, int splits, long k_per_split, hipStream_t st) {
+  const long bk = FP8 ? 128 : 64;                       // elements of K per stage of the direct kernels
+  const bool direct_ok = p.K > 0 && p.K % bk == 0;      // slice lengths are multiples of 128 already
+  if (!direct_ok) return launch_one<false, CfgS128, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
+  if (use_big_tile(p.M, p.N, splits))
+    return launch_one<true, CfgD256, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
+  return launch_one<true, CfgD128, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
 }
 
-template <bool FP8, int FA, int FB, bool A_KC, bool B_KC, int EPI>
-hipError_t launch_sized(const GemmProblem& p, int splits, long k_per_split, hipStream_t st) {
-  GemmArgs g = make_args(p, k_per_split);
-  if (use_big_tile(p.M, p.N, splits)) return launch_one<256, 256, FP8, FA, FB, A_KC, B_KC, EPI>(g, splits, st);
-  return launch_one<128, 128, FP8, FA, FB, A_KC, B_KC, EPI>(g, splits, st);
+// Plain store epilogue: FP16 or FP32 output.
+template <bool FP8, int FA, int FB, bool A_KC, bool B_KC>
+hipError_t launch_store(const GemmProblem& p, hipStream_t st) {
+  if (p.c_dt == US_F32) return launch_sized<FP8, FA, FB, A_KC, B_KC, EPI_STORE, true>(p, 1, p.K, st);
+  return launch_sized<FP8, FA, FB, A_KC, B_KC, EPI_STORE, false>(p, 1, p.K, st);
 }
 
 hipError_t launch_splitk_reduce(const float* partial, void* out, long total, int splits, float scale, bool out_is_f32,

@@ -4,8 +4,8 @@
 namespace us {
 
 hipError_t gemm_nn_f16(const GemmProblem& p, hipStream_t st) {
-  if (p.epi == US_EPI_GELU) return launch_sized<false, 0, 0, true, false, EPI_GELU>(p, 1, p.K, st);
-  return launch_sized<false, 0, 0, true, false, EPI_STORE>(p, 1, p.K, st);
+  if (p.epi == US_EPI_GELU) return launch_sized<false, 0, 0, true, false, EPI_GELU, false>(p, 1, p.K, st);
+  return launch_store<false, 0, 0, true, false>(p, st);
 }
 
 }  // namespace us

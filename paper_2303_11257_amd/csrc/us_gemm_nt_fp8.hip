@@ -4,8 +4,8 @@
 namespace us {
 
 hipError_t gemm_nt_fp8(const GemmProblem& p, hipStream_t st) {
-  if (p.epi == US_EPI_GELU_GRAD) return launch_sized<true, 1, 0, true, true, EPI_GELU_GRAD>(p, 1, p.K, st);
-  return launch_sized<true, 1, 0, true, true, EPI_STORE>(p, 1, p.K, st);
+  if (p.epi == US_EPI_GELU_GRAD) return launch_sized<true, 1, 0, true, true, EPI_GELU_GRAD, false>(p, 1, p.K, st);
+  return launch_store<true, 1, 0, true, true>(p, st);
 }
 
 }  // namespace us

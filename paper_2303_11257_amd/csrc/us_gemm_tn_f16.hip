@@ -6,10 +6,9 @@ namespace us {
 
 hipError_t gemm_tn_f16(const GemmProblem& p, hipStream_t st) {
   const int splits = p.workspace ? gemm_splits(p.M, p.N, p.K) : 1;
-  if (splits <= 1) return launch_sized<false, 0, 0, false, false, EPI_STORE>(p, 1, p.K, st);
-  const long unit = 128;
-  const long k_per_split = ((p.K + splits - 1) / splits + unit - 1) / unit * unit;
-  hipError_t e = launch_sized<false, 0, 0, false, false, EPI_PARTIAL>(p, splits, k_per_split, st);
+  if (splits <= 1) return launch_store<false, 0, 0, false, false>(p, st);
+  const long k_per_split = gemm_k_per_split(p.K, splits);
+  hipError_t e = launch_sized<false, 0, 0, false, false, EPI_PARTIAL, true>(p, splits, k_per_split, st);
   if (e != hipSuccess) return e;
   return launch_splitk_reduce((const float*)p.workspace, p.C, p.M * p.N, splits, p.scale, p.c_dt == US_F32, st);
 }

@@ -42,6 +42,7 @@ struct GemmProblem {
 
 // Number of K slices the dW reduction is cut into, and the scratch it needs (0 when 1 slice).
 int gemm_splits(long M, long N, long K);
+long gemm_k_per_split(long K, int splits);
 size_t gemm_workspace_bytes(long M, long N, long K);
 
 hipError_t launch_gemm(const GemmProblem& p, hipStream_t stream);
