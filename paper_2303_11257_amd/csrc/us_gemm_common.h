@@ -24,7 +24,8 @@ struct GemmArgs {
   _Float16* aux16;       // EPI_GELU: optional FP16 activation output
   uint8_t* aux8;         // optional FP8 copy of the epilogue's FP16 result
   float* partial;        // EPI_PARTIAL: [splits][M][N] FP32
-  int xcd_gm, xcd_gn;    // XCD rectangle split of the tile grid (0,0 = linear order)
+  int xcd_gm, xcd_gn;    // XCD rectangle split of the tile grid (0,0 = one rectangle)
+  int grp_w;             // width of the column bands the rectangle is walked in
 };
 
 // Tile configuration.  BKB = bytes of K per row and pipeline stage; NST = LDS stage buffers;
@@ -49,18 +50,26 @@ __device__ __forceinline__ v16f mfma_fp8(v8i a, v8i b, v16f c) {
 // ---- workgroup -> output tile ------------------------------------------------------------------------
 // Workgroups are handed to the 8 XCDs round-robin by linear id, and every XCD has its own L2.  When
 // the tile grid divides evenly (host: choose_xcd_grid), XCD x gets a compact rectangle of
-// (tiles_m/gm) x (tiles_n/gn) tiles, so the A and B panels it touches are shared inside one L2, and
-// walks it M-fastest; with gm == 0 the plain M-fastest order is used.
-__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int gm, int gn, int& tm, int& tn) {
-  if (gm == 0) {
-    tm = bid % tiles_m;
-    tn = bid / tiles_m;
-    return;
+// (tiles_m/gm) x (tiles_n/gn) tiles; with gm == 0 the whole grid is one rectangle.  Inside a
+// rectangle the tiles are walked in column bands `grp_w` tiles wide, N-fastest within a band, so the
+// ~32-64 workgroups that run at the same time on one XCD form a compact block and share the A and B
+// panels they stream through that XCD's L2.
+__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int gm, int gn, int grp_w, int& tm,
+                                              int& tn) {
+  int rm = tiles_m, rn = tiles_n, base_m = 0, base_n = 0, idx = bid;
+  if (gm != 0) {
+    const int xcd = bid & 7;
+    idx = bid >> 3;
+    rm = tiles_m / gm;
+    rn = tiles_n / gn;
+    base_m = (xcd % gm) * rm;
+    base_n = (xcd / gm) * rn;
   }
-  const int xcd = bid & 7, idx = bid >> 3;
-  const int rm = tiles_m / gm, rn = tiles_n / gn;
-  tm = (xcd % gm) * rm + idx % rm;
-  tn = (xcd / gm) * rn + idx / rm;
+  const int band = idx / (rm * grp_w);
+  const int r = idx - band * rm * grp_w;
+  const int w = (rn - band * grp_w < grp_w) ? rn - band * grp_w : grp_w;   // last band may be narrower
+  tm = base_m + r / w;
+  tn = base_n + band * grp_w + r % w;
 }
 
 // Host side: the split gm x gn = 8 that divides the tile grid and minimises the number of operand

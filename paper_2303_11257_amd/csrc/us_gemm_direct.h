@@ -39,8 +39,9 @@ struct DirectTile {
   static constexpr int EPI_BYTES = EpiStrip<Cfg, WIDE>::BYTES;
   static constexpr int LDS_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
   static_assert(A_BYTES % (16 * Cfg::THREADS) == 0 && B_BYTES % (16 * Cfg::THREADS) == 0, "whole wave loads only");
-  static_assert(Cfg::NST >= 2 && Cfg::NST <= 4, "");
-  static_assert((FP8 ? Cfg::BKB / 64 : Cfg::BKB / 32) % 2 == 0, "an even number of k-steps per stage (register double buffer)");
+  static_assert(Cfg::NST >= 2 && Cfg::NST <= 5, "");
+  static_assert(Cfg::BKB == 64 || Cfg::BKB == 128, "");
+  static_assert(LDS_BYTES <= 160 * 1024, "the ring must fit the CU's 160 KB of LDS");
 };
 
 // XOR mask on the 16-byte chunk index of LDS row `row` (see the bank analysis in the file header of the
@@ -121,6 +122,20 @@ __device__ __forceinline__ void frag_ready(F (&f)[N]) {
   for (int i = 0; i < N; ++i) asm volatile("" : "+v"(f[i]));
 }
 
+// One of this thread's loads of a stage: number j of the A tile's NA loads, then the B tile's.
+template <int THREADS, int NA, int NB>
+__device__ __forceinline__ void direct_issue_one(int j, const uint8_t* const (&srcA)[NA], const uint8_t* const (&srcB)[NB],
+                                                 long advA, long advB, uint8_t* stage_base, int a_bytes) {
+  const int wave = threadIdx.x >> 6;
+  const bool is_a = j < NA;
+  const int jj = is_a ? j : j - NA;
+  const uint8_t* src = is_a ? srcA[jj] : srcB[jj];
+  uint8_t* dst = stage_base + (is_a ? 0 : a_bytes) + (jj * THREADS + wave * 64) * 16;
+  if (src)
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + (is_a ? advA : advB)),
+                                     US_LDS_PTR(void, dst), 16, 0, 0);
+}
+
 // Fragment = 32 rows (r0..r0+31) x one MFMA's worth of k, number `kstep` within the stage.  Lane l
 // supplies row r0 + l%32 and the k-half l/32 (FP8: 32 consecutive k; FP16: 8 consecutive k).
 template <bool KC, int PITCH>
@@ -193,7 +208,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_direct_kernel(Ge
 
   const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
   int tm, tn;
-  tile_of_block((int)blockIdx.x, tiles_m, tiles_n, g.xcd_gm, g.xcd_gn, tm, tn);
+  tile_of_block((int)blockIdx.x, tiles_m, tiles_n, g.xcd_gm, g.xcd_gn, g.grp_w, tm, tn);
   const long m0 = (long)tm * BM, n0 = (long)tn * BN;
   const long split = blockIdx.y;
   const long k_begin = split * g.k_per_split;
@@ -262,16 +277,22 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_direct_kernel(Ge
     load_frags(fa[0], fb[0], 0, 0);
   }
 
-  int slot = 0;            // ring slot of stage s
-  for (int s = 0; s < nstages; ++s) {
-    int next_slot = slot + 1;
-    if (next_slot == NST) next_slot = 0;
+  // The two fragment sets alternate per k-step.  With an odd number of k-steps per stage (one) the
+  // loop body therefore spans two stages, so that the set index stays a compile-time constant.
+  constexpr int SPI = (KSTEPS % 2) ? 2 : 1;     // stages per loop iteration
+  int slot = 0;                                 // ring slot of the current stage
+  bool refill = false;
+  int refill_slot = 0, refill_stage = 0;
+  for (int s0 = 0; s0 < nstages; s0 += SPI) {
 #pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-      FragT (&ca)[FM] = fa[ks & 1];
-      FragT (&cb)[FN] = fb[ks & 1];
-      FragT (&na)[FM] = fa[(ks + 1) & 1];
-      FragT (&nb)[FN] = fb[(ks + 1) & 1];
+    for (int u = 0; u < SPI * KSTEPS; ++u) {
+      const int s = s0 + u / KSTEPS;
+      const int ks = u % KSTEPS;
+      if (SPI > 1 && s >= nstages) break;       // odd stage count: the last iteration is half empty
+      FragT (&ca)[FM] = fa[u & 1];
+      FragT (&cb)[FN] = fb[u & 1];
+      FragT (&na)[FM] = fa[(u + 1) & 1];
+      FragT (&nb)[FN] = fb[(u + 1) & 1];
       // the fragments of this k-step were requested one k-step ago
       lds_reads_done();
       frag_ready(ca);
@@ -286,20 +307,36 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_direct_kernel(Ge
           else wait_vmcnt<0>();
         }
         __builtin_amdgcn_s_barrier();   // stage s+1 complete for everyone; nobody reads stage s any more
-        if (s + NST < nstages) issue_stage(s + NST, slot);
-        if (s + 1 < nstages) load_frags(na, nb, next_slot, 0);
+        refill = (s + NST < nstages);   // the freed slot receives stage s+NST, a few loads per MFMA below
+        refill_slot = slot;
+        refill_stage = s + NST;
+        if (++slot == NST) slot = 0;
+        if (s + 1 < nstages) load_frags(na, nb, slot, 0);
       }
       __builtin_amdgcn_sched_barrier(0);   // keep the LDS requests ahead of the MFMAs they overlap with
+      // The refill loads are spread over the MFMAs of this k-step: issued in one burst by all waves
+      // they would queue up in the vector-memory pipeline and hold the waves back from the matrix core.
+      constexpr int NMFMA = FM * FN;
+      constexpr int PER = (LOADS + NMFMA - 1) / NMFMA;
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
           if constexpr (FP8) acc[i][j] = mfma_fp8<FB, FA>(cb[j], ca[i], acc[i][j]);
           else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(cb[j], ca[i], acc[i][j], 0, 0, 0);
+          if (ks + 1 == KSTEPS) {
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+              const int l = (i * FN + j) * PER + q;
+              if (l < LOADS && refill)
+                direct_issue_one<THREADS>(l, srcA, srcB, (long)refill_stage * advA, (long)refill_stage * advB,
+                                          lds + refill_slot * T::STAGE_BYTES, T::A_BYTES);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
         }
       __builtin_amdgcn_sched_barrier(0);   // ... and the MFMAs ahead of the next k-step's wait
     }
-    slot = next_slot;
   }
 
   __syncthreads();       // every wave is past its last fragment read before the strips overlay the ring
