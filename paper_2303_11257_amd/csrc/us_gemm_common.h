@@ -107,9 +107,10 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
   }
   if (g.aux8) {
     // FP8 copy of the FP16 value just stored: identical to casting the stored tensor afterwards
+    const v2h p0 = {r[0], r[1]}, p1 = {r[2], r[3]}, p2 = {r[4], r[5]}, p3 = {r[6], r[7]};
     v2i w;
-    w.x = (int)cvt4_fp8<AUX_FMT>((float)r[0], (float)r[1], (float)r[2], (float)r[3]);
-    w.y = (int)cvt4_fp8<AUX_FMT>((float)r[4], (float)r[5], (float)r[6], (float)r[7]);
+    w.x = (int)(cvt_pk_fp8_from_half<AUX_FMT>(p0) | (cvt_pk_fp8_from_half<AUX_FMT>(p1) << 16));
+    w.y = (int)(cvt_pk_fp8_from_half<AUX_FMT>(p2) | (cvt_pk_fp8_from_half<AUX_FMT>(p3) << 16));
     *reinterpret_cast<v2i*>(g.aux8 + idx) = w;
   }
 }

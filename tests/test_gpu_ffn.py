@@ -154,3 +154,44 @@ def test_c5_llm_size_fp8_sampled():
     run = FfnRun(X, W1, W2, G, fp8=True)
     check_ffn(run, _sample(T, 6, 7), _sample(f, 3, 8), _sample(d, 3, 9))
     _variances(run)
+
+
+def test_hip_graph_replays_match_eager():
+    """The whole step (casts + FFN forward + backward) captured in a HIP graph: every replay, with
+    eager work and synchronisations in between, reproduces the eager result bit for bit."""
+    T, d, f = 512, 256, 1024
+    X, W1, W2, G = synth.ffn_inputs(T, d, f, seed=131)
+    eager = FfnRun(X, W1, W2, G, fp8=True)
+    names = ("Z", "H", "Y", "dZ16", "dZ8", "dX", "dW1", "dW2")
+    want = {k: eager.full(k) for k in names}
+    dev = eager.dev
+    wsb = us.ffn_workspace_bytes(T, d, f)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=DEV)
+
+    def step():
+        st = stream()
+        for k, fmt in (("X", us.E4M3), ("W1", us.E4M3), ("W2", us.E4M3), ("G", us.E5M2)):
+            us.cast_fp8(ptr(dev[k]), us.F16, ptr(dev[k + "op"]), fmt, dev[k].numel(), 1.0, None, st)
+        us.ffn_fwd(ptr(dev["Xop"]), ptr(dev["W1op"]), ptr(dev["W2op"]), ptr(dev["Z"]), ptr(dev["H"]), ptr(dev["Y"]),
+                   T, d, f, True, st)
+        us.ffn_bwd(ptr(dev["Xop"]), ptr(dev["W1op"]), ptr(dev["W2op"]), ptr(dev["Z"]), ptr(dev["H"]), ptr(dev["Gop"]),
+                   ptr(dev["dZ16"]), ptr(dev["dZ8"]), ptr(dev["dX"]), ptr(dev["dW1"]), ptr(dev["dW2"]), T, d, f, True,
+                   ptr(ws), wsb, st)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(4):
+        for k in names:                                   # eager work between replays: wipe the outputs
+            dev[k].zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in names:
+            assert np.array_equal(dev[k].cpu().numpy(), want[k]), (rep, k)
