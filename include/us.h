@@ -89,7 +89,10 @@ us_status us_cast_fp8(const void* src, us_dtype src_dt, void* dst, us_dtype dst_
  * stores H to aux16 (FP16 [b,n]) if aux16 != NULL and the E4M3 cast of that FP16 H (scale 1) to aux8
  * ([b,n] bytes) if aux8 != NULL; at least one of them must be given.  epi_scale <= 0 selects the
  * unit-scaling factor 1.7009.  Y itself is always written (the backward pass needs it).
- * workspace is unused by the forward pass and may be NULL.
+ * workspace may be NULL.  With FP8 operands, epi = US_EPI_GELU, aux16 == NULL and a workspace of at
+ * least 128 KB (16-byte aligned, contents undefined on entry and exit) large problems take the
+ * activation codes from a table over the 65536 possible FP16 values of Y that is first built in the
+ * workspace; the result is the same as without a workspace.
  */
 us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, long n,
                         us_dtype x_dt, us_dtype w_dt, us_dtype y_dt, float alpha,
@@ -108,9 +111,11 @@ us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, l
  *   dX = fp16( epi_scale * gelu'(Zpre) * fp16(beta_x * G W^T) ),  gelu'(z) = Phi(z) + z*phi(z),
  * i.e. the scaled-GELU backward of Sec. 5.1 applied to the FP16-rounded matmul gradient; if aux8 !=
  * NULL the E5M2 cast of the stored FP16 dX is written there.  epi_scale <= 0 selects 1.4811.
- * dW is reduced over the b tokens in slices; when us_workspace_bytes(b, m, n) is non-zero the
- * caller must pass a workspace of at least that many bytes (16-byte aligned, contents undefined
- * on entry and exit).
+ * Workspace (16-byte aligned, contents undefined on entry and exit): us_workspace_bytes(b, m, n) is
+ * the size that serves every use.  Its first 128 KB hold the table of the table-driven GELU' epilogue
+ * (same results as the arithmetic one; used for large problems when at least 128 KB are given), the
+ * rest the FP32 slices of the dW reduction over tokens.  A workspace is REQUIRED only when dW needs
+ * slices, i.e. when us_workspace_bytes(b, m, n) > 128 KB: then fewer bytes give US_ERR_WORKSPACE.
  */
 us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, void* dW,
                         long b, long m, long n, us_dtype x_dt, us_dtype w_dt, us_dtype g_dt,
@@ -118,7 +123,8 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
                         const void* Zpre, void* aux8, void* workspace, size_t workspace_bytes,
                         void* stream);
 
-/* Bytes of workspace us_linear_bwd needs for the dW of a [b,m] x [b,n] problem (0 if none). */
+/* Bytes of workspace that serve every use by us_linear_fwd / us_linear_bwd for a [b,m] x [m,n] layer:
+ * 128 KB of table area plus the dW slices (0 for a non-positive dimension). */
 size_t us_workspace_bytes(long b, long m, long n);
 
 /*
@@ -147,10 +153,11 @@ us_status us_gelu_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtyp
  *              dX = fp16(f^-1/2 dZ W1^T);  dW1 = fp16(T^-1/2 X^T dZ)
  *   G [T,d]: F16 or E5M2;  dZ16 [T,f] F16 out;  dZ8 [T,f] E5M2 out (fp8 != 0 only, else ignored)
  *   dX [T,d], dW1 [d,f], dW2 [f,d] F16 out
- *   workspace: at least us_ffn_workspace_bytes(T, d, f) bytes.
+ *   workspace: us_ffn_workspace_bytes(T, d, f) bytes serve both calls (optional for us_ffn_fwd, where it
+ *   only enables the table-driven GELU; required for us_ffn_bwd whenever a dW needs slices).
  */
 us_status us_ffn_fwd(const void* X, const void* W1, const void* W2, void* Z, void* H, void* Y,
-                     long T, long d, long f, int fp8, void* stream);
+                     long T, long d, long f, int fp8, void* workspace, size_t workspace_bytes, void* stream);
 us_status us_ffn_bwd(const void* X, const void* W1, const void* W2, const void* Z, const void* H,
                      const void* G, void* dZ16, void* dZ8, void* dX, void* dW1, void* dW2,
                      long T, long d, long f, int fp8, void* workspace, size_t workspace_bytes,

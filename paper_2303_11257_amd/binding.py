@@ -49,7 +49,7 @@ def lib() -> ctypes.CDLL:
     L.us_workspace_bytes.restype = sz
     L.us_gelu_fwd.argtypes = [vp, vp, sz, i, f, vp]
     L.us_gelu_bwd.argtypes = [vp, vp, vp, sz, i, f, vp]
-    L.us_ffn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, l, l, l, i, vp]
+    L.us_ffn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, l, l, l, i, vp, sz, vp]
     L.us_ffn_bwd.argtypes = [vp] * 11 + [l, l, l, i, vp, sz, vp]
     L.us_ffn_workspace_bytes.argtypes = [l, l, l]
     L.us_ffn_workspace_bytes.restype = sz
@@ -103,8 +103,8 @@ def gelu_bwd(z, gh, gz, n, dt=F16, beta_g=0.0, stream=None):
     _check(lib().us_gelu_bwd(z, gh, gz, n, dt, beta_g, stream), "us_gelu_bwd")
 
 
-def ffn_fwd(X, W1, W2, Z, H, Y, T, d, f, fp8, stream=None):
-    _check(lib().us_ffn_fwd(X, W1, W2, Z, H, Y, T, d, f, int(fp8), stream), "us_ffn_fwd")
+def ffn_fwd(X, W1, W2, Z, H, Y, T, d, f, fp8, workspace=None, workspace_bytes=0, stream=None):
+    _check(lib().us_ffn_fwd(X, W1, W2, Z, H, Y, T, d, f, int(fp8), workspace, workspace_bytes, stream), "us_ffn_fwd")
 
 
 def ffn_bwd(X, W1, W2, Z, H, G, dZ16, dZ8, dX, dW1, dW2, T, d, f, fp8, workspace=None, workspace_bytes=0, stream=None):

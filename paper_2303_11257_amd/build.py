@@ -17,6 +17,8 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-fno-gpu-flush-denormals-to-zero",                        # FP32 subnormals are part of the cast's contract
+    "-ffp-contract=off",                                       # only the fmas written in the source: the table-driven
+                                                               # and the arithmetic epilogues must round identically
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",  # no packed-FP32 VALU ops
     "-Wno-unused-command-line-argument",
 ]

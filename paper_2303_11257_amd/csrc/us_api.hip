@@ -73,14 +73,12 @@ us_status us_gelu_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtyp
 
 size_t us_workspace_bytes(long b, long m, long n) {
   if (b < 1 || m < 1 || n < 1) return 0;
-  return gemm_workspace_bytes(m, n, b);
+  return (size_t)kTableAreaBytes + gemm_workspace_bytes(m, n, b);
 }
 
 us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, long n, us_dtype x_dt, us_dtype w_dt,
                         us_dtype y_dt, float alpha, us_epilogue epi, float epi_scale, void* aux16, void* aux8,
                         void* workspace, size_t workspace_bytes, void* stream) {
-  (void)workspace;
-  (void)workspace_bytes;
   const bool f16 = (x_dt == US_F16 && w_dt == US_F16);
   const bool fp8 = (x_dt == US_E4M3 && w_dt == US_E4M3);
   if (!f16 && !fp8) return US_ERR_DTYPE;
@@ -91,7 +89,8 @@ us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, l
   if (b == 0 || n == 0) return US_OK;
   if (!Y || (m > 0 && (!X || !W))) return US_ERR_NULL;
   if (epi == US_EPI_GELU && !aux16 && !aux8) return US_ERR_NULL;
-  if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || !aligned16(aux16) || !aligned16(aux8)) return US_ERR_ALIGN;
+  if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || !aligned16(aux16) || !aligned16(aux8) || !aligned16(workspace))
+    return US_ERR_ALIGN;
   GemmProblem p{};
   p.A = X; p.B = W; p.C = Y;
   p.M = b; p.N = n; p.K = m;
@@ -103,6 +102,7 @@ us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, l
   p.epi_scale = (epi_scale > 0.0f) ? epi_scale : kGeluAlpha;
   p.aux16 = (epi == US_EPI_GELU) ? aux16 : nullptr;
   p.aux8 = (epi == US_EPI_GELU) ? aux8 : nullptr;
+  p.table = (workspace && workspace_bytes >= (size_t)kTableAreaBytes) ? workspace : nullptr;
   return from_hip(launch_gemm(p, as_stream(stream)));
 }
 
@@ -126,10 +126,10 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
   if (!aligned16(X) || !aligned16(W) || !aligned16(G) || !aligned16(dX) || !aligned16(dW) || !aligned16(Zpre) ||
       !aligned16(aux8) || !aligned16(workspace))
     return US_ERR_ALIGN;
-  if (do_dw) {
-    const size_t need = gemm_workspace_bytes(m, n, b);
-    if (need > 0 && (!workspace || workspace_bytes < need)) return US_ERR_WORKSPACE;
-  }
+  // workspace layout: [0, 128 KB) tables of the table-driven epilogues, then the dW slices
+  const size_t slices = do_dw ? gemm_workspace_bytes(m, n, b) : 0;
+  if (slices > 0 && (!workspace || workspace_bytes < (size_t)kTableAreaBytes + slices)) return US_ERR_WORKSPACE;
+  void* const table = (workspace && workspace_bytes >= (size_t)kTableAreaBytes) ? workspace : nullptr;
   hipStream_t st = as_stream(stream);
   if (do_dx) {
     GemmProblem p{};
@@ -143,6 +143,7 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
     p.epi_scale = (epi_scale > 0.0f) ? epi_scale : kGeluBeta;
     p.Zpre = (epi == US_EPI_GELU_GRAD) ? Zpre : nullptr;
     p.aux8 = (epi == US_EPI_GELU_GRAD) ? aux8 : nullptr;
+    p.table = table;
     hipError_t e = launch_gemm(p, st);
     if (e != hipSuccess) return US_ERR_LAUNCH;
   }
@@ -155,8 +156,8 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
     p.a_dt = x_dt; p.b_dt = g_dt; p.c_dt = out_dt;
     p.scale = (beta_w > 0.0f) ? beta_w : (float)(1.0 / sqrt((double)(b > 0 ? b : 1)));
     p.epi = US_EPI_NONE;
-    p.workspace = gemm_workspace_bytes(m, n, b) > 0 ? workspace : nullptr;
-    p.workspace_bytes = workspace_bytes;
+    p.workspace = slices > 0 ? (void*)((char*)workspace + kTableAreaBytes) : nullptr;
+    p.workspace_bytes = slices;
     hipError_t e = launch_gemm(p, st);
     if (e != hipSuccess) return US_ERR_LAUNCH;
   }
@@ -170,11 +171,11 @@ size_t us_ffn_workspace_bytes(long T, long d, long f) {
 }
 
 us_status us_ffn_fwd(const void* X, const void* W1, const void* W2, void* Z, void* H, void* Y, long T, long d, long f,
-                     int fp8, void* stream) {
+                     int fp8, void* workspace, size_t workspace_bytes, void* stream) {
   const us_dtype op = fp8 ? US_E4M3 : US_F16;
   // layer 1 with the GELU fused: Z = d^-1/2 X W1 (FP16), H = 1.7009 gelu(Z) as FP16 or as E4M3 codes
   us_status s = us_linear_fwd(X, W1, Z, T, d, f, op, op, US_F16, 0.0f, US_EPI_GELU, 0.0f, fp8 ? nullptr : H,
-                              fp8 ? H : nullptr, nullptr, 0, stream);
+                              fp8 ? H : nullptr, workspace, workspace_bytes, stream);
   if (s != US_OK) return s;
   // layer 2: Y = f^-1/2 H W2
   return us_linear_fwd(H, W2, Y, T, f, d, op, op, US_F16, 0.0f, US_EPI_NONE, 0.0f, nullptr, nullptr, nullptr, 0, stream);

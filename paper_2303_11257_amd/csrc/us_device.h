@@ -24,6 +24,15 @@ typedef short v4s __attribute__((ext_vector_type(4)));
 constexpr float kGeluAlpha = 1.7009261846542358f;
 constexpr float kGeluBeta = 1.481114387512207f;
 
+// ---- FP32 -> FP16 ------------------------------------------------------------------------------------
+// Round-to-nearest-even conversion that keeps the sign of a zero product: the compiler likes to fuse
+// "multiply, then convert" into v_fma_mixlo_f16(a, b, +0), and (-0) + (+0) is +0.  The empty asm makes
+// the product a value of its own, so the conversion stays a plain v_cvt.
+__device__ __forceinline__ _Float16 to_half(float x) {
+  asm volatile("" : "+v"(x));
+  return (_Float16)x;
+}
+
 // ---- FP32 -> FP8 (E4M3: max 448, one NaN, no inf; E5M2: max 57344) -------------------------------
 // The hardware converter rounds to nearest-even and handles subnormals; it turns overflow into
 // NaN/inf, so the value is first clipped to the finite range (that also maps +-inf to +-max).
@@ -86,9 +95,9 @@ __device__ __forceinline__ GaussTerms gauss_terms(float z) {
   poly = __builtin_fmaf(poly, t, c2);
   poly = __builtin_fmaf(poly, t, c1);
   poly = __builtin_fmaf(poly, t, c0);
-  float q = (poly * t) * e;
+  const float pt = poly * t;
   GaussTerms g;
-  g.Phi = (z < 0.0f) ? q : 1.0f - q;
+  g.Phi = (z < 0.0f) ? pt * e : __builtin_fmaf(-pt, e, 1.0f);
   g.pdf = 0.3989422804014327f * e;
   return g;
 }
@@ -98,10 +107,39 @@ __device__ __forceinline__ float gelu_scaled(float z, float alpha_g) {
   GaussTerms g = gauss_terms(z);
   return alpha_g * (z * g.Phi);
 }
-// d/dz gelu(z) * beta_g * gh
+// beta_g * gelu'(|z|),  gelu'(x) = Phi(x) + x*phi(x)
+__device__ __forceinline__ float gelu_slope_abs(float az, float beta_g) {
+  GaussTerms g = gauss_terms(az);
+  return beta_g * __builtin_fmaf(az, g.pdf, g.Phi);
+}
+// beta_g * gelu'(z) * gh.  Negative arguments use gelu'(-x) = 1 - gelu'(x), so that the function of
+// |z| can also be tabulated (see the table-driven GEMM epilogue); +-inf and NaN give NaN.
 __device__ __forceinline__ float gelu_grad_scaled(float z, float gh, float beta_g) {
-  GaussTerms g = gauss_terms(z);
-  return (beta_g * __builtin_fmaf(z, g.pdf, g.Phi)) * gh;
+  const float t = gelu_slope_abs(__builtin_fabsf(z), beta_g);
+  const float r = (__builtin_signbit(z)) ? beta_g - t : t;
+  return r * gh;
+}
+
+// ---- tables over the FP16 pre-activation (65536 possible inputs) ----------------------------------------
+// Forward: the E4M3 code of fp16(alpha_g * gelu(z)) for every bit pattern of z.
+// Backward: beta_g * gelu'(|z|) in FP32 for |z| <= 8 (bit patterns 0 .. 0x4800; the slope is exactly
+// 1 in FP32 beyond that).  Both are filled by the same device functions the arithmetic epilogues use,
+// so the table-driven epilogues give identical results.
+constexpr int kGeluTableBytes = 65536;
+constexpr int kGeluSlopeLast = 0x4800;                                   // FP16 bits of 8.0
+constexpr int kGeluSlopeTableBytes = 73 * 1024;                          // (0x4801 entries * 4 B) rounded up to whole KB
+constexpr int kTableAreaBytes = 128 * 1024;                              // head of a workspace reserved for tables
+
+__device__ __forceinline__ _Float16 half_from_bits(uint32_t b) {
+  const unsigned short u = (unsigned short)b;
+  _Float16 h;
+  __builtin_memcpy(&h, &u, 2);
+  return h;
+}
+__device__ __forceinline__ uint32_t half_bits(_Float16 h) {
+  unsigned short u;
+  __builtin_memcpy(&u, &h, 2);
+  return u;
 }
 
 }  // namespace us

@@ -94,7 +94,7 @@ __global__ void __launch_bounds__(kThreads) cast_kernel(const SrcT* __restrict__
 
 // h = fp16/fp32( alpha_g * z * Phi(z) ), eight (FP16) or four (FP32) elements per 128-bit access.
 template <typename T, bool BWD>
-__global__ void __launch_bounds__(kThreads) gelu_kernel(const T* __restrict__ z, const T* gh, T* out, size_t n,
+__global__ void __launch_bounds__(kThreads) gelu_kernel(const T* z, const T* gh, T* out, size_t n,
                                                         float s) {
   constexpr int V = 16 / sizeof(T);
   typedef T vec_t __attribute__((ext_vector_type(V)));
@@ -107,15 +107,33 @@ __global__ void __launch_bounds__(kThreads) gelu_kernel(const T* __restrict__ z,
     if (BWD) gv = *reinterpret_cast<const vec_t*>(gh + v * V);
     vec_t o;
 #pragma unroll
-    for (int k = 0; k < V; ++k)
-      o[k] = (T)(BWD ? gelu_grad_scaled((float)zv[k], (float)gv[k], s) : gelu_scaled((float)zv[k], s));
+    for (int k = 0; k < V; ++k) {
+      const float r = BWD ? gelu_grad_scaled((float)zv[k], (float)gv[k], s) : gelu_scaled((float)zv[k], s);
+      if constexpr (sizeof(T) == 2) o[k] = to_half(r);
+      else o[k] = r;
+    }
     *reinterpret_cast<vec_t*>(out + v * V) = o;
   }
   const size_t tail0 = nvec * V;
   if (tid < n - tail0) {
-    float zi = (float)z[tail0 + tid];
-    out[tail0 + tid] = (T)(BWD ? gelu_grad_scaled(zi, (float)gh[tail0 + tid], s) : gelu_scaled(zi, s));
+    const float zi = (float)z[tail0 + tid];
+    const float r = BWD ? gelu_grad_scaled(zi, (float)gh[tail0 + tid], s) : gelu_scaled(zi, s);
+    if constexpr (sizeof(T) == 2) out[tail0 + tid] = to_half(r);
+    else out[tail0 + tid] = r;
   }
+}
+
+// tab[i] = E4M3 code of fp16(alpha_g * gelu(z)) for the FP16 value z with bit pattern i
+__global__ void __launch_bounds__(kThreads) gelu_table_kernel(uint8_t* tab, float alpha_g) {
+  const uint32_t i = blockIdx.x * kThreads + threadIdx.x;       // 0 .. 65535
+  const _Float16 h = to_half(gelu_scaled((float)half_from_bits(i), alpha_g));
+  const v2h pair = {h, h};
+  tab[i] = (uint8_t)cvt_pk_fp8_from_half<US_E4M3>(pair);
+}
+// tab[i] = beta_g * gelu'(|z|) in FP32 for the FP16 magnitudes 0 .. 8.0 (bit patterns 0 .. 0x4800)
+__global__ void __launch_bounds__(kThreads) gelu_slope_table_kernel(float* tab, float beta_g) {
+  const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
+  if (i <= (uint32_t)kGeluSlopeLast) tab[i] = gelu_slope_abs((float)half_from_bits(i), beta_g);
 }
 
 inline int grid_for(size_t nvec) {
@@ -145,6 +163,16 @@ hipError_t launch_cast(const void* src, us_dtype src_dt, void* dst, us_dtype dst
                              : cast_dispatch<_Float16, US_E5M2>(src, dst, n, scale, stats, st);
   return dst_dt == US_E4M3 ? cast_dispatch<float, US_E4M3>(src, dst, n, scale, stats, st)
                            : cast_dispatch<float, US_E5M2>(src, dst, n, scale, stats, st);
+}
+
+hipError_t launch_gelu_table(void* table, float alpha_g, hipStream_t st) {
+  gelu_table_kernel<<<65536 / kThreads, kThreads, 0, st>>>((uint8_t*)table, alpha_g);
+  return hipGetLastError();
+}
+
+hipError_t launch_gelu_slope_table(void* table, float beta_g, hipStream_t st) {
+  gelu_slope_table_kernel<<<(kGeluSlopeLast + kThreads) / kThreads, kThreads, 0, st>>>((float*)table, beta_g);
+  return hipGetLastError();
 }
 
 hipError_t launch_gelu_fwd(const void* z, void* h, size_t n, us_dtype dt, float alpha_g, hipStream_t st) {

@@ -14,7 +14,7 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
   if (out_is_f32) {
     *reinterpret_cast<v4f*>((float*)out + i4) = s;
   } else {
-    v4h o = {(_Float16)s.x, (_Float16)s.y, (_Float16)s.z, (_Float16)s.w};
+    v4h o = {to_half(s.x), to_half(s.y), to_half(s.z), to_half(s.w)};
     *reinterpret_cast<v4h*>((_Float16*)out + i4) = o;
   }
 }

@@ -7,7 +7,9 @@
 
 namespace us {
 
-enum GemmEpi : int { EPI_STORE = 0, EPI_GELU = 1, EPI_GELU_GRAD = 2, EPI_PARTIAL = 3 };
+// EPI_GELU_TAB / EPI_GELU_GRAD_TAB: same results as EPI_GELU (FP8 activation only) / EPI_GELU_GRAD,
+// taken from a table over the FP16 pre-activation that the workgroup copies into LDS.
+enum GemmEpi : int { EPI_STORE = 0, EPI_GELU = 1, EPI_GELU_GRAD = 2, EPI_PARTIAL = 3, EPI_GELU_TAB = 4, EPI_GELU_GRAD_TAB = 5 };
 
 //   C[M,N] = epilogue( scale * sum_k A(m,k) * B(n,k) )
 // An operand is K-contiguous (element (r,k) at base[r*ld + k]) or K-strided (element (r,k) at
@@ -24,6 +26,7 @@ struct GemmArgs {
   _Float16* aux16;       // EPI_GELU: optional FP16 activation output
   uint8_t* aux8;         // optional FP8 copy of the epilogue's FP16 result
   float* partial;        // EPI_PARTIAL: [splits][M][N] FP32
+  const uint8_t* table;  // EPI_*_TAB: the table in global memory (us_device.h)
   int xcd_gm, xcd_gn;    // XCD rectangle split of the tile grid (0,0 = one rectangle)
   int grp_w;             // width of the column bands the rectangle is walked in
 };
@@ -88,7 +91,41 @@ inline void choose_xcd_grid(long tiles_m, long tiles_n, int& gm, int& gn) {
 
 // ---- epilogue on eight consecutive columns of one row (FP16 strip) ---------------------------------
 template <int EPI, int AUX_FMT>
-__device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y) {
+__device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y, const uint8_t* lut) {
+  if (EPI == EPI_GELU_TAB) {
+    *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = y;   // the FP16 matmul result, kept for backward
+    uint32_t c[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) c[k] = *US_LDS_PTR(const uint8_t, lut + half_bits(y[k]));
+    v2i w;
+    w.x = (int)(c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24));
+    w.y = (int)(c[4] | (c[5] << 8) | (c[6] << 16) | (c[7] << 24));
+    *reinterpret_cast<v2i*>(g.aux8 + idx) = w;
+    return;
+  }
+  if (EPI == EPI_GELU_GRAD_TAB) {
+    const v8h z = *reinterpret_cast<const v8h*>(g.Zpre + idx);
+    v8h r;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const uint32_t zb = half_bits(z[k]);
+      const uint32_t a = zb & 0x7fffu;
+      const uint32_t i = a < (uint32_t)kGeluSlopeLast ? a : (uint32_t)kGeluSlopeLast;
+      float t = *US_LDS_PTR(const float, lut + i * 4);
+      t = (zb & 0x8000u) ? g.epi_scale - t : t;
+      t = (a >= 0x7c00u) ? __builtin_nanf("") : t;       // +-inf and NaN, as the arithmetic form gives
+      r[k] = to_half(t * (float)y[k]);
+    }
+    *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = r;
+    if (g.aux8) {
+      const v2h p0 = {r[0], r[1]}, p1 = {r[2], r[3]}, p2 = {r[4], r[5]}, p3 = {r[6], r[7]};
+      v2i w;
+      w.x = (int)(cvt_pk_fp8_from_half<AUX_FMT>(p0) | (cvt_pk_fp8_from_half<AUX_FMT>(p1) << 16));
+      w.y = (int)(cvt_pk_fp8_from_half<AUX_FMT>(p2) | (cvt_pk_fp8_from_half<AUX_FMT>(p3) << 16));
+      *reinterpret_cast<v2i*>(g.aux8 + idx) = w;
+    }
+    return;
+  }
   if (EPI == EPI_STORE) {
     *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = y;
     return;
@@ -97,12 +134,12 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
   if (EPI == EPI_GELU) {
     *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = y;   // the FP16 matmul result, kept for backward
 #pragma unroll
-    for (int k = 0; k < 8; ++k) r[k] = (_Float16)gelu_scaled((float)y[k], g.epi_scale);
+    for (int k = 0; k < 8; ++k) r[k] = to_half(gelu_scaled((float)y[k], g.epi_scale));
     if (g.aux16) *reinterpret_cast<v8h*>(g.aux16 + idx) = r;
   } else {  // EPI_GELU_GRAD: y is the FP16-rounded matmul gradient
     v8h z = *reinterpret_cast<const v8h*>(g.Zpre + idx);
 #pragma unroll
-    for (int k = 0; k < 8; ++k) r[k] = (_Float16)gelu_grad_scaled((float)z[k], (float)y[k], g.epi_scale);
+    for (int k = 0; k < 8; ++k) r[k] = to_half(gelu_grad_scaled((float)z[k], (float)y[k], g.epi_scale));
     *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = r;
   }
   if (g.aux8) {
@@ -116,11 +153,13 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
 }
 
 // Strip geometry: every wave owns 32 rows x WN values of LDS (FP16, or FP32 when WIDE).
-template <class Cfg, bool WIDE>
+template <class Cfg, bool WIDE, int EPI = EPI_STORE>
 struct EpiStrip {
   static constexpr int ES = WIDE ? 4 : 2;
   static constexpr int PITCH = Cfg::WN * ES + 16;
-  static constexpr int BYTES = 32 * PITCH * Cfg::WAVES;
+  static constexpr int STRIP_BYTES = 32 * PITCH * Cfg::WAVES;
+  static constexpr int TABLE_BYTES = EPI == EPI_GELU_TAB ? kGeluTableBytes : EPI == EPI_GELU_GRAD_TAB ? kGeluSlopeTableBytes : 0;
+  static constexpr int BYTES = STRIP_BYTES + TABLE_BYTES;     // the table sits behind the strips
 };
 
 // The matrix core is fed with the N-side fragment as first operand, so register 4q+e of lane l of a
@@ -132,8 +171,18 @@ template <class Cfg, int EPI, bool WIDE>
 __device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&acc)[Cfg::FM][Cfg::FN], uint8_t* lds,
                                                      long m0, long n0, long split) {
   static_assert(WIDE ? (EPI == EPI_STORE || EPI == EPI_PARTIAL) : (EPI != EPI_PARTIAL), "");
-  using S = EpiStrip<Cfg, WIDE>;
-  constexpr int AUX_FMT = (EPI == EPI_GELU_GRAD) ? US_E5M2 : US_E4M3;
+  using S = EpiStrip<Cfg, WIDE, EPI>;
+  constexpr int AUX_FMT = (EPI == EPI_GELU_GRAD || EPI == EPI_GELU_GRAD_TAB) ? US_E5M2 : US_E4M3;
+  const uint8_t* lut = lds + S::STRIP_BYTES;
+  if constexpr (S::TABLE_BYTES > 0) {
+    // copy the table into LDS: whole 1 KB wave loads, 16 bytes per lane, spread over the waves
+    for (int c = threadIdx.x >> 6; c < S::TABLE_BYTES / 1024; c += Cfg::WAVES)
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(g.table + c * 1024 + (threadIdx.x & 63) * 16),
+          US_LDS_PTR(void, lds + S::STRIP_BYTES + c * 1024), 16, 0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of the table has landed
+    __syncthreads();
+  }
   constexpr int EP = S::PITCH;
   const int wave = threadIdx.x >> 6;
   const int lane = threadIdx.x & 63;
@@ -155,7 +204,7 @@ __device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&a
           v4f o = {v0, v1, v2, v3};
           *US_LDS_PTR(v4f, p) = o;
         } else {
-          v4h o = {(_Float16)v0, (_Float16)v1, (_Float16)v2, (_Float16)v3};
+          v4h o = {to_half(v0), to_half(v1), to_half(v2), to_half(v3)};
           *US_LDS_PTR(v4h, p) = o;
         }
       }
@@ -180,7 +229,7 @@ __device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&a
             *reinterpret_cast<v4f*>((float*)g.C + m * g.ldc + n) = v;
         } else {
           v8h y = *US_LDS_PTR(const v8h, p);
-          epilogue_row8<EPI, AUX_FMT>(g, m * g.ldc + n, y);
+          epilogue_row8<EPI, AUX_FMT>(g, m * g.ldc + n, y, lut);
         }
       }
     }

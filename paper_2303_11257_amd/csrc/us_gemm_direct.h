@@ -24,7 +24,7 @@
 
 namespace us {
 
-template <class Cfg, bool FP8, bool A_KC, bool B_KC, bool WIDE>
+template <class Cfg, bool FP8, bool A_KC, bool B_KC, bool WIDE, int EPI = EPI_STORE>
 struct DirectTile {
   static constexpr int ES = FP8 ? 1 : 2;
   static constexpr int BK = Cfg::BKB / ES;                      // elements of K per stage
@@ -36,7 +36,7 @@ struct DirectTile {
   static constexpr int A_LOADS = A_BYTES / 16 / Cfg::THREADS;   // 16-byte loads per thread and stage
   static constexpr int B_LOADS = B_BYTES / 16 / Cfg::THREADS;
   static constexpr int RING_BYTES = Cfg::NST * STAGE_BYTES;
-  static constexpr int EPI_BYTES = EpiStrip<Cfg, WIDE>::BYTES;
+  static constexpr int EPI_BYTES = EpiStrip<Cfg, WIDE, EPI>::BYTES;
   static constexpr int LDS_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
   static_assert(A_BYTES % (16 * Cfg::THREADS) == 0 && B_BYTES % (16 * Cfg::THREADS) == 0, "whole wave loads only");
   static_assert(Cfg::NST >= 2 && Cfg::NST <= 5, "");
@@ -196,7 +196,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 
 template <class Cfg, bool FP8, int FA, int FB, bool A_KC, bool B_KC, int EPI, bool WIDE>
 __global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_direct_kernel(GemmArgs g) {
-  using T = DirectTile<Cfg, FP8, A_KC, B_KC, WIDE>;
+  using T = DirectTile<Cfg, FP8, A_KC, B_KC, WIDE, EPI>;
   constexpr int BM = Cfg::BM, BN = Cfg::BN, THREADS = Cfg::THREADS, BKB = Cfg::BKB, NST = Cfg::NST;
   constexpr int FM = Cfg::FM, FN = Cfg::FN;
   constexpr int ES = T::ES;

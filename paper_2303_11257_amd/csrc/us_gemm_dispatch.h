@@ -36,6 +36,7 @@ inline GemmArgs make_args(const GemmProblem& p, long k_per_split, int BM, int BN
   g.aux16 = (_Float16*)p.aux16;
   g.aux8 = (uint8_t*)p.aux8;
   g.partial = (float*)p.workspace;
+  g.table = (const uint8_t*)p.table;
   choose_xcd_grid(ceil_div(p.M, BM), ceil_div(p.N, BN), g.xcd_gm, g.xcd_gn);
   g.grp_w = (BM >= 256) ? 4 : 8;   // 32 (one per CU) resp. 64 (two per CU) concurrent tiles per XCD: 8 x 4 / 8 x 8
   return g;
@@ -43,8 +44,8 @@ inline GemmArgs make_args(const GemmProblem& p, long k_per_split, int BM, int BN
 
 template <bool DIRECT, class Cfg, bool FP8, int FA, int FB, bool A_KC, bool B_KC, int EPI, bool WIDE>
 hipError_t launch_one(const GemmProblem& p, int splits, long k_per_split, hipStream_t st) {
-  constexpr int LDS = DIRECT ? DirectTile<Cfg, FP8, A_KC, B_KC, WIDE>::LDS_BYTES
-                             : StagedTile<Cfg, FP8, A_KC, B_KC, WIDE>::LDS_BYTES;
+  constexpr int LDS = DIRECT ? DirectTile<Cfg, FP8, A_KC, B_KC, WIDE, EPI>::LDS_BYTES
+                             : StagedTile<Cfg, FP8, A_KC, B_KC, WIDE, EPI>::LDS_BYTES;
   auto kern = DIRECT ? gemm_direct_kernel<Cfg, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>
                      : gemm_staged_kernel<Cfg, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>;
   static bool configured = false;  // raising the dynamic-LDS limit is a per-function, once-only call
@@ -68,6 +69,14 @@ hipError_t launch_sized(const GemmProblem& p, int splits, long k_per_split, hipS
   if (use_big_tile(p.M, p.N, splits))
     return launch_one<true, CfgD256, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
   return launch_one<true, CfgD128, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
+}
+
+// The table-driven GELU epilogues exist for the large tile of the direct kernel only (the table
+// needs 64-73 KB of LDS next to the strips).
+template <bool FP8>
+inline bool table_path_ok(const GemmProblem& p) {
+  const long bk = FP8 ? 128 : 64;
+  return p.table != nullptr && p.K > 0 && p.K % bk == 0 && use_big_tile(p.M, p.N, 1);
 }
 
 // Plain store epilogue: FP16 or FP32 output.

@@ -12,7 +12,7 @@
 
 namespace us {
 
-template <class Cfg, bool FP8, bool A_KC, bool B_KC, bool WIDE>
+template <class Cfg, bool FP8, bool A_KC, bool B_KC, bool WIDE, int EPI = EPI_STORE>
 struct StagedTile {
   static constexpr int ES = FP8 ? 1 : 2;
   static constexpr int BK = Cfg::BKB / ES;               // elements of K per stage
@@ -24,7 +24,7 @@ struct StagedTile {
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int A_PER_THREAD = Cfg::BM * Cfg::BKB / 16 / Cfg::THREADS;   // 16-byte chunks
   static constexpr int B_PER_THREAD = Cfg::BN * Cfg::BKB / 16 / Cfg::THREADS;
-  static constexpr int EPI_BYTES = EpiStrip<Cfg, WIDE>::BYTES;
+  static constexpr int EPI_BYTES = EpiStrip<Cfg, WIDE, EPI>::BYTES;
   static constexpr int LDS_BYTES = (2 * STAGE_BYTES > EPI_BYTES) ? 2 * STAGE_BYTES : EPI_BYTES;
   static_assert((Cfg::BM * Cfg::BKB / 16) % Cfg::THREADS == 0 && (Cfg::BN * Cfg::BKB / 16) % Cfg::THREADS == 0, "");
 };
@@ -115,7 +115,7 @@ __device__ __forceinline__ v8h staged_frag_f16(const uint8_t* tile, int r0, int 
 
 template <class Cfg, bool FP8, int FA, int FB, bool A_KC, bool B_KC, int EPI, bool WIDE>
 __global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_staged_kernel(GemmArgs g) {
-  using T = StagedTile<Cfg, FP8, A_KC, B_KC, WIDE>;
+  using T = StagedTile<Cfg, FP8, A_KC, B_KC, WIDE, EPI>;
   constexpr int BM = Cfg::BM, BN = Cfg::BN, WM = Cfg::WM, WN = Cfg::WN, THREADS = Cfg::THREADS, BKB = Cfg::BKB;
   constexpr int ES = T::ES;
   constexpr int FM = Cfg::FM, FN = Cfg::FN;

@@ -37,6 +37,7 @@ struct GemmProblem {
   void* aux16;             // GELU: FP16 [M,N] or NULL
   void* aux8;              // GELU: E4M3 [M,N]; GELU_GRAD: E5M2 [M,N]; or NULL
   void* workspace;         // split-K partial sums (FP32), or NULL
+  void* table;             // scratch for the GELU table (>= 73 KB), or NULL: arithmetic epilogue
   size_t workspace_bytes;
 };
 
@@ -46,5 +47,9 @@ long gemm_k_per_split(long K, int splits);
 size_t gemm_workspace_bytes(long M, long N, long K);
 
 hipError_t launch_gemm(const GemmProblem& p, hipStream_t stream);
+
+// Fill the tables of the table-driven GELU epilogues (layouts in us_device.h).
+hipError_t launch_gelu_table(void* table, float alpha_g, hipStream_t stream);
+hipError_t launch_gelu_slope_table(void* table, float beta_g, hipStream_t stream);
 
 }  // namespace us

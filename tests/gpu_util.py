@@ -49,15 +49,17 @@ def cast_fp8(x: np.ndarray, dst_dt: int, scale: float = 1.0, want_stats: bool = 
     return codes
 
 
-def linear_fwd(X, W, x_dt, w_dt, alpha=0.0, out_dt=us.F16, epi=us.EPI_NONE, epi_scale=0.0, want16=True, want8=False):
+def linear_fwd(X, W, x_dt, w_dt, alpha=0.0, out_dt=us.F16, epi=us.EPI_NONE, epi_scale=0.0, want16=True, want8=False,
+               workspace_bytes=0):
     b, m = X.shape
     n = W.shape[1]
     dX_, dW_ = to_dev(X), to_dev(W)
     Y = empty((b, n), np.float16 if out_dt == us.F16 else np.float32)
     a16 = empty((b, n), np.float16) if (epi == us.EPI_GELU and want16) else None
     a8 = empty((b, n), np.uint8) if (epi == us.EPI_GELU and want8) else None
+    ws = torch.empty(workspace_bytes, dtype=torch.uint8, device=DEV) if workspace_bytes else None
     us.linear_fwd(ptr(dX_), ptr(dW_), ptr(Y), b, m, n, x_dt, w_dt, out_dt, alpha, epi, epi_scale, ptr(a16), ptr(a8),
-                  None, 0, stream())
+                  ptr(ws), workspace_bytes, stream())
     out = [to_np(Y)]
     if epi == us.EPI_GELU:
         out += [to_np(a16) if a16 is not None else None, to_np(a8) if a8 is not None else None]
@@ -65,7 +67,7 @@ def linear_fwd(X, W, x_dt, w_dt, alpha=0.0, out_dt=us.F16, epi=us.EPI_NONE, epi_
 
 
 def linear_bwd(X, W, G, x_dt, w_dt, g_dt, beta_x=0.0, beta_w=0.0, out_dt=us.F16, epi=us.EPI_NONE, epi_scale=0.0,
-               Zpre=None, want8=False, do_dx=True, do_dw=True):
+               Zpre=None, want8=False, do_dx=True, do_dw=True, no_workspace=False):
     b, n = G.shape
     m = W.shape[0] if W is not None else X.shape[1]
     tX = to_dev(X) if X is not None else None
@@ -76,7 +78,7 @@ def linear_bwd(X, W, G, x_dt, w_dt, g_dt, beta_x=0.0, beta_w=0.0, out_dt=us.F16,
     dW = empty((m, n), odt) if do_dw else None
     tZ = to_dev(Zpre) if Zpre is not None else None
     a8 = empty((b, m), np.uint8) if want8 else None
-    wsb = us.workspace_bytes(b, m, n)
+    wsb = 0 if no_workspace else us.workspace_bytes(b, m, n)
     ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=DEV)
     us.linear_bwd(ptr(tX), ptr(tW), ptr(tG), ptr(dX), ptr(dW), b, m, n, x_dt, w_dt, g_dt, out_dt, beta_x, beta_w, epi,
                   epi_scale, ptr(tZ), ptr(a8), ptr(ws), wsb, stream())

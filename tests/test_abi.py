@@ -38,10 +38,12 @@ def test_scales_and_status_strings():
 
 
 def test_workspace_rule():
-    assert us.workspace_bytes(32768, 4096, 16384) == 0              # output alone fills the chip
-    wb = us.workspace_bytes(8192, 1024, 4096)
+    table_area = 128 * 1024
+    assert us.workspace_bytes(32768, 4096, 16384) == table_area     # the output alone fills the chip: no dW slices
+    wb = us.workspace_bytes(8192, 1024, 4096) - table_area
     assert wb > 0 and wb % (1024 * 4096 * 4) == 0                   # whole FP32 slices of the output
-    assert us.ffn_workspace_bytes(8192, 1024, 4096) >= wb
+    assert us.ffn_workspace_bytes(8192, 1024, 4096) >= wb + table_area
+    assert us.workspace_bytes(0, 16, 16) == 0
 
 
 def test_argument_errors_are_detected_on_the_host():

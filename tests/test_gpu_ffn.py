@@ -40,7 +40,7 @@ class FfnRun:
         wsb = us.ffn_workspace_bytes(T, d, f)
         ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=DEV)
         us.ffn_fwd(ptr(dev["Xop"]), ptr(dev["W1op"]), ptr(dev["W2op"]), ptr(dev["Z"]), ptr(dev["H"]), ptr(dev["Y"]),
-                   T, d, f, fp8, st)
+                   T, d, f, fp8, ptr(ws), wsb, st)
         us.ffn_bwd(ptr(dev["Xop"]), ptr(dev["W1op"]), ptr(dev["W2op"]), ptr(dev["Z"]), ptr(dev["H"]), ptr(dev["Gop"]),
                    ptr(dev["dZ16"]), ptr(dev["dZ8"]), ptr(dev["dX"]), ptr(dev["dW1"]), ptr(dev["dW2"]), T, d, f, fp8,
                    ptr(ws), wsb, st)
@@ -173,7 +173,7 @@ def test_hip_graph_replays_match_eager():
         for k, fmt in (("X", us.E4M3), ("W1", us.E4M3), ("W2", us.E4M3), ("G", us.E5M2)):
             us.cast_fp8(ptr(dev[k]), us.F16, ptr(dev[k + "op"]), fmt, dev[k].numel(), 1.0, None, st)
         us.ffn_fwd(ptr(dev["Xop"]), ptr(dev["W1op"]), ptr(dev["W2op"]), ptr(dev["Z"]), ptr(dev["H"]), ptr(dev["Y"]),
-                   T, d, f, True, st)
+                   T, d, f, True, ptr(ws), wsb, st)
         us.ffn_bwd(ptr(dev["Xop"]), ptr(dev["W1op"]), ptr(dev["W2op"]), ptr(dev["Z"]), ptr(dev["H"]), ptr(dev["Gop"]),
                    ptr(dev["dZ16"]), ptr(dev["dZ8"]), ptr(dev["dX"]), ptr(dev["dW1"]), ptr(dev["dW2"]), T, d, f, True,
                    ptr(ws), wsb, st)

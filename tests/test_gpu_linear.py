@@ -154,3 +154,49 @@ def test_fp16_output_overflows_to_infinity():
     Y = linear_fwd(X, X, us.F16, us.F16, alpha=1.0)
     assert np.all(np.isinf(Y.astype(np.float32)))
     assert rel_err(Y, O.linear_fwd(X, X, 1.0)) == 0.0
+
+
+def test_table_driven_gelu_epilogues_equal_the_arithmetic_ones():
+    """Large problems with a workspace take GELU / GELU' from a table over the FP16 pre-activation;
+    the results must be bit-identical to the arithmetic epilogue (no workspace), special values included."""
+    b, m, n = 8192, 128, 4096
+    X = cast_fp8(synth.normal(137, synth.T_X, (b, m)), us.E4M3)
+    W = cast_fp8(synth.normal(137, synth.T_W1, (m, n)), us.E4M3)
+    X[5, :] = 0x7E                      # 448 everywhere ...
+    W[:, :2] = 0x7E                     # ... times 448 / -448 columns: +-inf in the FP16 Z
+    W[:, 1] = 0xFE
+    X[6, 3] = 0x7F                      # a NaN operand -> NaN in a whole row of Z
+    X[7, :] = 0                         # zeros
+    Z0, _, H0 = linear_fwd(X, W, us.E4M3, us.E4M3, epi=us.EPI_GELU, want16=False, want8=True)
+    Z1, _, H1 = linear_fwd(X, W, us.E4M3, us.E4M3, epi=us.EPI_GELU, want16=False, want8=True,
+                           workspace_bytes=us.workspace_bytes(b, m, n))
+    assert np.array_equal(Z0.view(np.uint16), Z1.view(np.uint16))
+    assert np.isinf(Z0[5].astype(np.float32)).any() and np.isnan(Z0[6].astype(np.float32)).all()
+    assert np.array_equal(H0, H1)
+    # sampled rows against the oracle as well (the codes may differ by one where FP32 GELU flipped an FP16 tie)
+    rows = [0, 1, 7, 100, 4095, 8191]
+    ref = O.cast_fp8(O.gelu_fwd(Z1[rows], O.gelu_scales()[0]), O.E4M3)[0]
+    d = np.abs(H1[rows].astype(np.int32) - ref.astype(np.int32))
+    assert d.max() <= 1 and np.mean(d != 0) < 1e-3
+
+    # grad_X with GELU': output [b, m] must be large, the reduction n short
+    b, m, n = 8192, 4096, 128
+    G = cast_fp8(synth.normal(139, synth.T_G, (b, n)), us.E5M2)
+    W = cast_fp8(synth.normal(139, synth.T_W1, (m, n)), us.E4M3)
+    Zpre = synth.normal(139, 7, (b, m), sigma=2.0)
+    special = np.array([np.nan, np.inf, -np.inf, 0.0, -0.0, 6e-8, -6e-8, 8.0, -8.0, 8.01, -8.01, 65504.0, -65504.0, 7.996],
+                       np.float16)
+    Zpre[3, :special.size] = special
+    args = dict(epi=us.EPI_GELU_GRAD, Zpre=Zpre, want8=True, do_dw=False)
+    dZ0, _, c0 = linear_bwd(None, W, G, us.E4M3, us.E4M3, us.E5M2, no_workspace=True, **args)
+    dZ1, _, c1 = linear_bwd(None, W, G, us.E4M3, us.E4M3, us.E5M2, **args)
+    same = (dZ0.view(np.uint16) == dZ1.view(np.uint16)) | (np.isnan(dZ0.astype(np.float32)) & np.isnan(dZ1.astype(np.float32)))
+    assert same.all()
+    assert np.isnan(dZ1[3, :3].astype(np.float32)).all() and np.isfinite(dZ1[3, 3:special.size].astype(np.float32)).all()
+    ok = ~np.isnan(dZ0.astype(np.float32))
+    assert np.array_equal(c0[ok], c1[ok])
+    rows = [0, 3, 4, 4095, 8191]
+    dH = O.linear_bwd_dx(G[rows], W, n ** -0.5, O.E5M2, O.E4M3)
+    ref = O.gelu_bwd(Zpre[rows], dH, O.gelu_scales()[1])
+    fin = np.isfinite(ref.astype(np.float32))
+    assert_close(np.where(fin, dZ1[rows], 0), np.where(fin, ref, 0), "dZ (table)")
