@@ -81,6 +81,16 @@ us_status us_cast_fp8(const void* src, us_dtype src_dt, void* dst, us_dtype dst_
                       float scale, us_cast_stats* stats, void* stream);
 
 /*
+ * The same cast with scale 1 for up to US_CAST_BATCH_MAX FP16 tensors in one launch (the activation,
+ * weight and gradient casts of one step).  src, dst, n, dst_dt are HOST arrays of `count` entries:
+ * device pointers (16-byte aligned), element counts, and US_E4M3 / US_E5M2 per tensor.  No counters.
+ * US_ERR_SHAPE if count is outside 0..US_CAST_BATCH_MAX.
+ */
+#define US_CAST_BATCH_MAX 8
+us_status us_cast_fp8_batch(int count, const void* const* src, void* const* dst, const size_t* n,
+                            const us_dtype* dst_dt, void* stream);
+
+/*
  * Forward of the scaled projection (Sec. 5.5):  Y[b,n] = alpha * X[b,m] W[m,n].
  * Operand types (x_dt, w_dt): (F16, F16) or (E4M3, E4M3).  FP32 accumulation; y_dt = F16 or F32.
  * alpha <= 0 selects m^-1/2.

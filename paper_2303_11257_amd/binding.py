@@ -43,6 +43,7 @@ def lib() -> ctypes.CDLL:
     L.us_status_string.restype = ctypes.c_char_p
     L.us_linear_scales.argtypes = [l, l, l, i, fp, fp, fp]
     L.us_cast_fp8.argtypes = [vp, i, vp, i, sz, f, vp, vp]
+    L.us_cast_fp8_batch.argtypes = [i, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(sz), ctypes.POINTER(i), vp]
     L.us_linear_fwd.argtypes = [vp, vp, vp, l, l, l, i, i, i, f, i, f, vp, vp, vp, sz, vp]
     L.us_linear_bwd.argtypes = [vp, vp, vp, vp, vp, l, l, l, i, i, i, i, f, f, i, f, vp, vp, vp, sz, vp]
     L.us_workspace_bytes.argtypes = [l, l, l]
@@ -53,7 +54,7 @@ def lib() -> ctypes.CDLL:
     L.us_ffn_bwd.argtypes = [vp] * 11 + [l, l, l, i, vp, sz, vp]
     L.us_ffn_workspace_bytes.argtypes = [l, l, l]
     L.us_ffn_workspace_bytes.restype = sz
-    for name in ("us_linear_scales", "us_cast_fp8", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd",
+    for name in ("us_linear_scales", "us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd",
                  "us_ffn_fwd", "us_ffn_bwd"):
         getattr(L, name).restype = i
     _lib = L
@@ -77,6 +78,14 @@ def linear_scales(b: int, m: int, n: int, mode: int = 0):
 
 def cast_fp8(src, src_dt, dst, dst_dt, n, scale=1.0, stats=None, stream=None):
     _check(lib().us_cast_fp8(src, src_dt, dst, dst_dt, n, scale, stats, stream), "us_cast_fp8")
+
+
+def cast_fp8_batch(srcs, dsts, ns, dst_dts, stream=None):
+    """One launch for several FP16 tensors: sequences of device addresses, element counts and FP8 types."""
+    k = len(srcs)
+    A = lambda T, vals: (T * k)(*vals)
+    _check(lib().us_cast_fp8_batch(k, A(ctypes.c_void_p, srcs), A(ctypes.c_void_p, dsts), A(ctypes.c_size_t, ns),
+                                   A(ctypes.c_int, dst_dts), stream), "us_cast_fp8_batch")
 
 
 def linear_fwd(X, W, Y, b, m, n, x_dt, w_dt, y_dt=F16, alpha=0.0, epi=EPI_NONE, epi_scale=0.0, aux16=None, aux8=None,

@@ -53,6 +53,21 @@ us_status us_cast_fp8(const void* src, us_dtype src_dt, void* dst, us_dtype dst_
   return from_hip(launch_cast(src, src_dt, dst, dst_dt, n, scale, stats, as_stream(stream)));
 }
 
+us_status us_cast_fp8_batch(int count, const void* const* src, void* const* dst, const size_t* n, const us_dtype* dst_dt,
+                            void* stream) {
+  if (count < 0 || count > US_CAST_BATCH_MAX) return US_ERR_SHAPE;
+  if (count == 0) return US_OK;
+  if (!src || !dst || !n || !dst_dt) return US_ERR_NULL;
+  for (int i = 0; i < count; ++i) {
+    if (!is_fp8(dst_dt[i])) return US_ERR_DTYPE;
+    if (n[i] == 0) continue;
+    if (!src[i] || !dst[i]) return US_ERR_NULL;
+    if (!aligned16(src[i]) || !aligned16(dst[i])) return US_ERR_ALIGN;
+    if (n[i] / 16 / 1024 >= 0xffffffffull / US_CAST_BATCH_MAX) return US_ERR_SHAPE;   // block index stays 32-bit
+  }
+  return from_hip(launch_cast_batch(count, src, dst, n, dst_dt, as_stream(stream)));
+}
+
 us_status us_gelu_fwd(const void* z, void* h, size_t n, us_dtype dt, float alpha_g, void* stream) {
   if (dt != US_F16 && dt != US_F32) return US_ERR_DTYPE;
   if (n == 0) return US_OK;

@@ -8,6 +8,7 @@ namespace us {
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kMaxCastBatch = US_CAST_BATCH_MAX;
 
 __device__ __forceinline__ void load16(const _Float16* src, size_t i, float (&x)[16]) {
   v8h a = *reinterpret_cast<const v8h*>(src + i);
@@ -92,6 +93,61 @@ __global__ void __launch_bounds__(kThreads) cast_kernel(const SrcT* __restrict__
   }
 }
 
+// Up to kMaxCastBatch FP16 tensors cast with scale 1 in one launch (the casts of one training step:
+// activations, two weight matrices and the incoming gradient are each only a few microseconds of
+// work, so four launches cost more in ramp-up and tails than in traffic).  blockIdx.x is mapped to a
+// tensor through the prefix sums of the per-tensor block counts; each block converts a contiguous
+// run of 16-element vectors with the packed FP16 -> FP8 converter.
+struct CastBatch {
+  const _Float16* src[kMaxCastBatch];
+  uint8_t* dst[kMaxCastBatch];
+  unsigned long long n[kMaxCastBatch];
+  unsigned int first_block[kMaxCastBatch + 1];
+  int e5m2[kMaxCastBatch];
+  int count;
+};
+constexpr int kBatchVecsPerBlock = 4 * kThreads;   // 16 KiB of codes per block
+
+template <int FMT>
+__device__ __forceinline__ void cast_run_half(const _Float16* __restrict__ src, uint8_t* __restrict__ dst, size_t n,
+                                              size_t vec0) {
+  const size_t nvec = n / 16;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const size_t v = vec0 + (size_t)u * kThreads + threadIdx.x;
+    if (v < nvec) {
+      const v8h a = *reinterpret_cast<const v8h*>(src + v * 16);
+      const v8h b = *reinterpret_cast<const v8h*>(src + v * 16 + 8);
+      v4i out;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const v2h p0 = {a[4 * q], a[4 * q + 1]}, p1 = {a[4 * q + 2], a[4 * q + 3]};
+        const v2h p2 = {b[4 * q], b[4 * q + 1]}, p3 = {b[4 * q + 2], b[4 * q + 3]};
+        out[q] = (int)(cvt_pk_fp8_from_half<FMT>(p0) | (cvt_pk_fp8_from_half<FMT>(p1) << 16));
+        out[2 + q] = (int)(cvt_pk_fp8_from_half<FMT>(p2) | (cvt_pk_fp8_from_half<FMT>(p3) << 16));
+      }
+      *reinterpret_cast<v4i*>(dst + v * 16) = out;
+    }
+  }
+  // the last n % 16 elements, by the block that owns the end of the tensor
+  const size_t tail0 = nvec * 16;
+  if (vec0 + kBatchVecsPerBlock >= nvec && threadIdx.x < n - tail0) {
+    const _Float16 h = src[tail0 + threadIdx.x];
+    const v2h p = {h, h};
+    dst[tail0 + threadIdx.x] = (uint8_t)cvt_pk_fp8_from_half<FMT>(p);
+  }
+}
+
+__global__ void __launch_bounds__(kThreads) cast_batch_kernel(CastBatch cb) {
+  int t = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxCastBatch; ++i)
+    if (i < cb.count && blockIdx.x >= cb.first_block[i]) t = i;
+  const size_t vec0 = (size_t)(blockIdx.x - cb.first_block[t]) * kBatchVecsPerBlock;
+  if (cb.e5m2[t]) cast_run_half<US_E5M2>(cb.src[t], cb.dst[t], cb.n[t], vec0);
+  else cast_run_half<US_E4M3>(cb.src[t], cb.dst[t], cb.n[t], vec0);
+}
+
 // h = fp16/fp32( alpha_g * z * Phi(z) ), eight (FP16) or four (FP32) elements per 128-bit access.
 template <typename T, bool BWD>
 __global__ void __launch_bounds__(kThreads) gelu_kernel(const T* z, const T* gh, T* out, size_t n,
@@ -163,6 +219,28 @@ hipError_t launch_cast(const void* src, us_dtype src_dt, void* dst, us_dtype dst
                              : cast_dispatch<_Float16, US_E5M2>(src, dst, n, scale, stats, st);
   return dst_dt == US_E4M3 ? cast_dispatch<float, US_E4M3>(src, dst, n, scale, stats, st)
                            : cast_dispatch<float, US_E5M2>(src, dst, n, scale, stats, st);
+}
+
+hipError_t launch_cast_batch(int count, const void* const* src, void* const* dst, const size_t* n, const us_dtype* dst_dt,
+                             hipStream_t st) {
+  CastBatch cb{};
+  cb.count = count;
+  unsigned int blocks = 0;
+  for (int i = 0; i < count; ++i) {
+    cb.src[i] = (const _Float16*)src[i];
+    cb.dst[i] = (uint8_t*)dst[i];
+    cb.n[i] = n[i];
+    cb.e5m2[i] = (dst_dt[i] == US_E5M2) ? 1 : 0;
+    cb.first_block[i] = blocks;
+    const size_t nvec = n[i] / 16;
+    size_t nb = (nvec + kBatchVecsPerBlock - 1) / kBatchVecsPerBlock;
+    if (nb == 0 && n[i] > 0) nb = 1;                 // a tensor shorter than one vector still needs its tail
+    blocks += (unsigned int)nb;
+  }
+  cb.first_block[count] = blocks;
+  if (blocks == 0) return hipSuccess;
+  cast_batch_kernel<<<blocks, kThreads, 0, st>>>(cb);
+  return hipGetLastError();
 }
 
 hipError_t launch_gelu_table(void* table, float alpha_g, hipStream_t st) {

@@ -11,6 +11,8 @@ namespace us {
 
 hipError_t launch_cast(const void* src, us_dtype src_dt, void* dst, us_dtype dst_dt, size_t n, float scale,
                        us_cast_stats* stats, hipStream_t stream);
+hipError_t launch_cast_batch(int count, const void* const* src, void* const* dst, const size_t* n, const us_dtype* dst_dt,
+                             hipStream_t stream);
 hipError_t launch_gelu_fwd(const void* z, void* h, size_t n, us_dtype dt, float alpha_g, hipStream_t stream);
 hipError_t launch_gelu_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtype dt, float beta_g,
                            hipStream_t stream);

@@ -19,7 +19,7 @@ def _declared():
 
 def test_every_declared_symbol_is_exported():
     names = _declared()
-    assert {"us_cast_fp8", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd", "us_linear_scales",
+    assert {"us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd", "us_linear_scales",
             "us_workspace_bytes", "us_status_string", "us_ffn_fwd", "us_ffn_bwd"} <= set(names)
     L = ctypes.CDLL(us.library_path())
     for n in names:
@@ -69,6 +69,16 @@ def test_argument_errors_are_detected_on_the_host():
         with pytest.raises(us.UsError) as e:
             fn()
         assert e.value.status == status, (status, e.value)
+    with pytest.raises(us.UsError) as e:
+        us.cast_fp8_batch([16] * 9, [32] * 9, [4] * 9, [E4] * 9)         # more than US_CAST_BATCH_MAX tensors
+    assert e.value.status == 2
+    with pytest.raises(us.UsError) as e:
+        us.cast_fp8_batch([16, 24], [32, 32], [4, 4], [E4, E5])          # second source misaligned
+    assert e.value.status == 3
+    with pytest.raises(us.UsError) as e:
+        us.cast_fp8_batch([16], [32], [4], [F16])
+    assert e.value.status == 4
+    us.cast_fp8_batch([], [], [], [])
     # empty problems are accepted without touching any pointer
     us.cast_fp8(None, F16, None, E4, 0)
     us.gelu_fwd(None, None, 0)

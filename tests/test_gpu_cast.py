@@ -95,3 +95,30 @@ def test_range_stress_tensor_counters(sigma):
         assert gs == ws
         if 1000.0 * s > 448.0:
             assert gs["n_sat"] >= n_out
+
+
+def test_batched_cast_equals_single_casts():
+    """One launch for several tensors (ragged lengths, mixed formats) gives the oracle's codes for each."""
+    import torch
+    from gpu_util import DEV, ptr, stream, to_dev, to_np
+    lens = [1 << 20, 16, 1, 0, 4096 * 16 + 5, 1023, 16384 * 16, 37]
+    fmts = [us.E4M3, us.E5M2, us.E4M3, us.E5M2, us.E5M2, us.E4M3, us.E4M3, us.E5M2]
+    xs = [synth.normal(149, i + 1, (n,), sigma=50.0) for i, n in enumerate(lens)]
+    for x in xs:
+        if x.size > 8:
+            x[:8] = np.array([np.inf, -np.inf, np.nan, 0.0, -0.0, 6e-8, 65504.0, -500.0], np.float16)
+    src = [to_dev(x) if x.size else None for x in xs]
+    dst = [torch.full((max(n, 1),), 0xAA, dtype=torch.uint8, device=DEV) for n in lens]
+    us.cast_fp8_batch([ptr(t) for t in src], [ptr(t) for t in dst], lens, fmts, stream())
+    for x, d, n, f in zip(xs, dst, lens, fmts):
+        got = to_np(d)[:n]
+        want = O_cast(x, f)
+        ok = ~np.isnan(x.astype(np.float32))
+        assert np.array_equal(got[ok], want[ok])
+        assert np.all((got[~ok] & 0x7F) >= (0x7F if f == us.E4M3 else 0x7D))
+        if n == 0:
+            assert to_np(d)[0] == 0xAA
+
+
+def O_cast(x, f):
+    return oracle.cast_fp8(x, oracle.E4M3 if f == us.E4M3 else oracle.E5M2)[0]
