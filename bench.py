@@ -175,6 +175,18 @@ def cpu_baseline(ffn, sample_tokens):
                 sample=f"first {n} of {ffn.T} tokens, full d_model and d_ff, every stage (casts, 6 matmuls, GELU fwd/bwd)")
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (None if absent)."""
+    path = os.path.join(ROOT, "profiles", f"gemm_gelugrad_{workload.lower()}_hbm_traffic.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -184,7 +196,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="time HIP-graph replays of the captured step instead of eager launches")
     ap.add_argument("--no-secondary", action="store_true", help="skip the FP16 BERT-base side measurement")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=512)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 256 MiB FP16 copy kernel (y = x + 0): the known-size reference for scaling "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path shards over tokens; see DESIGN.md); use --gpus 1",
@@ -201,6 +216,13 @@ def main():
     us.lib()   # fails loudly if the HIP library is not built
     torch.cuda.set_device(0)
 
+    if args.pmc_calibration:
+        x = torch.ones(128 << 20, dtype=torch.float16, device="cuda:0")     # 256 MiB read + 256 MiB written
+        y = torch.empty_like(x)
+        torch.add(x, 0, out=y)
+        torch.cuda.synchronize()
+        del x, y
+
     w = WORKLOADS[args.workload]
     ffn = Ffn(torch, us, synth, w["T"], w["d"], w["f"], w["fp8"], synth.BASE_SEED + 2)
     ms_eager = time_steps(torch, ffn.step, args.steps, args.warmup)
@@ -216,7 +238,7 @@ def main():
     dom = max(gemms, key=lambda c: c["ms"])
     gemm_ms = sum(c["ms"] for c in gemms)
     roof = dict(bound="mfma", kernel=dom["name"], achieved=dom["flop"] / (dom["ms"] * 1e-3) * 1e-12,
-                peak=PEAK_TFLOPS[dt_key], unit="TFLOP/s", traffic=None)
+                peak=PEAK_TFLOPS[dt_key], unit="TFLOP/s", traffic=measured_traffic(args.workload))
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["ms"] = dom["ms"]
     roof["all_gemms_achieved"] = sum(c["flop"] for c in gemms) / (gemm_ms * 1e-3) * 1e-12
