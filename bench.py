@@ -47,7 +47,10 @@ class Ffn:
             self.X8, self.W1_8, self.W2_8, self.G8 = e((T, d), u8), e((d, f), u8), e((f, d), u8), e((T, d), u8)
         self.Z, self.Y = e((T, f)), e((T, d))
         self.H = e((T, f), u8 if fp8 else torch.float16)
-        self.dZ16, self.dX, self.dW1, self.dW2 = e((T, f)), e((T, d)), e((d, f)), e((f, d))
+        self.dX, self.dW1, self.dW2 = e((T, d)), e((d, f)), e((f, d))
+        # grad of the pre-activation: FP16 in the FP16 step; in the FP8 step only its E5M2 codes are stored
+        # (they are all the layer-1 backward matmuls read)
+        self.dZ16 = None if fp8 else e((T, f))
         self.dZ8 = e((T, f), u8) if fp8 else None
         self.wsb = us.ffn_workspace_bytes(T, d, f)
         self.ws = torch.empty(max(self.wsb, 16), dtype=u8, device=dev)
@@ -248,7 +251,7 @@ def main():
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "fp8" if w["fp8"] else "f16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {w['desc']}", "tokens": w["T"], "d_model": w["d"], "d_ff": w["f"],
-                   "step": "one batched cast of X,W1,W2,G + Linear+GELU + Linear + 4 backward matmuls (GELU' fused)" if w["fp8"]
+                   "step": "one batched cast of X,W1,W2,G + Linear+GELU + Linear + 4 backward matmuls (GELU' fused; stored: Z16, H8, Y16, dZ8, dX16, dW16)" if w["fp8"]
                            else "Linear+GELU + Linear + 4 backward matmuls (GELU' fused)"},
         "frac_of_mfma_peak": tflops / PEAK_TFLOPS[dt_key],
         "launch": "hip-graph replay of the captured step" if args.graph else "eager",

@@ -120,7 +120,8 @@ us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, l
  * pre-activation saved by the forward pass),
  *   dX = fp16( epi_scale * gelu'(Zpre) * fp16(beta_x * G W^T) ),  gelu'(z) = Phi(z) + z*phi(z),
  * i.e. the scaled-GELU backward of Sec. 5.1 applied to the FP16-rounded matmul gradient; if aux8 !=
- * NULL the E5M2 cast of the stored FP16 dX is written there.  epi_scale <= 0 selects 1.4811.
+ * NULL the E5M2 cast of that FP16 dX is written there, and dX itself may then be NULL (only the
+ * codes are stored: the values are the same).  epi_scale <= 0 selects 1.4811.
  * Workspace (16-byte aligned, contents undefined on entry and exit): us_workspace_bytes(b, m, n) is
  * the size that serves every use.  Its first 128 KB hold the table of the table-driven GELU' epilogue
  * (same results as the arithmetic one; used for large problems when at least 128 KB are given), the
@@ -161,7 +162,8 @@ us_status us_gelu_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtyp
  *   Z [T,f] F16 out;  H [T,f] out: F16 when fp8 == 0, E4M3 codes when fp8 != 0;  Y [T,d] F16 out
  * us_ffn_bwd:  dH = fp16(d^-1/2 G W2^T);  dZ = fp16(1.4811 gelu'(Z) dH);  dW2 = fp16(T^-1/2 H^T G);
  *              dX = fp16(f^-1/2 dZ W1^T);  dW1 = fp16(T^-1/2 X^T dZ)
- *   G [T,d]: F16 or E5M2;  dZ16 [T,f] F16 out;  dZ8 [T,f] E5M2 out (fp8 != 0 only, else ignored)
+ *   G [T,d]: F16 or E5M2;  dZ16 [T,f] F16 out;  dZ8 [T,f] E5M2 out (fp8 != 0 only, else ignored).
+ *   With fp8 != 0 the layer-1 matmuls read dZ8 only, so dZ16 may be NULL and is then not stored.
  *   dX [T,d], dW1 [d,f], dW2 [f,d] F16 out
  *   workspace: us_ffn_workspace_bytes(T, d, f) bytes serve both calls (optional for us_ffn_fwd, where it
  *   only enables the table-driven GELU; required for us_ffn_bwd whenever a dW needs slices).

@@ -132,7 +132,8 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
   if (epi != US_EPI_NONE && epi != US_EPI_GELU_GRAD) return US_ERR_DTYPE;
   if (epi == US_EPI_GELU_GRAD && out_dt != US_F16) return US_ERR_DTYPE;
   if (b < 0 || m < 0 || n < 0 || !mult16(b) || !mult16(m) || !mult16(n)) return US_ERR_SHAPE;
-  const bool do_dx = dX && b > 0 && m > 0;
+  // with the GELU' epilogue the FP16 result is optional: its E5M2 copy alone may be asked for
+  const bool do_dx = (dX || (epi == US_EPI_GELU_GRAD && aux8)) && b > 0 && m > 0;
   const bool do_dw = dW && m > 0 && n > 0;
   if (!do_dx && !do_dw) return US_OK;
   if (do_dx && n > 0 && (!G || !W)) return US_ERR_NULL;
@@ -201,7 +202,7 @@ us_status us_ffn_bwd(const void* X, const void* W1, const void* W2, const void* 
                      void* workspace, size_t workspace_bytes, void* stream) {
   const us_dtype op = fp8 ? US_E4M3 : US_F16;
   const us_dtype gr = fp8 ? US_E5M2 : US_F16;
-  if (!dZ16 || (fp8 && !dZ8)) return US_ERR_NULL;
+  if (fp8 ? !dZ8 : !dZ16) return US_ERR_NULL;
   // layer 2 backward: dH = d^-1/2 G W2^T, fused with GELU' -> dZ (FP16 + E5M2 copy); dW2 = T^-1/2 H^T G
   us_status s = us_linear_bwd(H, W2, G, dZ16, dW2, T, f, d, op, op, gr, US_F16, 0.0f, 0.0f, US_EPI_GELU_GRAD, 0.0f, Z,
                               fp8 ? dZ8 : nullptr, workspace, workspace_bytes, stream);

@@ -35,7 +35,7 @@ long gemm_k_per_split(long K, int splits) {
 }
 
 int gemm_splits(long M, long N, long K) {
-  if (use_big_tile(M, N, 1) || K < 1024) return 1;
+  if (use_big_tile(M, N, 1) || K < 1024 || use_wave_split_tile(M, N, K)) return 1;
   const long tiles = ceil_div(M, 128) * ceil_div(N, 128);
   long s = 512 / tiles;
   const long max_by_k = K / 512;

@@ -32,11 +32,15 @@ struct GemmArgs {
 };
 
 // Tile configuration.  BKB = bytes of K per row and pipeline stage; NST = LDS stage buffers;
-// MINB = workgroups per CU the register allocation should allow.
-template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int BKB_, int NST_, int MINB_>
+// MINB = workgroups per CU the register allocation should allow.  WAVES_K > 1: that many groups of
+// WAVES_M x WAVES_N waves work on the same output tile, each on its own share of every stage's k-steps;
+// their accumulators are added through LDS before the epilogue (direct kernel only).
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int BKB_, int NST_, int MINB_, int WAVES_K_ = 1>
 struct GemmCfg {
   static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, BKB = BKB_, NST = NST_, MINB = MINB_;
-  static constexpr int WAVES = WAVES_M * WAVES_N;
+  static constexpr int WAVES_K = WAVES_K_;
+  static constexpr int WAVES_MN = WAVES_M * WAVES_N;
+  static constexpr int WAVES = WAVES_MN * WAVES_K;
   static constexpr int THREADS = 64 * WAVES;
   static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   static constexpr int FM = WM / 32, FN = WN / 32;   // 32x32 accumulator blocks per wave
@@ -90,8 +94,10 @@ inline void choose_xcd_grid(long tiles_m, long tiles_n, int& gm, int& gn) {
 }
 
 // ---- epilogue on eight consecutive columns of one row (FP16 strip) ---------------------------------
+// z: the saved pre-activation at the same eight positions (GELU' epilogues only; fetched by the caller
+// well ahead of its use).
 template <int EPI, int AUX_FMT>
-__device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y, const uint8_t* lut) {
+__device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y, v8h z, const uint8_t* lut) {
   if (EPI == EPI_GELU_TAB) {
     *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = y;   // the FP16 matmul result, kept for backward
     uint32_t c[8];
@@ -104,7 +110,6 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
     return;
   }
   if (EPI == EPI_GELU_GRAD_TAB) {
-    const v8h z = *reinterpret_cast<const v8h*>(g.Zpre + idx);
     v8h r;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
@@ -116,7 +121,7 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
       t = (a >= 0x7c00u) ? __builtin_nanf("") : t;       // +-inf and NaN, as the arithmetic form gives
       r[k] = to_half(t * (float)y[k]);
     }
-    *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = r;
+    if (g.C) *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = r;
     if (g.aux8) {
       const v2h p0 = {r[0], r[1]}, p1 = {r[2], r[3]}, p2 = {r[4], r[5]}, p3 = {r[6], r[7]};
       v2i w;
@@ -137,10 +142,9 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
     for (int k = 0; k < 8; ++k) r[k] = to_half(gelu_scaled((float)y[k], g.epi_scale));
     if (g.aux16) *reinterpret_cast<v8h*>(g.aux16 + idx) = r;
   } else {  // EPI_GELU_GRAD: y is the FP16-rounded matmul gradient
-    v8h z = *reinterpret_cast<const v8h*>(g.Zpre + idx);
 #pragma unroll
     for (int k = 0; k < 8; ++k) r[k] = to_half(gelu_grad_scaled((float)z[k], (float)y[k], g.epi_scale));
-    *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = r;
+    if (g.C) *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = r;      // optional: the FP8 copy may be all that is wanted
   }
   if (g.aux8) {
     // FP8 copy of the FP16 value just stored: identical to casting the stored tensor afterwards
@@ -157,7 +161,7 @@ template <class Cfg, bool WIDE, int EPI = EPI_STORE>
 struct EpiStrip {
   static constexpr int ES = WIDE ? 4 : 2;
   static constexpr int PITCH = Cfg::WN * ES + 16;
-  static constexpr int STRIP_BYTES = 32 * PITCH * Cfg::WAVES;
+  static constexpr int STRIP_BYTES = 32 * PITCH * Cfg::WAVES_MN;
   static constexpr int TABLE_BYTES = EPI == EPI_GELU_TAB ? kGeluTableBytes : EPI == EPI_GELU_GRAD_TAB ? kGeluSlopeTableBytes : 0;
   static constexpr int BYTES = STRIP_BYTES + TABLE_BYTES;     // the table sits behind the strips
 };
@@ -166,7 +170,8 @@ struct EpiStrip {
 // 32x32 accumulator block holds (row l%32, column 8q + 4(l/32) + e).  Each wave pushes 32 rows of
 // its block at a time through its LDS strip and reads them back row-contiguously: all global stores
 // (and the read of the saved pre-activation) are 128-bit accesses sweeping whole rows.
-// Must be entered by all waves after a workgroup barrier (the strips overlay the operand tiles).
+// Must be entered by all waves that hold accumulators (the first WAVES_M x WAVES_N of the workgroup)
+// after a workgroup barrier (the strips overlay the operand tiles).
 template <class Cfg, int EPI, bool WIDE>
 __device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&acc)[Cfg::FM][Cfg::FN], uint8_t* lds,
                                                      long m0, long n0, long split) {
@@ -174,6 +179,7 @@ __device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&a
   using S = EpiStrip<Cfg, WIDE, EPI>;
   constexpr int AUX_FMT = (EPI == EPI_GELU_GRAD || EPI == EPI_GELU_GRAD_TAB) ? US_E5M2 : US_E4M3;
   const uint8_t* lut = lds + S::STRIP_BYTES;
+  static_assert(S::TABLE_BYTES == 0 || Cfg::WAVES_K == 1, "the table copy below meets all waves at a barrier");
   if constexpr (S::TABLE_BYTES > 0) {
     // copy the table into LDS: whole 1 KB wave loads, 16 bytes per lane, spread over the waves
     for (int c = threadIdx.x >> 6; c < S::TABLE_BYTES / 1024; c += Cfg::WAVES)
@@ -190,6 +196,25 @@ __device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&a
   const int wn0 = (wave / Cfg::WAVES_M) * Cfg::WN;
   uint8_t* strip = lds + wave * (32 * EP);
   const float scale = (EPI == EPI_PARTIAL) ? 1.0f : g.scale;
+  constexpr int CPR = Cfg::WN * S::ES / 16;          // 16-byte chunks per strip row
+  constexpr int PER_LANE = 32 * CPR / 64;
+  // GELU': the wave's whole share of the saved pre-activation is requested up front, before any store.
+  // Loads and stores share one in-order completion counter here, so a load issued between stores
+  // could only be waited for together with every store before it (each one an HBM round trip); with
+  // all loads first, the stores below are never waited for.
+  constexpr bool NEEDS_Z = (EPI == EPI_GELU_GRAD || EPI == EPI_GELU_GRAD_TAB);
+  v8h zpre[NEEDS_Z ? Cfg::FM : 1][NEEDS_Z ? PER_LANE : 1] = {};
+  if constexpr (NEEDS_Z) {
+#pragma unroll
+    for (int i = 0; i < Cfg::FM; ++i)
+#pragma unroll
+      for (int u = 0; u < PER_LANE; ++u) {
+        const int c = lane + u * 64;
+        const long m = m0 + wm0 + i * 32 + c / CPR;
+        const long n = n0 + wn0 + (c % CPR) * 8;
+        if (m < g.M && n < g.N) zpre[i][u] = *reinterpret_cast<const v8h*>(g.Zpre + m * g.ldc + n);
+      }
+  }
 #pragma unroll
   for (int i = 0; i < Cfg::FM; ++i) {
 #pragma unroll
@@ -211,8 +236,9 @@ __device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&a
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    constexpr int CPR = Cfg::WN * S::ES / 16;          // 16-byte chunks per strip row
-    constexpr int PER_LANE = 32 * CPR / 64;
+    // one unconditional wait for the pre-activation loads: the uses below sit in bounds-checked
+    // branches, where the compiler would otherwise wait again and again, by then for the stores too
+    if (NEEDS_Z && i == 0) __builtin_amdgcn_s_waitcnt(0x0F70);
 #pragma unroll
     for (int u = 0; u < PER_LANE; ++u) {
       const int c = lane + u * 64;
@@ -229,7 +255,7 @@ __device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&a
             *reinterpret_cast<v4f*>((float*)g.C + m * g.ldc + n) = v;
         } else {
           v8h y = *US_LDS_PTR(const v8h, p);
-          epilogue_row8<EPI, AUX_FMT>(g, m * g.ldc + n, y, lut);
+          epilogue_row8<EPI, AUX_FMT>(g, m * g.ldc + n, y, zpre[NEEDS_Z ? i : 0][NEEDS_Z ? u : 0], lut);
         }
       }
     }

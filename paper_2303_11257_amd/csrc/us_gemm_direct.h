@@ -36,11 +36,17 @@ struct DirectTile {
   static constexpr int A_LOADS = A_BYTES / 16 / Cfg::THREADS;   // 16-byte loads per thread and stage
   static constexpr int B_LOADS = B_BYTES / 16 / Cfg::THREADS;
   static constexpr int RING_BYTES = Cfg::NST * STAGE_BYTES;
-  static constexpr int EPI_BYTES = EpiStrip<Cfg, WIDE, EPI>::BYTES;
+  // WAVES_K > 1: the accumulators of the extra wave groups (FP32, one 256-byte row per register) sit
+  // behind the strips while they are added up
+  static constexpr int REDUCE_BYTES = (Cfg::WAVES_K - 1) * Cfg::WAVES_MN * Cfg::FM * Cfg::FN * 16 * 64 * 4;
+  static constexpr int REDUCE_OFFSET = EpiStrip<Cfg, WIDE, EPI>::BYTES;
+  static constexpr int EPI_BYTES = REDUCE_OFFSET + REDUCE_BYTES;
   static constexpr int LDS_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
   static_assert(A_BYTES % (16 * Cfg::THREADS) == 0 && B_BYTES % (16 * Cfg::THREADS) == 0, "whole wave loads only");
   static_assert(Cfg::NST >= 2 && Cfg::NST <= 5, "");
-  static_assert(Cfg::BKB == 64 || Cfg::BKB == 128, "");
+  static_assert(Cfg::BKB == 64 || Cfg::BKB == 128 || (Cfg::BKB == 256 && !A_KC && !B_KC),
+                "256-byte stages exist for K-strided tiles only (the K-contiguous swizzle stops at 128)");
+  static_assert((FP8 ? Cfg::BKB / 64 : Cfg::BKB / 32) % Cfg::WAVES_K == 0, "whole k-steps per wave group");
   static_assert(LDS_BYTES <= 160 * 1024, "the ring must fit the CU's 160 KB of LDS");
 };
 
@@ -200,7 +206,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_direct_kernel(Ge
   constexpr int BM = Cfg::BM, BN = Cfg::BN, THREADS = Cfg::THREADS, BKB = Cfg::BKB, NST = Cfg::NST;
   constexpr int FM = Cfg::FM, FN = Cfg::FN;
   constexpr int ES = T::ES;
-  constexpr int KSTEPS = FP8 ? BKB / 64 : BKB / 32;
+  constexpr int KSTEPS = (FP8 ? BKB / 64 : BKB / 32) / Cfg::WAVES_K;   // k-steps of a stage this wave works on
   constexpr int PA = T::PA, PB = T::PB;
   constexpr int LOADS = T::A_LOADS + T::B_LOADS;       // per thread and stage
 
@@ -216,8 +222,11 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_direct_kernel(Ge
   const int nstages = (k_end > k_begin) ? (int)((k_end - k_begin) / T::BK) : 0;   // host guarantees divisibility
 
   const int wave = threadIdx.x >> 6;
-  const int wm0 = (wave % Cfg::WAVES_M) * Cfg::WM;
-  const int wn0 = (wave / Cfg::WAVES_M) * Cfg::WN;
+  const int wmn = wave % Cfg::WAVES_MN;             // position in the output tile
+  const int wk = wave / Cfg::WAVES_MN;              // share of the k-steps
+  const int wm0 = (wmn % Cfg::WAVES_M) * Cfg::WM;
+  const int wn0 = (wmn / Cfg::WAVES_M) * Cfg::WN;
+  const int ks0 = wk * KSTEPS;
 
   // edge tiles: slots that are never loaded must read as zero
   const bool edge = (m0 + BM > g.M || n0 + BN > g.N);
@@ -250,13 +259,13 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_direct_kernel(Ge
     const uint8_t* tb = ta + T::A_BYTES;
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
-      if constexpr (FP8) b[j] = direct_frag_fp8<B_KC, PB>(tb, wn0 + j * 32, ks);
-      else b[j] = direct_frag_f16<B_KC, PB>(tb, wn0 + j * 32, ks);
+      if constexpr (FP8) b[j] = direct_frag_fp8<B_KC, PB>(tb, wn0 + j * 32, ks0 + ks);
+      else b[j] = direct_frag_f16<B_KC, PB>(tb, wn0 + j * 32, ks0 + ks);
     }
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
-      if constexpr (FP8) a[i] = direct_frag_fp8<A_KC, PA>(ta, wm0 + i * 32, ks);
-      else a[i] = direct_frag_f16<A_KC, PA>(ta, wm0 + i * 32, ks);
+      if constexpr (FP8) a[i] = direct_frag_fp8<A_KC, PA>(ta, wm0 + i * 32, ks0 + ks);
+      else a[i] = direct_frag_f16<A_KC, PA>(ta, wm0 + i * 32, ks0 + ks);
     }
   };
   auto issue_stage = [&](int stage, int slot) {
@@ -340,6 +349,34 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_direct_kernel(Ge
   }
 
   __syncthreads();       // every wave is past its last fragment read before the strips overlay the ring
+  if constexpr (Cfg::WAVES_K > 1) {
+    // add the wave groups' accumulators in group order (a fixed order: the result is deterministic);
+    // register r of lane l of group wk >= 1 travels through red[wk-1][wmn][r][l]
+    constexpr int NR = FM * FN * 16;
+    float* red = reinterpret_cast<float*>(lds + T::REDUCE_OFFSET);
+    const int lane = threadIdx.x & 63;
+    if (wk > 0) {
+      float* mine = red + ((size_t)((wk - 1) * Cfg::WAVES_MN + wmn) * NR) * 64 + lane;
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) *US_LDS_PTR(float, mine + ((i * FN + j) * 16 + r) * 64) = acc[i][j][r];
+    }
+    __syncthreads();
+    if (wk > 0) return;
+#pragma unroll
+    for (int k = 1; k < Cfg::WAVES_K; ++k) {
+      const float* theirs = red + ((size_t)((k - 1) * Cfg::WAVES_MN + wmn) * NR) * 64 + lane;
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[i][j][r] += *US_LDS_PTR(const float, theirs + ((i * FN + j) * 16 + r) * 64);
+    }
+  }
   store_block_epilogue<Cfg, EPI, WIDE>(g, acc, lds, m0, n0, split);
 }
 

@@ -13,14 +13,25 @@ namespace us {
 //   D128: 4 waves (2 x 2, 64 x 64 per wave), two workgroups per CU, 64 KB ring
 //   S128: the register-staged kernel for reduction lengths that are not a multiple of the stage
 using CfgD256 = GemmCfg<256, 256, 2, 4, 128, 2, 1>;
+//   K128: grad_W only (both operands K-strided): 8 waves on one 128 x 128 tile, two groups of 2 x 2 that
+//         each take half of every 256-byte stage; one workgroup per CU, no K slices in global memory
 using CfgD128 = GemmCfg<128, 128, 2, 2, 128, 2, 2>;
 using CfgS128 = GemmCfg<128, 128, 2, 2, 128, 2, 2>;
+using CfgK128 = GemmCfg<128, 128, 2, 2, 256, 2, 1, 2>;
 
 inline long ceil_div(long a, long b) { return (a + b - 1) / b; }
 
 // The large tile needs the output to cover the 256 CUs about one and a half times; below that the
 // small tile (two workgroups per CU, four times as many tiles) keeps more of the chip busy.
 inline bool use_big_tile(long M, long N, int splits) { return ceil_div(M, 256) * ceil_div(N, 256) * splits >= 384; }
+
+// grad_W whose 128 x 128 tiles just about cover the CUs once (C3: 4096 x 1024 -> 256 tiles): instead of
+// cutting the long token reduction into slices that travel through HBM, two wave groups of one
+// workgroup share it and add up in LDS.
+inline bool use_wave_split_tile(long M, long N, long K) {
+  const long tiles = ceil_div(M, 128) * ceil_div(N, 128);
+  return !use_big_tile(M, N, 1) && K >= 1024 && K % 256 == 0 && tiles >= 192 && tiles <= 256;
+}
 
 inline GemmArgs make_args(const GemmProblem& p, long k_per_split, int BM, int BN) {
   GemmArgs g{};
@@ -44,10 +55,12 @@ inline GemmArgs make_args(const GemmProblem& p, long k_per_split, int BM, int BN
 
 template <bool DIRECT, class Cfg, bool FP8, int FA, int FB, bool A_KC, bool B_KC, int EPI, bool WIDE>
 hipError_t launch_one(const GemmProblem& p, int splits, long k_per_split, hipStream_t st) {
-  constexpr int LDS = DIRECT ? DirectTile<Cfg, FP8, A_KC, B_KC, WIDE, EPI>::LDS_BYTES
-                             : StagedTile<Cfg, FP8, A_KC, B_KC, WIDE, EPI>::LDS_BYTES;
-  auto kern = DIRECT ? gemm_direct_kernel<Cfg, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>
-                     : gemm_staged_kernel<Cfg, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>;
+  using Tile = typename std::conditional<DIRECT, DirectTile<Cfg, FP8, A_KC, B_KC, WIDE, EPI>,
+                                         StagedTile<Cfg, FP8, A_KC, B_KC, WIDE, EPI>>::type;
+  constexpr int LDS = Tile::LDS_BYTES;
+  void (*kern)(GemmArgs);
+  if constexpr (DIRECT) kern = gemm_direct_kernel<Cfg, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>;
+  else kern = gemm_staged_kernel<Cfg, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>;
   static bool configured = false;  // raising the dynamic-LDS limit is a per-function, once-only call
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -68,6 +81,10 @@ hipError_t launch_sized(const GemmProblem& p, int splits, long k_per_split, hipS
   if (!direct_ok) return launch_one<false, CfgS128, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
   if (use_big_tile(p.M, p.N, splits))
     return launch_one<true, CfgD256, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
+  if constexpr (!A_KC && !B_KC && EPI == EPI_STORE) {
+    if (splits == 1 && use_wave_split_tile(p.M, p.N, p.K))
+      return launch_one<true, CfgK128, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
+  }
   return launch_one<true, CfgD128, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
 }
 

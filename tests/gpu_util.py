@@ -67,14 +67,14 @@ def linear_fwd(X, W, x_dt, w_dt, alpha=0.0, out_dt=us.F16, epi=us.EPI_NONE, epi_
 
 
 def linear_bwd(X, W, G, x_dt, w_dt, g_dt, beta_x=0.0, beta_w=0.0, out_dt=us.F16, epi=us.EPI_NONE, epi_scale=0.0,
-               Zpre=None, want8=False, do_dx=True, do_dw=True, no_workspace=False):
+               Zpre=None, want8=False, do_dx=True, do_dw=True, no_workspace=False, store_dx=True):
     b, n = G.shape
     m = W.shape[0] if W is not None else X.shape[1]
     tX = to_dev(X) if X is not None else None
     tW = to_dev(W) if W is not None else None
     tG = to_dev(G)
     odt = np.float16 if out_dt == us.F16 else np.float32
-    dX = empty((b, m), odt) if do_dx else None
+    dX = empty((b, m), odt) if (do_dx and store_dx) else None      # store_dx=False: GELU' epilogue, codes only
     dW = empty((m, n), odt) if do_dw else None
     tZ = to_dev(Zpre) if Zpre is not None else None
     a8 = empty((b, m), np.uint8) if want8 else None
@@ -82,7 +82,7 @@ def linear_bwd(X, W, G, x_dt, w_dt, g_dt, beta_x=0.0, beta_w=0.0, out_dt=us.F16,
     ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=DEV)
     us.linear_bwd(ptr(tX), ptr(tW), ptr(tG), ptr(dX), ptr(dW), b, m, n, x_dt, w_dt, g_dt, out_dt, beta_x, beta_w, epi,
                   epi_scale, ptr(tZ), ptr(a8), ptr(ws), wsb, stream())
-    return (to_np(dX) if do_dx else None, to_np(dW) if do_dw else None, to_np(a8) if want8 else None)
+    return (to_np(dX) if dX is not None else None, to_np(dW) if do_dw else None, to_np(a8) if want8 else None)
 
 
 # ---- error metric for matmul / GELU outputs ---------------------------------------------------------

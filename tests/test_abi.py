@@ -40,9 +40,11 @@ def test_scales_and_status_strings():
 def test_workspace_rule():
     table_area = 128 * 1024
     assert us.workspace_bytes(32768, 4096, 16384) == table_area     # the output alone fills the chip: no dW slices
-    wb = us.workspace_bytes(8192, 1024, 4096) - table_area
-    assert wb > 0 and wb % (1024 * 4096 * 4) == 0                   # whole FP32 slices of the output
-    assert us.ffn_workspace_bytes(8192, 1024, 4096) >= wb + table_area
+    # 256 tiles of 128 x 128 cover the CUs once: the token reduction is shared by wave groups, no slices
+    assert us.workspace_bytes(8192, 1024, 4096) == table_area
+    wb = us.workspace_bytes(4096, 768, 3072) - table_area           # 144 tiles: sliced
+    assert wb > 0 and wb % (768 * 3072 * 4) == 0                    # whole FP32 slices of the output
+    assert us.ffn_workspace_bytes(4096, 768, 3072) >= wb + table_area
     assert us.workspace_bytes(0, 16, 16) == 0
 
 

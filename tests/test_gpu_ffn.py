@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 class FfnRun:
     """Device buffers of one FFN forward + backward; `dev` tensors stay on the GPU."""
 
-    def __init__(self, X, W1, W2, G, fp8):
+    def __init__(self, X, W1, W2, G, fp8, store_dz16=True):
         self.fp8 = fp8
         T, d = X.shape
         f = W1.shape[1]
@@ -37,6 +37,8 @@ class FfnRun:
         dev["H"] = e((T, f), torch.uint8 if fp8 else torch.float16)
         dev["dZ16"], dev["dX"], dev["dW1"], dev["dW2"] = e((T, f)), e((T, d)), e((d, f)), e((f, d))
         dev["dZ8"] = e((T, f), torch.uint8) if fp8 else None
+        if not store_dz16:
+            dev["dZ16"] = None                     # FP8 only: the layer-1 matmuls read the E5M2 codes
         wsb = us.ffn_workspace_bytes(T, d, f)
         ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=DEV)
         us.ffn_fwd(ptr(dev["Xop"]), ptr(dev["W1op"]), ptr(dev["W2op"]), ptr(dev["Z"]), ptr(dev["H"]), ptr(dev["Y"]),
@@ -113,6 +115,19 @@ def test_small_ragged_ffn_full_comparison(fp8):
     check_ffn(run, np.arange(T), np.arange(f), np.arange(d))
 
 
+def _same_without_fp16_dz(run, X, W1, W2, G):
+    """FP8 step that does not store the FP16 dZ: every other output is bit-identical."""
+    lean = FfnRun(X, W1, W2, G, fp8=True, store_dz16=False)
+    for name in ("Z", "H", "Y", "dZ8", "dX", "dW1", "dW2"):
+        assert torch.equal(lean.dev[name], run.dev[name]), name
+
+
+def test_fp8_ffn_without_fp16_dz_small():
+    T, d, f = 272, 144, 400
+    X, W1, W2, G = synth.ffn_inputs(T, d, f, seed=127)
+    _same_without_fp16_dz(FfnRun(X, W1, W2, G, fp8=True), X, W1, W2, G)
+
+
 def _sample(n, k, seed):
     rng = np.random.default_rng(seed)
     return np.sort(rng.choice(n, size=min(k, n), replace=False))
@@ -141,6 +156,7 @@ def test_c3_bert_large_fp8():
     run = FfnRun(X, W1, W2, G, fp8=True)
     check_ffn(run, _sample(c["T"], 48, 4), _sample(c["f"], 24, 5), _sample(c["d"], 24, 6))
     _variances(run)
+    _same_without_fp16_dz(run, X, W1, W2, G)
 
 
 def test_c5_llm_size_fp8_sampled():

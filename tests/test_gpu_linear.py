@@ -100,6 +100,24 @@ def test_split_k_reduction_of_grad_w():
 
 
 @pytest.mark.parametrize("fp8", [False, True])
+def test_grad_w_wave_split_reduction(fp8):
+    """An output of 192-256 tiles of 128 x 128 with a long token dimension: two wave groups of one
+    workgroup share the reduction and add up in LDS (no workspace).  Ragged in both output dimensions."""
+    b, m, n = 1024, 2000, 1936                                   # 16 x 16 tiles, the last ones partial
+    assert us.workspace_bytes(b, m, n) == 128 * 1024                 # the table area only: no K slices
+    (X, W, G), gdt, odt = _operands(b, m, n, 109, fp8)
+    _, dW, _ = linear_bwd(X, None, G, *gdt, do_dx=False)
+    assert_close(dW, O.linear_bwd_dw(X, G, b ** -0.5, odt[0], odt[2]), "dW wave split")
+    # exact integers: both halves of every stage must land in the right sum
+    Xi, Gi = synth.small_ints(113, 1, (b, m)), synth.small_ints(113, 4, (b, n))
+    if fp8:
+        Xi, Gi = cast_fp8(Xi, us.E4M3), cast_fp8(Gi, us.E5M2)
+    for out_g, out_o in ((us.F32, O.F32), (us.F16, O.F16)):
+        _, dWi, _ = linear_bwd(Xi, None, Gi, *gdt, beta_w=0.125, out_dt=out_g, do_dx=False)
+        assert np.array_equal(dWi, O.linear_bwd_dw(Xi, Gi, 0.125, odt[0], odt[2], out_o))
+
+
+@pytest.mark.parametrize("fp8", [False, True])
 def test_fused_gelu_epilogues(fp8):
     """Stage-wise: Z vs the oracle matmul; H vs oracle GELU of the GPU's own stored Z; the FP8 copy vs the
     oracle cast of the GPU's own stored H (bit exact); the same for GELU' in the grad_X epilogue."""
@@ -122,6 +140,9 @@ def test_fused_gelu_epilogues(fp8):
     dZ, _, dZ8 = linear_bwd(None, W, G, *gdt, epi=us.EPI_GELU_GRAD, Zpre=Zpre, want8=True, do_dw=False)
     assert_close(dZ, O.gelu_bwd(Zpre, dH, bg), "dZ")
     assert np.array_equal(dZ8, O.cast_fp8(dZ, O.E5M2)[0])
+    # codes only (no FP16 dZ stored): the same codes
+    none16, _, dZ8b = linear_bwd(None, W, G, *gdt, epi=us.EPI_GELU_GRAD, Zpre=Zpre, want8=True, do_dw=False, store_dx=False)
+    assert none16 is None and np.array_equal(dZ8b, dZ8)
 
 
 def test_zero_reduction_length_writes_zeros():
