@@ -63,7 +63,7 @@ def test_argument_errors_are_detected_on_the_host():
         (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, F16, F16, F16, 0.0, us.EPI_GELU), 1),   # no aux buffer
         (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, F16, F16, F32, 0.0, us.EPI_GELU, 0.0, 16), 4),
         (lambda: us.linear_bwd(16, 16, 16, 16, 16, 16, 16, 16, E4, E4, E4), 4),   # gradients are E5M2
-        (lambda: us.linear_bwd(16, 16, 16, 16, 16, 8192, 1024, 4096, F16, F16, F16), 5),  # workspace missing
+        (lambda: us.linear_bwd(16, 16, 16, 16, 16, 4096, 768, 3072, F16, F16, F16), 5),   # workspace missing
         (lambda: us.linear_bwd(16, 16, 16, 16, None, 16, 16, 16, F16, F16, F16, F16, 0, 0, us.EPI_GELU_GRAD), 1),
         (lambda: us.linear_bwd(16, 16, 8, 16, 16, 16, 16, 16, F16, F16, F16), 3),
     ]
