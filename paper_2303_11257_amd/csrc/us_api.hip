@@ -147,8 +147,9 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
   if (slices > 0 && (!workspace || workspace_bytes < (size_t)kTableAreaBytes + slices)) return US_ERR_WORKSPACE;
   void* const table = (workspace && workspace_bytes >= (size_t)kTableAreaBytes) ? workspace : nullptr;
   hipStream_t st = as_stream(stream);
+  GemmProblem pdx{}, pdw{};
   if (do_dx) {
-    GemmProblem p{};
+    GemmProblem& p = pdx;
     p.A = G; p.B = W; p.C = dX;
     p.M = b; p.N = m; p.K = n;
     p.lda = n; p.ldb = n; p.ldc = m;
@@ -160,11 +161,9 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
     p.Zpre = (epi == US_EPI_GELU_GRAD) ? Zpre : nullptr;
     p.aux8 = (epi == US_EPI_GELU_GRAD) ? aux8 : nullptr;
     p.table = table;
-    hipError_t e = launch_gemm(p, st);
-    if (e != hipSuccess) return US_ERR_LAUNCH;
   }
   if (do_dw) {
-    GemmProblem p{};
+    GemmProblem& p = pdw;
     p.A = X; p.B = G; p.C = dW;
     p.M = m; p.N = n; p.K = b;
     p.lda = m; p.ldb = n; p.ldc = n;
@@ -174,9 +173,10 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
     p.epi = US_EPI_NONE;
     p.workspace = slices > 0 ? (void*)((char*)workspace + kTableAreaBytes) : nullptr;
     p.workspace_bytes = slices;
-    hipError_t e = launch_gemm(p, st);
-    if (e != hipSuccess) return US_ERR_LAUNCH;
   }
+  if (do_dx && do_dw && gemm_pair_applicable(pdx, pdw)) return from_hip(launch_gemm_pair(pdx, pdw, st));
+  if (do_dx && launch_gemm(pdx, st) != hipSuccess) return US_ERR_LAUNCH;
+  if (do_dw && launch_gemm(pdw, st) != hipSuccess) return US_ERR_LAUNCH;
   return US_OK;
 }
 

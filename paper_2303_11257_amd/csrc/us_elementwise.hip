@@ -186,6 +186,14 @@ __global__ void __launch_bounds__(kThreads) gelu_table_kernel(uint8_t* tab, floa
   const v2h pair = {h, h};
   tab[i] = (uint8_t)cvt_pk_fp8_from_half<US_E4M3>(pair);
 }
+// tab[s * 0x4601 + a] = fp16(alpha_g * gelu(z)) for the FP16 value z with sign s and magnitude bits a <= 0x4600
+__global__ void __launch_bounds__(kThreads) gelu_half_table_kernel(_Float16* tab, float alpha_g) {
+  const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
+  constexpr uint32_t kPer = kGeluHalfLast + 1;
+  if (i >= 2 * kPer) return;
+  const uint32_t bits = (i % kPer) | ((i / kPer) << 15);
+  tab[i] = to_half(gelu_scaled((float)half_from_bits(bits), alpha_g));
+}
 // tab[i] = beta_g * gelu'(|z|) in FP32 for the FP16 magnitudes 0 .. 8.0 (bit patterns 0 .. 0x4800)
 __global__ void __launch_bounds__(kThreads) gelu_slope_table_kernel(float* tab, float beta_g) {
   const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
@@ -245,6 +253,11 @@ hipError_t launch_cast_batch(int count, const void* const* src, void* const* dst
 
 hipError_t launch_gelu_table(void* table, float alpha_g, hipStream_t st) {
   gelu_table_kernel<<<65536 / kThreads, kThreads, 0, st>>>((uint8_t*)table, alpha_g);
+  return hipGetLastError();
+}
+
+hipError_t launch_gelu_half_table(void* table, float alpha_g, hipStream_t st) {
+  gelu_half_table_kernel<<<(2 * (kGeluHalfLast + 1) + kThreads - 1) / kThreads, kThreads, 0, st>>>((_Float16*)table, alpha_g);
   return hipGetLastError();
 }
 

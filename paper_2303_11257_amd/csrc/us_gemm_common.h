@@ -9,7 +9,10 @@ namespace us {
 
 // EPI_GELU_TAB / EPI_GELU_GRAD_TAB: same results as EPI_GELU (FP8 activation only) / EPI_GELU_GRAD,
 // taken from a table over the FP16 pre-activation that the workgroup copies into LDS.
-enum GemmEpi : int { EPI_STORE = 0, EPI_GELU = 1, EPI_GELU_GRAD = 2, EPI_PARTIAL = 3, EPI_GELU_TAB = 4, EPI_GELU_GRAD_TAB = 5 };
+// EPI_GELU_TAB16: EPI_GELU with an FP16 activation output (and optionally its FP8 copy), from a table.
+enum GemmEpi : int {
+  EPI_STORE = 0, EPI_GELU = 1, EPI_GELU_GRAD = 2, EPI_PARTIAL = 3, EPI_GELU_TAB = 4, EPI_GELU_GRAD_TAB = 5, EPI_GELU_TAB16 = 6
+};
 
 //   C[M,N] = epilogue( scale * sum_k A(m,k) * B(n,k) )
 // An operand is K-contiguous (element (r,k) at base[r*ld + k]) or K-strided (element (r,k) at
@@ -109,6 +112,30 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
     *reinterpret_cast<v2i*>(g.aux8 + idx) = w;
     return;
   }
+  if (EPI == EPI_GELU_TAB16) {
+    *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = y;   // the FP16 matmul result, kept for backward
+    v8h r;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const uint32_t zb = half_bits(y[k]);
+      const uint32_t a = zb & 0x7fffu;
+      const uint32_t neg = zb >> 15;
+      const uint32_t i = (a < (uint32_t)kGeluHalfLast ? a : (uint32_t)kGeluHalfLast) + neg * (uint32_t)(kGeluHalfLast + 1);
+      _Float16 t = half_from_bits(*US_LDS_PTR(const unsigned short, lut + i * 2));
+      // beyond the table: alpha_g * z for positive z (also +inf, NaN), -0 for finite negative z, NaN for -inf
+      const _Float16 far = neg ? half_from_bits(a >= 0x7c00u ? 0x7e00u : 0x8000u) : to_half(g.epi_scale * (float)y[k]);
+      r[k] = (a > (uint32_t)kGeluHalfLast) ? far : t;
+    }
+    if (g.aux16) *reinterpret_cast<v8h*>(g.aux16 + idx) = r;
+    if (g.aux8) {
+      const v2h p0 = {r[0], r[1]}, p1 = {r[2], r[3]}, p2 = {r[4], r[5]}, p3 = {r[6], r[7]};
+      v2i w;
+      w.x = (int)(cvt_pk_fp8_from_half<AUX_FMT>(p0) | (cvt_pk_fp8_from_half<AUX_FMT>(p1) << 16));
+      w.y = (int)(cvt_pk_fp8_from_half<AUX_FMT>(p2) | (cvt_pk_fp8_from_half<AUX_FMT>(p3) << 16));
+      *reinterpret_cast<v2i*>(g.aux8 + idx) = w;
+    }
+    return;
+  }
   if (EPI == EPI_GELU_GRAD_TAB) {
     v8h r;
 #pragma unroll
@@ -162,7 +189,9 @@ struct EpiStrip {
   static constexpr int ES = WIDE ? 4 : 2;
   static constexpr int PITCH = Cfg::WN * ES + 16;
   static constexpr int STRIP_BYTES = 32 * PITCH * Cfg::WAVES_MN;
-  static constexpr int TABLE_BYTES = EPI == EPI_GELU_TAB ? kGeluTableBytes : EPI == EPI_GELU_GRAD_TAB ? kGeluSlopeTableBytes : 0;
+  static constexpr int TABLE_BYTES = EPI == EPI_GELU_TAB ? kGeluTableBytes
+                                     : EPI == EPI_GELU_GRAD_TAB ? kGeluSlopeTableBytes
+                                     : EPI == EPI_GELU_TAB16 ? kGeluHalfTableBytes : 0;
   static constexpr int BYTES = STRIP_BYTES + TABLE_BYTES;     // the table sits behind the strips
 };
 

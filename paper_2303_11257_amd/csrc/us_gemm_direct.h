@@ -200,8 +200,10 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+// One output tile (number `bid` in launch order, K slice `split`) by the whole workgroup; `lds` is the
+// workgroup's dynamic LDS (DirectTile::LDS_BYTES).
 template <class Cfg, bool FP8, int FA, int FB, bool A_KC, bool B_KC, int EPI, bool WIDE>
-__global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_direct_kernel(GemmArgs g) {
+__device__ __forceinline__ void gemm_direct_tile(const GemmArgs& g, int bid, long split, uint8_t* lds) {
   using T = DirectTile<Cfg, FP8, A_KC, B_KC, WIDE, EPI>;
   constexpr int BM = Cfg::BM, BN = Cfg::BN, THREADS = Cfg::THREADS, BKB = Cfg::BKB, NST = Cfg::NST;
   constexpr int FM = Cfg::FM, FN = Cfg::FN;
@@ -210,13 +212,10 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_direct_kernel(Ge
   constexpr int PA = T::PA, PB = T::PB;
   constexpr int LOADS = T::A_LOADS + T::B_LOADS;       // per thread and stage
 
-  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-
   const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
   int tm, tn;
-  tile_of_block((int)blockIdx.x, tiles_m, tiles_n, g.xcd_gm, g.xcd_gn, g.grp_w, tm, tn);
+  tile_of_block(bid, tiles_m, tiles_n, g.xcd_gm, g.xcd_gn, g.grp_w, tm, tn);
   const long m0 = (long)tm * BM, n0 = (long)tn * BN;
-  const long split = blockIdx.y;
   const long k_begin = split * g.k_per_split;
   const long k_end = (k_begin + g.k_per_split < g.K) ? k_begin + g.k_per_split : g.K;
   const int nstages = (k_end > k_begin) ? (int)((k_end - k_begin) / T::BK) : 0;   // host guarantees divisibility
@@ -378,6 +377,38 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_direct_kernel(Ge
     }
   }
   store_block_epilogue<Cfg, EPI, WIDE>(g, acc, lds, m0, n0, split);
+}
+
+template <class Cfg, bool FP8, int FA, int FB, bool A_KC, bool B_KC, int EPI, bool WIDE>
+__global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_direct_kernel(GemmArgs g) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  gemm_direct_tile<Cfg, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(g, (int)blockIdx.x, (long)blockIdx.y, lds);
+}
+
+// Two independent GEMMs in one launch (the two products of a layer's backward pass), for tile shapes
+// with the same workgroup size: the first nb workgroups work on problem B (grad_W: few tiles, long main
+// loop), the rest on problem A (grad_X).  Compared with two launches there is no drain between the
+// two, and because the B tiles finish at slightly different times the A tiles start staggered: their
+// epilogues (GELU' over a large output: a burst of HBM reads, vector ALU work, HBM writes) no longer
+// hit every CU at the same moment, while launched on their own all CUs run in lockstep.  (Interleaving
+// A and B tiles more finely was measured to be slower than either.)
+// nb must be a multiple of 8, so that both problems keep their XCD-aware tile walk.
+template <class Cfg, bool FP8, int FA, int FB, bool A_KC, bool B_KC, int EPI, bool WIDE>
+struct GemmKind {
+  using Tile = DirectTile<Cfg, FP8, A_KC, B_KC, WIDE, EPI>;
+  static constexpr int THREADS = Cfg::THREADS, BM = Cfg::BM, BN = Cfg::BN;
+  __device__ static __forceinline__ void run(const GemmArgs& g, int bid, uint8_t* lds) {
+    gemm_direct_tile<Cfg, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(g, bid, 0, lds);
+  }
+};
+
+template <class KA, class KB>
+__global__ void __launch_bounds__(KA::THREADS, 1) gemm_pair_kernel(GemmArgs a, GemmArgs b, int nb) {
+  static_assert(KA::THREADS == KB::THREADS, "one workgroup size for both problems");
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  const int bid = (int)blockIdx.x;
+  if (bid < nb) KB::run(b, bid, lds);
+  else KA::run(a, bid - nb, lds);
 }
 
 }  // namespace us

@@ -18,6 +18,9 @@ using CfgD256 = GemmCfg<256, 256, 2, 4, 128, 2, 1>;
 using CfgD128 = GemmCfg<128, 128, 2, 2, 128, 2, 2>;
 using CfgS128 = GemmCfg<128, 128, 2, 2, 128, 2, 2>;
 using CfgK128 = GemmCfg<128, 128, 2, 2, 256, 2, 1, 2>;
+//   M256: 256 x 128 tile, 8 waves as two groups of 2 x 2 sharing every stage's k-steps, three stages; as
+//         fast as D128 on its own, used where a 512-thread shape is needed next to K128 in a paired launch
+using CfgM256 = GemmCfg<256, 128, 2, 2, 128, 3, 1, 2>;
 
 inline long ceil_div(long a, long b) { return (a + b - 1) / b; }
 

@@ -1,0 +1,63 @@
+// Both products of a layer's backward pass (grad_X and grad_W) in one launch, when grad_X uses the
+// large tile and grad_W the wave-split small tile (both 512 threads): see gemm_pair_kernel.
+#include "us_gemm_dispatch.h"
+
+namespace us {
+
+namespace {
+
+template <class KA, class KB>
+hipError_t launch_pair(const GemmProblem& dx, const GemmProblem& dw, hipStream_t st) {
+  constexpr int LDS = KA::Tile::LDS_BYTES > KB::Tile::LDS_BYTES ? KA::Tile::LDS_BYTES : KB::Tile::LDS_BYTES;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_pair_kernel<KA, KB>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const GemmArgs a = make_args(dx, dx.K, KA::BM, KA::BN);
+  const GemmArgs b = make_args(dw, dw.K, KB::BM, KB::BN);
+  const long tiles_a = ceil_div(dx.M, KA::BM) * ceil_div(dx.N, KA::BN), tiles_b = ceil_div(dw.M, KB::BM) * ceil_div(dw.N, KB::BN);
+  gemm_pair_kernel<KA, KB><<<(unsigned)(tiles_a + tiles_b), KA::THREADS, LDS, st>>>(a, b, (int)tiles_b);
+  return hipGetLastError();
+}
+
+template <bool FP8>
+hipError_t launch_pair_typed(const GemmProblem& dx, const GemmProblem& dw, hipStream_t st) {
+  constexpr int FG = FP8 ? 1 : 0;                     // gradient operand format (E5M2) where it applies
+  using KW = GemmKind<CfgK128, FP8, 0, FG, false, false, EPI_STORE, false>;
+  if (dx.epi == US_EPI_GELU_GRAD) {
+    hipError_t e = launch_gelu_slope_table(dx.table, dx.epi_scale, st);
+    if (e != hipSuccess) return e;
+    return launch_pair<GemmKind<CfgD256, FP8, FG, 0, true, true, EPI_GELU_GRAD_TAB, false>, KW>(dx, dw, st);
+  }
+  if (use_big_tile(dx.M, dx.N, 1)) return launch_pair<GemmKind<CfgD256, FP8, FG, 0, true, true, EPI_STORE, false>, KW>(dx, dw, st);
+  return launch_pair<GemmKind<CfgM256, FP8, FG, 0, true, true, EPI_STORE, false>, KW>(dx, dw, st);
+}
+
+// grad_X without an epilogue whose 256 x 128 tiles cover the CUs about once
+bool mid_tile_ok(const GemmProblem& dx) {
+  const long t = ceil_div(dx.M, 256) * ceil_div(dx.N, 128);
+  return dx.epi == US_EPI_NONE && t >= 192 && t <= 320;
+}
+
+}  // namespace
+
+bool gemm_pair_applicable(const GemmProblem& dx, const GemmProblem& dw) {
+  const bool fp8 = dx.a_dt != US_F16;
+  if ((dw.a_dt != US_F16) != fp8) return false;
+  if (!(dx.a_kc && dx.b_kc) || dw.a_kc || dw.b_kc) return false;
+  if (dx.c_dt != US_F16 || dw.c_dt != US_F16 || dw.epi != US_EPI_NONE) return false;
+  const long bk = fp8 ? 128 : 64;
+  if (dx.K <= 0 || dx.K % bk || !(use_big_tile(dx.M, dx.N, 1) || mid_tile_ok(dx))) return false;
+  if (dx.epi == US_EPI_GELU_GRAD && !dx.table) return false;       // the arithmetic epilogue is launched on its own
+  if (dx.epi != US_EPI_NONE && dx.epi != US_EPI_GELU_GRAD) return false;
+  if (!use_wave_split_tile(dw.M, dw.N, dw.K)) return false;
+  return (ceil_div(dw.M, 128) * ceil_div(dw.N, 128)) % 8 == 0;
+}
+
+hipError_t launch_gemm_pair(const GemmProblem& dx, const GemmProblem& dw, hipStream_t st) {
+  return dx.a_dt != US_F16 ? launch_pair_typed<true>(dx, dw, st) : launch_pair_typed<false>(dx, dw, st);
+}
+
+}  // namespace us

@@ -50,8 +50,14 @@ size_t gemm_workspace_bytes(long M, long N, long K);
 
 hipError_t launch_gemm(const GemmProblem& p, hipStream_t stream);
 
+// grad_X (dx) and grad_W (dw) of one layer in a single launch with interleaved tiles; only for the
+// shape / type combinations gemm_pair_applicable accepts (results are the same as two launches).
+bool gemm_pair_applicable(const GemmProblem& dx, const GemmProblem& dw);
+hipError_t launch_gemm_pair(const GemmProblem& dx, const GemmProblem& dw, hipStream_t stream);
+
 // Fill the tables of the table-driven GELU epilogues (layouts in us_device.h).
 hipError_t launch_gelu_table(void* table, float alpha_g, hipStream_t stream);
 hipError_t launch_gelu_slope_table(void* table, float beta_g, hipStream_t stream);
+hipError_t launch_gelu_half_table(void* table, float alpha_g, hipStream_t stream);
 
 }  // namespace us

@@ -221,3 +221,68 @@ def test_table_driven_gelu_epilogues_equal_the_arithmetic_ones():
     ref = O.gelu_bwd(Zpre[rows], dH, O.gelu_scales()[1])
     fin = np.isfinite(ref.astype(np.float32))
     assert_close(np.where(fin, dZ1[rows], 0), np.where(fin, ref, 0), "dZ (table)")
+
+
+def test_table_driven_gelu_fp16_output_equals_the_arithmetic_one():
+    """FP16 operands, FP16 activation out: the table (|z| <= 6, both signs) plus its closed forms beyond
+    must reproduce the arithmetic epilogue bit for bit.  Z is steered through every interesting value by
+    a one-hot X row block: Z[i, j] = W[k(i), j] exactly (alpha = 1)."""
+    b, m, n = 8192, 64, 4096                         # 32 x 16 tiles of 256: the table path
+    vals = np.arange(65536, dtype=np.uint32).astype(np.uint16).view(np.float16)      # every FP16 pattern
+    W = vals.reshape(16, 4096).copy()                # 16 reduction rows hold all 65536 patterns
+    W[~np.isfinite(W.astype(np.float32))] = 0        # (0 * inf would poison whole columns; see below)
+    W = np.concatenate([W, np.zeros((m - 16, n), np.float16)])
+    W[16, :] = 65504.0
+    X = np.zeros((b, m), np.float16)
+    X[np.arange(b), np.arange(b) % 16] = 1.0         # row i selects reduction row i % 16
+    X[4000, 16], X[4001, 16], X[4002, 3] = 2.0, -2.0, np.nan     # rows of +inf, -inf and NaN in Z
+    kw = dict(alpha=1.0, epi=us.EPI_GELU, want16=True, want8=False)
+    Z0, H0, _ = linear_fwd(X, W, us.F16, us.F16, **kw)
+    Z1, H1, _ = linear_fwd(X, W, us.F16, us.F16, workspace_bytes=us.workspace_bytes(b, m, n), **kw)
+    fin = np.ones((16, n), bool)
+    assert np.array_equal(Z1[:16], W[:16]) and np.array_equal(Z0.view(np.uint16), Z1.view(np.uint16))   # Z is W (-0 -> +0)
+    assert np.all(Z1[4000] == np.inf) and np.all(Z1[4001] == -np.inf) and np.isnan(Z1[4002].astype(np.float32)).all()
+    assert np.all(H1[4000] == np.inf) and np.isnan(H1[4001].astype(np.float32)).all()
+    nan0, nan1 = np.isnan(H0.astype(np.float32)), np.isnan(H1.astype(np.float32))
+    assert np.array_equal(nan0, nan1)
+    assert np.array_equal(H0.view(np.uint16)[~nan0], H1.view(np.uint16)[~nan1])
+    # a quarter of everything: tiny negative products round to -0, which a sum of products cannot give
+    kw["alpha"] = 0.25
+    Zq0, Hq0, _ = linear_fwd(X, W, us.F16, us.F16, **kw)
+    Zq1, Hq1, _ = linear_fwd(X, W, us.F16, us.F16, workspace_bytes=us.workspace_bytes(b, m, n), **kw)
+    assert (Zq1[:16].view(np.uint16) == 0x8000).any()
+    nq = np.isnan(Hq0.astype(np.float32))
+    assert np.array_equal(nq, np.isnan(Hq1.astype(np.float32))) and np.array_equal(Hq0.view(np.uint16)[~nq], Hq1.view(np.uint16)[~nq])
+    # and against the oracle on the 65536 distinct inputs (at most one FP16 ulp apart, rarely)
+    ref = O.gelu_fwd(Z1[:16], O.gelu_scales()[0])
+    ok = np.isfinite(ref.astype(np.float32)) & fin
+    assert_close(np.where(ok, H1[:16], 0), np.where(ok, ref, 0), "H (table, FP16)")
+
+
+@pytest.mark.parametrize("fp8", [False, True])
+@pytest.mark.parametrize("shape", [(8192, 4096, 1024), (8192, 1024, 4096)])
+def test_paired_grad_x_grad_w_launch_equals_separate_launches(fp8, shape):
+    """A grad_X of large (or 256 x 128) tiles together with a grad_W of about one small tile per CU goes
+    out as one launch; every output must equal, bit for bit, what the two separate launches give.
+    Shapes: grad_X 8192 x 4096 (512 large tiles) with grad_W 4096 x 1024, and grad_X 8192 x 1024
+    (256 tiles of 256 x 128; no GELU' there) with grad_W 1024 x 4096."""
+    b, m, n = shape
+    (X, W, G), gdt, odt = _operands(b, m, n, 149, fp8)
+    Zpre = synth.normal(149, 7, (b, m))
+    for epi in (us.EPI_NONE, us.EPI_GELU_GRAD):
+        kw = dict(epi=epi, Zpre=Zpre if epi else None, want8=bool(epi) and fp8)
+        dX, dW, c8 = linear_bwd(X, W, G, *gdt, **kw)                       # paired
+        dX1, _, c81 = linear_bwd(None, W, G, *gdt, do_dw=False, **kw)
+        _, dW1, _ = linear_bwd(X, None, G, *gdt, do_dx=False)
+        if m >= 4096 or epi:
+            assert np.array_equal(dX.view(np.uint16), dX1.view(np.uint16)), epi
+        else:      # the paired grad_X adds its k-steps in two interleaved halves: same sum, another order
+            assert_close(dX, dX1, "dX paired vs separate")
+            assert np.mean(dX.view(np.uint16) != dX1.view(np.uint16)) < 0.2
+        assert np.array_equal(dW.view(np.uint16), dW1.view(np.uint16)), epi
+        if c8 is not None:
+            assert np.array_equal(c8, c81)
+    rows, cols = [0, 1, 4097, 8191], [0, 5, 1023]
+    assert_close(dW[:, cols], O.linear_bwd_dw(X, np.ascontiguousarray(G[:, cols]), b ** -0.5, odt[0], odt[2]), "dW paired")
+    dH = O.linear_bwd_dx(G[rows], W, n ** -0.5, odt[2], odt[1])
+    assert_close(dX[rows], O.gelu_bwd(Zpre[rows], dH, O.gelu_scales()[1]), "dZ paired")
