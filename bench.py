@@ -54,6 +54,9 @@ class Ffn:
         self.dZ8 = e((T, f), u8) if fp8 else None
         self.wsb = us.ffn_workspace_bytes(T, d, f)
         self.ws = torch.empty(max(self.wsb, 16), dtype=u8, device=dev)
+        # the GELU tables depend on the two scale factors only: built once here, like the workspace itself
+        us.gelu_tables(self.ws.data_ptr(), self.wsb, 0.0, 0.0, torch.cuda.current_stream().cuda_stream)
+        self.mode = (us.FFN_FP8 if fp8 else 0) | us.FFN_TABLES_READY
         self.flop = 12.0 * T * d * f
 
     def p(self, t):
@@ -77,12 +80,12 @@ class Ffn:
             X, W1, W2, G = self.X, self.W1, self.W2, self.G
         a16, a8 = (None, self.H) if self.fp8 else (self.H, None)
         out.append(("fwd1_gelu", "gemm", gemm, 0.0, lambda: us.linear_fwd(p(X), p(W1), p(self.Z), T, d, f, op, op, us.F16, 0.0,
-                                                                         us.EPI_GELU, 0.0, p(a16), p(a8), p(self.ws), self.wsb, st)))
+                                                                         us.EPI_GELU | us.EPI_TABLES_READY, 0.0, p(a16), p(a8), p(self.ws), self.wsb, st)))
         out.append(("fwd2", "gemm", gemm, 0.0, lambda: us.linear_fwd(p(self.H), p(W2), p(self.Y), T, f, d, op, op, us.F16, 0.0,
                                                                     us.EPI_NONE, 0.0, None, None, None, 0, st)))
         out.append(("dx2_gelugrad", "gemm", gemm, 0.0,
                     lambda: us.linear_bwd(None, p(W2), p(G), p(self.dZ16), None, T, f, d, op, op, gr, us.F16, 0.0, 0.0,
-                                          us.EPI_GELU_GRAD, 0.0, p(self.Z), p(self.dZ8), p(self.ws), self.wsb, st)))
+                                          us.EPI_GELU_GRAD | us.EPI_TABLES_READY, 0.0, p(self.Z), p(self.dZ8), p(self.ws), self.wsb, st)))
         out.append(("dw2", "gemm", gemm, 0.0,
                     lambda: us.linear_bwd(p(self.H), None, p(G), None, p(self.dW2), T, f, d, op, op, gr, us.F16, 0.0, 0.0,
                                           us.EPI_NONE, 0.0, None, None, p(self.ws), self.wsb, st)))
@@ -106,9 +109,9 @@ class Ffn:
             X, W1, W2, G = self.X8, self.W1_8, self.W2_8, self.G8
         else:
             X, W1, W2, G = self.X, self.W1, self.W2, self.G
-        us.ffn_fwd(p(X), p(W1), p(W2), p(self.Z), p(self.H), p(self.Y), T, d, f, self.fp8, p(self.ws), self.wsb, st)
+        us.ffn_fwd(p(X), p(W1), p(W2), p(self.Z), p(self.H), p(self.Y), T, d, f, self.mode, p(self.ws), self.wsb, st)
         us.ffn_bwd(p(X), p(W1), p(W2), p(self.Z), p(self.H), p(G), p(self.dZ16), p(self.dZ8), p(self.dX), p(self.dW1),
-                   p(self.dW2), T, d, f, self.fp8, p(self.ws), self.wsb, st)
+                   p(self.dW2), T, d, f, self.mode, p(self.ws), self.wsb, st)
 
 
 def time_steps(torch, fn, steps, warmup):

@@ -47,8 +47,19 @@ typedef enum { US_F32 = 0, US_F16 = 1, US_E4M3 = 2, US_E5M2 = 3 } us_dtype;
 typedef enum {
   US_EPI_NONE = 0,
   US_EPI_GELU = 1,       /* forward: also emit the unit-scaled GELU of the output            */
-  US_EPI_GELU_GRAD = 2   /* grad_X: multiply by the unit-scaled GELU derivative of Zpre     */
+  US_EPI_GELU_GRAD = 2,  /* grad_X: multiply by the unit-scaled GELU derivative of Zpre     */
+  /* flag, OR-ed onto one of the two above: the table area of the workspace already holds the GELU
+   * tables for this epi_scale (us_gelu_tables) and must not be rebuilt by the call                */
+  US_EPI_TABLES_READY = 0x100
 } us_epilogue;
+
+/* The first US_TABLE_AREA_BYTES of every workspace belong to the tables of the table-driven GELU
+ * epilogues (three tables at fixed offsets; a call only touches the one it uses). */
+#define US_TABLE_AREA_BYTES (256 * 1024)
+
+/* mode bits of us_ffn_fwd / us_ffn_bwd */
+#define US_FFN_FP8 1            /* operands are FP8 codes (else FP16)                                   */
+#define US_FFN_TABLES_READY 2   /* as US_EPI_TABLES_READY, for the GELU / GELU' inside the FFN calls  */
 
 /* Counters of the scaled cast; device memory; added to, never cleared, by us_cast_fp8. */
 typedef struct {
@@ -99,10 +110,12 @@ us_status us_cast_fp8_batch(int count, const void* const* src, void* const* dst,
  * stores H to aux16 (FP16 [b,n]) if aux16 != NULL and the E4M3 cast of that FP16 H (scale 1) to aux8
  * ([b,n] bytes) if aux8 != NULL; at least one of them must be given.  epi_scale <= 0 selects the
  * unit-scaling factor 1.7009.  Y itself is always written (the backward pass needs it).
- * workspace may be NULL.  With FP8 operands, epi = US_EPI_GELU, aux16 == NULL and a workspace of at
- * least 128 KB (16-byte aligned, contents undefined on entry and exit) large problems take the
- * activation codes from a table over the 65536 possible FP16 values of Y that is first built in the
- * workspace; the result is the same as without a workspace.
+ * workspace may be NULL.  With epi = US_EPI_GELU, exactly one of aux16 / aux8 and a workspace of at
+ * least US_TABLE_AREA_BYTES (16-byte aligned) large problems take the activation from a table over
+ * the FP16 values of Y; the result is the same as without a workspace.  By default the call first
+ * builds that table in the workspace (so its contents may be undefined on entry); with
+ * US_EPI_GELU | US_EPI_TABLES_READY the caller vouches that us_gelu_tables filled this workspace
+ * with the same epi_scale and that its first US_TABLE_AREA_BYTES were not overwritten since.
  */
 us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, long n,
                         us_dtype x_dt, us_dtype w_dt, us_dtype y_dt, float alpha,
@@ -122,11 +135,13 @@ us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, l
  * i.e. the scaled-GELU backward of Sec. 5.1 applied to the FP16-rounded matmul gradient; if aux8 !=
  * NULL the E5M2 cast of that FP16 dX is written there, and dX itself may then be NULL (only the
  * codes are stored: the values are the same).  epi_scale <= 0 selects 1.4811.
- * Workspace (16-byte aligned, contents undefined on entry and exit): us_workspace_bytes(b, m, n) is
- * the size that serves every use.  Its first 128 KB hold the table of the table-driven GELU' epilogue
- * (same results as the arithmetic one; used for large problems when at least 128 KB are given), the
- * rest the FP32 slices of the dW reduction over tokens.  A workspace is REQUIRED only when dW needs
- * slices, i.e. when us_workspace_bytes(b, m, n) > 128 KB: then fewer bytes give US_ERR_WORKSPACE.
+ * Workspace (16-byte aligned): us_workspace_bytes(b, m, n) is the size that serves every use.  Its
+ * first US_TABLE_AREA_BYTES are the table area (the table-driven GELU' epilogue gives the same results
+ * as the arithmetic one and is used for large problems when the area is there; it is rebuilt by the
+ * call unless epi carries US_EPI_TABLES_READY, see us_linear_fwd), the rest holds the FP32 slices of
+ * the dW reduction over tokens (contents undefined on entry and exit).  A workspace is REQUIRED only
+ * when dW needs slices, i.e. when us_workspace_bytes(b, m, n) > US_TABLE_AREA_BYTES: then fewer
+ * bytes give US_ERR_WORKSPACE.
  */
 us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, void* dW,
                         long b, long m, long n, us_dtype x_dt, us_dtype w_dt, us_dtype g_dt,
@@ -135,8 +150,16 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
                         void* stream);
 
 /* Bytes of workspace that serve every use by us_linear_fwd / us_linear_bwd for a [b,m] x [m,n] layer:
- * 128 KB of table area plus the dW slices (0 for a non-positive dimension). */
+ * the table area plus the dW slices (0 for a non-positive dimension). */
 size_t us_workspace_bytes(long b, long m, long n);
+
+/*
+ * Fill the table area of a workspace (its first US_TABLE_AREA_BYTES; workspace_bytes must be at least
+ * that) with all GELU tables for the factors alpha_g / beta_g (<= 0: 1.7009 / 1.4811, Table A.2).  The
+ * tables depend on nothing else, so a training loop calls this once and then passes
+ * US_EPI_TABLES_READY / US_FFN_TABLES_READY; the matmul calls never write to the table area then.
+ */
+us_status us_gelu_tables(void* workspace, size_t workspace_bytes, float alpha_g, float beta_g, void* stream);
 
 /*
  * Stand-alone unit-scaled GELU (Table A.2 "Activations"; backward by the f_grad rule of Sec. 5.1).
@@ -154,8 +177,9 @@ us_status us_gelu_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtyp
  * direction, composed of the operations above with the scales of Table A.2 (alpha = fan_in^-1/2,
  * beta_x = fan_out^-1/2, beta_w = tokens^-1/2, GELU 1.7009 / 1.4811).
  *
- * fp8 == 0: operands are the FP16 tensors.  fp8 != 0: X8, W1_8, W2_8 are E4M3 and G8 is E5M2 (made
- * by us_cast_fp8), H8 / dZ8 are written by the fused epilogues.
+ * mode: bit US_FFN_FP8 clear: operands are the FP16 tensors; set ("fp8" below): X8, W1_8, W2_8 are E4M3
+ * and G8 is E5M2 (made by us_cast_fp8), H8 / dZ8 are written by the fused epilogues.  Bit
+ * US_FFN_TABLES_READY: the workspace's table area was filled by us_gelu_tables (default factors).
  *
  * us_ffn_fwd:  Z[T,f] = fp16(d^-1/2 X W1);  H = fp16(1.7009 gelu(Z));  Y[T,d] = fp16(f^-1/2 H W2)
  *   X [T,d], W1 [d,f], W2 [f,d]: F16 (fp8 == 0) or E4M3 (fp8 != 0)
@@ -169,10 +193,10 @@ us_status us_gelu_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtyp
  *   only enables the table-driven GELU; required for us_ffn_bwd whenever a dW needs slices).
  */
 us_status us_ffn_fwd(const void* X, const void* W1, const void* W2, void* Z, void* H, void* Y,
-                     long T, long d, long f, int fp8, void* workspace, size_t workspace_bytes, void* stream);
+                     long T, long d, long f, int mode, void* workspace, size_t workspace_bytes, void* stream);
 us_status us_ffn_bwd(const void* X, const void* W1, const void* W2, const void* Z, const void* H,
                      const void* G, void* dZ16, void* dZ8, void* dX, void* dW1, void* dW2,
-                     long T, long d, long f, int fp8, void* workspace, size_t workspace_bytes,
+                     long T, long d, long f, int mode, void* workspace, size_t workspace_bytes,
                      void* stream);
 size_t us_ffn_workspace_bytes(long T, long d, long f);
 

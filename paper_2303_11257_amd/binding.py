@@ -11,6 +11,9 @@ import os
 
 F32, F16, E4M3, E5M2 = 0, 1, 2, 3
 EPI_NONE, EPI_GELU, EPI_GELU_GRAD = 0, 1, 2
+EPI_TABLES_READY = 0x100            # flag for EPI_GELU / EPI_GELU_GRAD: tables prebuilt by gelu_tables()
+FFN_FP8, FFN_TABLES_READY = 1, 2    # mode bits of ffn_fwd / ffn_bwd
+TABLE_AREA_BYTES = 256 * 1024
 STATUS = {0: "US_OK", 1: "US_ERR_NULL", 2: "US_ERR_SHAPE", 3: "US_ERR_ALIGN", 4: "US_ERR_DTYPE",
           5: "US_ERR_WORKSPACE", 6: "US_ERR_LAUNCH"}
 
@@ -47,6 +50,7 @@ def lib() -> ctypes.CDLL:
     L.us_linear_fwd.argtypes = [vp, vp, vp, l, l, l, i, i, i, f, i, f, vp, vp, vp, sz, vp]
     L.us_linear_bwd.argtypes = [vp, vp, vp, vp, vp, l, l, l, i, i, i, i, f, f, i, f, vp, vp, vp, sz, vp]
     L.us_workspace_bytes.argtypes = [l, l, l]
+    L.us_gelu_tables.argtypes = [vp, sz, f, f, vp]
     L.us_workspace_bytes.restype = sz
     L.us_gelu_fwd.argtypes = [vp, vp, sz, i, f, vp]
     L.us_gelu_bwd.argtypes = [vp, vp, vp, sz, i, f, vp]
@@ -55,7 +59,7 @@ def lib() -> ctypes.CDLL:
     L.us_ffn_workspace_bytes.argtypes = [l, l, l]
     L.us_ffn_workspace_bytes.restype = sz
     for name in ("us_linear_scales", "us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd",
-                 "us_ffn_fwd", "us_ffn_bwd"):
+                 "us_gelu_tables", "us_ffn_fwd", "us_ffn_bwd"):
         getattr(L, name).restype = i
     _lib = L
     return L
@@ -104,6 +108,10 @@ def workspace_bytes(b: int, m: int, n: int) -> int:
     return int(lib().us_workspace_bytes(b, m, n))
 
 
+def gelu_tables(workspace, workspace_bytes, alpha_g=0.0, beta_g=0.0, stream=None):
+    _check(lib().us_gelu_tables(workspace, workspace_bytes, alpha_g, beta_g, stream), "us_gelu_tables")
+
+
 def gelu_fwd(z, h, n, dt=F16, alpha_g=0.0, stream=None):
     _check(lib().us_gelu_fwd(z, h, n, dt, alpha_g, stream), "us_gelu_fwd")
 
@@ -112,12 +120,13 @@ def gelu_bwd(z, gh, gz, n, dt=F16, beta_g=0.0, stream=None):
     _check(lib().us_gelu_bwd(z, gh, gz, n, dt, beta_g, stream), "us_gelu_bwd")
 
 
-def ffn_fwd(X, W1, W2, Z, H, Y, T, d, f, fp8, workspace=None, workspace_bytes=0, stream=None):
-    _check(lib().us_ffn_fwd(X, W1, W2, Z, H, Y, T, d, f, int(fp8), workspace, workspace_bytes, stream), "us_ffn_fwd")
+def ffn_fwd(X, W1, W2, Z, H, Y, T, d, f, mode, workspace=None, workspace_bytes=0, stream=None):
+    """mode: FFN_FP8 (or True) for FP8 operands, optionally | FFN_TABLES_READY."""
+    _check(lib().us_ffn_fwd(X, W1, W2, Z, H, Y, T, d, f, int(mode), workspace, workspace_bytes, stream), "us_ffn_fwd")
 
 
-def ffn_bwd(X, W1, W2, Z, H, G, dZ16, dZ8, dX, dW1, dW2, T, d, f, fp8, workspace=None, workspace_bytes=0, stream=None):
-    _check(lib().us_ffn_bwd(X, W1, W2, Z, H, G, dZ16, dZ8, dX, dW1, dW2, T, d, f, int(fp8), workspace, workspace_bytes,
+def ffn_bwd(X, W1, W2, Z, H, G, dZ16, dZ8, dX, dW1, dW2, T, d, f, mode, workspace=None, workspace_bytes=0, stream=None):
+    _check(lib().us_ffn_bwd(X, W1, W2, Z, H, G, dZ16, dZ8, dX, dW1, dW2, T, d, f, int(mode), workspace, workspace_bytes,
                             stream), "us_ffn_bwd")
 
 

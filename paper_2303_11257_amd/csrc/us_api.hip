@@ -86,6 +86,20 @@ us_status us_gelu_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtyp
   return from_hip(launch_gelu_bwd(z, gh, gz, n, dt, beta_g, as_stream(stream)));
 }
 
+us_status us_gelu_tables(void* workspace, size_t workspace_bytes, float alpha_g, float beta_g, void* stream) {
+  if (!workspace) return US_ERR_NULL;
+  if (!aligned16(workspace)) return US_ERR_ALIGN;
+  if (workspace_bytes < (size_t)kTableAreaBytes) return US_ERR_WORKSPACE;
+  if (!(alpha_g > 0.0f)) alpha_g = kGeluAlpha;
+  if (!(beta_g > 0.0f)) beta_g = kGeluBeta;
+  char* const base = (char*)workspace;
+  hipStream_t st = as_stream(stream);
+  if (launch_gelu_table(base + kGeluTableOffset, alpha_g, st) != hipSuccess) return US_ERR_LAUNCH;
+  if (launch_gelu_slope_table(base + kGeluSlopeTableOffset, beta_g, st) != hipSuccess) return US_ERR_LAUNCH;
+  if (launch_gelu_half_table(base + kGeluHalfTableOffset, alpha_g, st) != hipSuccess) return US_ERR_LAUNCH;
+  return US_OK;
+}
+
 size_t us_workspace_bytes(long b, long m, long n) {
   if (b < 1 || m < 1 || n < 1) return 0;
   return (size_t)kTableAreaBytes + gemm_workspace_bytes(m, n, b);
@@ -94,6 +108,8 @@ size_t us_workspace_bytes(long b, long m, long n) {
 us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, long n, us_dtype x_dt, us_dtype w_dt,
                         us_dtype y_dt, float alpha, us_epilogue epi, float epi_scale, void* aux16, void* aux8,
                         void* workspace, size_t workspace_bytes, void* stream) {
+  const bool tables_ready = ((int)epi & US_EPI_TABLES_READY) != 0;
+  epi = (us_epilogue)((int)epi & ~US_EPI_TABLES_READY);
   const bool f16 = (x_dt == US_F16 && w_dt == US_F16);
   const bool fp8 = (x_dt == US_E4M3 && w_dt == US_E4M3);
   if (!f16 && !fp8) return US_ERR_DTYPE;
@@ -118,6 +134,7 @@ us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, l
   p.aux16 = (epi == US_EPI_GELU) ? aux16 : nullptr;
   p.aux8 = (epi == US_EPI_GELU) ? aux8 : nullptr;
   p.table = (workspace && workspace_bytes >= (size_t)kTableAreaBytes) ? workspace : nullptr;
+  p.tables_ready = tables_ready;
   return from_hip(launch_gemm(p, as_stream(stream)));
 }
 
@@ -125,6 +142,8 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
                         us_dtype x_dt, us_dtype w_dt, us_dtype g_dt, us_dtype out_dt, float beta_x, float beta_w,
                         us_epilogue epi, float epi_scale, const void* Zpre, void* aux8, void* workspace,
                         size_t workspace_bytes, void* stream) {
+  const bool tables_ready = ((int)epi & US_EPI_TABLES_READY) != 0;
+  epi = (us_epilogue)((int)epi & ~US_EPI_TABLES_READY);
   const bool f16 = (x_dt == US_F16 && w_dt == US_F16 && g_dt == US_F16);
   const bool fp8 = (x_dt == US_E4M3 && w_dt == US_E4M3 && g_dt == US_E5M2);
   if (!f16 && !fp8) return US_ERR_DTYPE;
@@ -142,7 +161,7 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
   if (!aligned16(X) || !aligned16(W) || !aligned16(G) || !aligned16(dX) || !aligned16(dW) || !aligned16(Zpre) ||
       !aligned16(aux8) || !aligned16(workspace))
     return US_ERR_ALIGN;
-  // workspace layout: [0, 128 KB) tables of the table-driven epilogues, then the dW slices
+  // workspace layout: table area of the table-driven epilogues, then the dW slices
   const size_t slices = do_dw ? gemm_workspace_bytes(m, n, b) : 0;
   if (slices > 0 && (!workspace || workspace_bytes < (size_t)kTableAreaBytes + slices)) return US_ERR_WORKSPACE;
   void* const table = (workspace && workspace_bytes >= (size_t)kTableAreaBytes) ? workspace : nullptr;
@@ -161,6 +180,7 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
     p.Zpre = (epi == US_EPI_GELU_GRAD) ? Zpre : nullptr;
     p.aux8 = (epi == US_EPI_GELU_GRAD) ? aux8 : nullptr;
     p.table = table;
+    p.tables_ready = tables_ready;
   }
   if (do_dw) {
     GemmProblem& p = pdw;
@@ -187,10 +207,12 @@ size_t us_ffn_workspace_bytes(long T, long d, long f) {
 }
 
 us_status us_ffn_fwd(const void* X, const void* W1, const void* W2, void* Z, void* H, void* Y, long T, long d, long f,
-                     int fp8, void* workspace, size_t workspace_bytes, void* stream) {
+                     int mode, void* workspace, size_t workspace_bytes, void* stream) {
+  const bool fp8 = (mode & US_FFN_FP8) != 0;
+  const int ready = (mode & US_FFN_TABLES_READY) ? US_EPI_TABLES_READY : 0;
   const us_dtype op = fp8 ? US_E4M3 : US_F16;
   // layer 1 with the GELU fused: Z = d^-1/2 X W1 (FP16), H = 1.7009 gelu(Z) as FP16 or as E4M3 codes
-  us_status s = us_linear_fwd(X, W1, Z, T, d, f, op, op, US_F16, 0.0f, US_EPI_GELU, 0.0f, fp8 ? nullptr : H,
+  us_status s = us_linear_fwd(X, W1, Z, T, d, f, op, op, US_F16, 0.0f, (us_epilogue)(US_EPI_GELU | ready), 0.0f, fp8 ? nullptr : H,
                               fp8 ? H : nullptr, workspace, workspace_bytes, stream);
   if (s != US_OK) return s;
   // layer 2: Y = f^-1/2 H W2
@@ -198,13 +220,16 @@ us_status us_ffn_fwd(const void* X, const void* W1, const void* W2, void* Z, voi
 }
 
 us_status us_ffn_bwd(const void* X, const void* W1, const void* W2, const void* Z, const void* H, const void* G,
-                     void* dZ16, void* dZ8, void* dX, void* dW1, void* dW2, long T, long d, long f, int fp8,
+                     void* dZ16, void* dZ8, void* dX, void* dW1, void* dW2, long T, long d, long f, int mode,
                      void* workspace, size_t workspace_bytes, void* stream) {
+  const bool fp8 = (mode & US_FFN_FP8) != 0;
+  const int ready = (mode & US_FFN_TABLES_READY) ? US_EPI_TABLES_READY : 0;
   const us_dtype op = fp8 ? US_E4M3 : US_F16;
   const us_dtype gr = fp8 ? US_E5M2 : US_F16;
   if (fp8 ? !dZ8 : !dZ16) return US_ERR_NULL;
   // layer 2 backward: dH = d^-1/2 G W2^T, fused with GELU' -> dZ (FP16 + E5M2 copy); dW2 = T^-1/2 H^T G
-  us_status s = us_linear_bwd(H, W2, G, dZ16, dW2, T, f, d, op, op, gr, US_F16, 0.0f, 0.0f, US_EPI_GELU_GRAD, 0.0f, Z,
+  us_status s = us_linear_bwd(H, W2, G, dZ16, dW2, T, f, d, op, op, gr, US_F16, 0.0f, 0.0f,
+                              (us_epilogue)(US_EPI_GELU_GRAD | ready), 0.0f, Z,
                               fp8 ? dZ8 : nullptr, workspace, workspace_bytes, stream);
   if (s != US_OK) return s;
   // layer 1 backward: dX = f^-1/2 dZ W1^T; dW1 = T^-1/2 X^T dZ

@@ -128,12 +128,17 @@ __device__ __forceinline__ float gelu_grad_scaled(float z, float gh, float beta_
 constexpr int kGeluTableBytes = 65536;
 constexpr int kGeluSlopeLast = 0x4800;                                   // FP16 bits of 8.0
 constexpr int kGeluSlopeTableBytes = 73 * 1024;                          // (0x4801 entries * 4 B) rounded up to whole KB
-constexpr int kTableAreaBytes = 128 * 1024;                              // head of a workspace reserved for tables
+constexpr int kTableAreaBytes = US_TABLE_AREA_BYTES;                     // head of a workspace reserved for tables
 // Forward with FP16 activation output: fp16(alpha_g * gelu(z)) for |z| <= 6 (bit patterns 0 .. 0x4600), the
 // non-negative inputs first, then the negative ones.  Beyond 6 the FP32 Phi is exactly 1 (result
 // alpha_g * z) resp. small enough that the product rounds to -0.
 constexpr int kGeluHalfLast = 0x4600;                                    // FP16 bits of 6.0
 constexpr int kGeluHalfTableBytes = 72 * 1024;                           // (2 * 0x4601 entries * 2 B) rounded up to whole KB
+// places of the three tables in the table area
+constexpr int kGeluTableOffset = 0;
+constexpr int kGeluSlopeTableOffset = kGeluTableOffset + kGeluTableBytes;
+constexpr int kGeluHalfTableOffset = kGeluSlopeTableOffset + kGeluSlopeTableBytes;
+static_assert(kGeluHalfTableOffset + kGeluHalfTableBytes <= kTableAreaBytes, "the tables fit their area");
 
 __device__ __forceinline__ _Float16 half_from_bits(uint32_t b) {
   const unsigned short u = (unsigned short)b;

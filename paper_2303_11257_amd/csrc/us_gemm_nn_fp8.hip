@@ -5,9 +5,13 @@ namespace us {
 
 hipError_t gemm_nn_fp8(const GemmProblem& p, hipStream_t st) {
   if (p.epi == US_EPI_GELU && !p.aux16 && p.aux8 && table_path_ok<true>(p)) {
-    hipError_t e = launch_gelu_table(p.table, p.epi_scale, st);
-    if (e != hipSuccess) return e;
-    return launch_one<true, CfgD256, true, 0, 0, true, false, EPI_GELU_TAB, false>(p, 1, p.K, st);
+    GemmProblem q = p;
+    q.table = (char*)p.table + kGeluTableOffset;
+    if (!p.tables_ready) {
+      hipError_t e = launch_gelu_table(q.table, p.epi_scale, st);
+      if (e != hipSuccess) return e;
+    }
+    return launch_one<true, CfgD256, true, 0, 0, true, false, EPI_GELU_TAB, false>(q, 1, p.K, st);
   }
   if (p.epi == US_EPI_GELU) return launch_sized<true, 0, 0, true, false, EPI_GELU, false>(p, 1, p.K, st);
   return launch_store<true, 0, 0, true, false>(p, st);

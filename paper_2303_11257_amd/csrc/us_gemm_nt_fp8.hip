@@ -5,9 +5,13 @@ namespace us {
 
 hipError_t gemm_nt_fp8(const GemmProblem& p, hipStream_t st) {
   if (p.epi == US_EPI_GELU_GRAD && table_path_ok<true>(p)) {
-    hipError_t e = launch_gelu_slope_table(p.table, p.epi_scale, st);
-    if (e != hipSuccess) return e;
-    return launch_one<true, CfgD256, true, 1, 0, true, true, EPI_GELU_GRAD_TAB, false>(p, 1, p.K, st);
+    GemmProblem q = p;
+    q.table = (char*)p.table + kGeluSlopeTableOffset;
+    if (!p.tables_ready) {
+      hipError_t e = launch_gelu_slope_table(q.table, p.epi_scale, st);
+      if (e != hipSuccess) return e;
+    }
+    return launch_one<true, CfgD256, true, 1, 0, true, true, EPI_GELU_GRAD_TAB, false>(q, 1, p.K, st);
   }
   if (p.epi == US_EPI_GELU_GRAD) return launch_sized<true, 1, 0, true, true, EPI_GELU_GRAD, false>(p, 1, p.K, st);
   return launch_store<true, 1, 0, true, true>(p, st);

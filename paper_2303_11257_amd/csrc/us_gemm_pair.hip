@@ -27,9 +27,13 @@ hipError_t launch_pair_typed(const GemmProblem& dx, const GemmProblem& dw, hipSt
   constexpr int FG = FP8 ? 1 : 0;                     // gradient operand format (E5M2) where it applies
   using KW = GemmKind<CfgK128, FP8, 0, FG, false, false, EPI_STORE, false>;
   if (dx.epi == US_EPI_GELU_GRAD) {
-    hipError_t e = launch_gelu_slope_table(dx.table, dx.epi_scale, st);
-    if (e != hipSuccess) return e;
-    return launch_pair<GemmKind<CfgD256, FP8, FG, 0, true, true, EPI_GELU_GRAD_TAB, false>, KW>(dx, dw, st);
+    GemmProblem q = dx;
+    q.table = (char*)dx.table + kGeluSlopeTableOffset;
+    if (!dx.tables_ready) {
+      hipError_t e = launch_gelu_slope_table(q.table, dx.epi_scale, st);
+      if (e != hipSuccess) return e;
+    }
+    return launch_pair<GemmKind<CfgD256, FP8, FG, 0, true, true, EPI_GELU_GRAD_TAB, false>, KW>(q, dw, st);
   }
   if (use_big_tile(dx.M, dx.N, 1)) return launch_pair<GemmKind<CfgD256, FP8, FG, 0, true, true, EPI_STORE, false>, KW>(dx, dw, st);
   return launch_pair<GemmKind<CfgM256, FP8, FG, 0, true, true, EPI_STORE, false>, KW>(dx, dw, st);

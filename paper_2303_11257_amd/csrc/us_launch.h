@@ -39,7 +39,8 @@ struct GemmProblem {
   void* aux16;             // GELU: FP16 [M,N] or NULL
   void* aux8;              // GELU: E4M3 [M,N]; GELU_GRAD: E5M2 [M,N]; or NULL
   void* workspace;         // split-K partial sums (FP32), or NULL
-  void* table;             // scratch for the GELU table (>= 73 KB), or NULL: arithmetic epilogue
+  void* table;             // table area of the workspace (us_device.h), or NULL: arithmetic epilogue
+  bool tables_ready;       // the table area is already filled for this epi_scale
   size_t workspace_bytes;
 };
 

@@ -20,7 +20,7 @@ def _declared():
 def test_every_declared_symbol_is_exported():
     names = _declared()
     assert {"us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd", "us_linear_scales",
-            "us_workspace_bytes", "us_status_string", "us_ffn_fwd", "us_ffn_bwd"} <= set(names)
+            "us_workspace_bytes", "us_status_string", "us_ffn_fwd", "us_ffn_bwd", "us_gelu_tables"} <= set(names)
     L = ctypes.CDLL(us.library_path())
     for n in names:
         assert hasattr(L, n), n
@@ -38,7 +38,8 @@ def test_scales_and_status_strings():
 
 
 def test_workspace_rule():
-    table_area = 128 * 1024
+    table_area = us.TABLE_AREA_BYTES
+    assert table_area == 256 * 1024
     assert us.workspace_bytes(32768, 4096, 16384) == table_area     # the output alone fills the chip: no dW slices
     # 256 tiles of 128 x 128 cover the CUs once: the token reduction is shared by wave groups, no slices
     assert us.workspace_bytes(8192, 1024, 4096) == table_area
@@ -66,6 +67,10 @@ def test_argument_errors_are_detected_on_the_host():
         (lambda: us.linear_bwd(16, 16, 16, 16, 16, 4096, 768, 3072, F16, F16, F16), 5),   # workspace missing
         (lambda: us.linear_bwd(16, 16, 16, 16, None, 16, 16, 16, F16, F16, F16, F16, 0, 0, us.EPI_GELU_GRAD), 1),
         (lambda: us.linear_bwd(16, 16, 8, 16, 16, 16, 16, 16, F16, F16, F16), 3),
+        (lambda: us.gelu_tables(None, 1 << 20), 1),
+        (lambda: us.gelu_tables(16, 1000), 5),                       # smaller than the table area
+        (lambda: us.gelu_tables(24, 1 << 20), 3),
+        (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, F16, F16, F16, 0.0, us.EPI_GELU | us.EPI_TABLES_READY), 1),   # flag is masked off
     ]
     for fn, status in cases:
         with pytest.raises(us.UsError) as e:

@@ -104,7 +104,7 @@ def test_grad_w_wave_split_reduction(fp8):
     """An output of 192-256 tiles of 128 x 128 with a long token dimension: two wave groups of one
     workgroup share the reduction and add up in LDS (no workspace).  Ragged in both output dimensions."""
     b, m, n = 1024, 2000, 1936                                   # 16 x 16 tiles, the last ones partial
-    assert us.workspace_bytes(b, m, n) == 128 * 1024                 # the table area only: no K slices
+    assert us.workspace_bytes(b, m, n) == us.TABLE_AREA_BYTES        # the table area only: no K slices
     (X, W, G), gdt, odt = _operands(b, m, n, 109, fp8)
     _, dW, _ = linear_bwd(X, None, G, *gdt, do_dx=False)
     assert_close(dW, O.linear_bwd_dw(X, G, b ** -0.5, odt[0], odt[2]), "dW wave split")
