@@ -96,13 +96,18 @@ inline void choose_xcd_grid(long tiles_m, long tiles_n, int& gm, int& gn) {
   }
 }
 
+// Store of a result that no kernel reads soon (FP16 / FP32 outputs: tens of MB per call): marked
+// non-temporal so that it does not displace the operand panels and FP8 activations in L2.
+template <class V>
+__device__ __forceinline__ void stream_store(V* p, V v) { __builtin_nontemporal_store(v, p); }
+
 // ---- epilogue on eight consecutive columns of one row (FP16 strip) ---------------------------------
 // z: the saved pre-activation at the same eight positions (GELU' epilogues only; fetched by the caller
 // well ahead of its use).
 template <int EPI, int AUX_FMT>
 __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y, v8h z, const uint8_t* lut) {
   if (EPI == EPI_GELU_TAB) {
-    *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = y;   // the FP16 matmul result, kept for backward
+    stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), y);   // the FP16 matmul result, kept for backward
     uint32_t c[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) c[k] = *US_LDS_PTR(const uint8_t, lut + half_bits(y[k]));
@@ -113,7 +118,7 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
     return;
   }
   if (EPI == EPI_GELU_TAB16) {
-    *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = y;   // the FP16 matmul result, kept for backward
+    stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), y);   // the FP16 matmul result, kept for backward
     v8h r;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
@@ -126,7 +131,7 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
       const _Float16 far = neg ? half_from_bits(a >= 0x7c00u ? 0x7e00u : 0x8000u) : to_half(g.epi_scale * (float)y[k]);
       r[k] = (a > (uint32_t)kGeluHalfLast) ? far : t;
     }
-    if (g.aux16) *reinterpret_cast<v8h*>(g.aux16 + idx) = r;
+    if (g.aux16) stream_store(reinterpret_cast<v8h*>(g.aux16 + idx), r);
     if (g.aux8) {
       const v2h p0 = {r[0], r[1]}, p1 = {r[2], r[3]}, p2 = {r[4], r[5]}, p3 = {r[6], r[7]};
       v2i w;
@@ -148,7 +153,7 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
       t = (a >= 0x7c00u) ? __builtin_nanf("") : t;       // +-inf and NaN, as the arithmetic form gives
       r[k] = to_half(t * (float)y[k]);
     }
-    if (g.C) *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = r;
+    if (g.C) stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), r);
     if (g.aux8) {
       const v2h p0 = {r[0], r[1]}, p1 = {r[2], r[3]}, p2 = {r[4], r[5]}, p3 = {r[6], r[7]};
       v2i w;
@@ -159,19 +164,19 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
     return;
   }
   if (EPI == EPI_STORE) {
-    *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = y;
+    stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), y);
     return;
   }
   v8h r;
   if (EPI == EPI_GELU) {
-    *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = y;   // the FP16 matmul result, kept for backward
+    stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), y);   // the FP16 matmul result, kept for backward
 #pragma unroll
     for (int k = 0; k < 8; ++k) r[k] = to_half(gelu_scaled((float)y[k], g.epi_scale));
-    if (g.aux16) *reinterpret_cast<v8h*>(g.aux16 + idx) = r;
+    if (g.aux16) stream_store(reinterpret_cast<v8h*>(g.aux16 + idx), r);
   } else {  // EPI_GELU_GRAD: y is the FP16-rounded matmul gradient
 #pragma unroll
     for (int k = 0; k < 8; ++k) r[k] = to_half(gelu_grad_scaled((float)z[k], (float)y[k], g.epi_scale));
-    if (g.C) *reinterpret_cast<v8h*>((_Float16*)g.C + idx) = r;      // optional: the FP8 copy may be all that is wanted
+    if (g.C) stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), r);      // optional: the FP8 copy may be all that is wanted
   }
   if (g.aux8) {
     // FP8 copy of the FP16 value just stored: identical to casting the stored tensor afterwards
@@ -281,7 +286,7 @@ __device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&a
           if (EPI == EPI_PARTIAL)
             *reinterpret_cast<v4f*>(g.partial + (size_t)split * g.M * g.N + m * g.N + n) = v;
           else
-            *reinterpret_cast<v4f*>((float*)g.C + m * g.ldc + n) = v;
+            stream_store(reinterpret_cast<v4f*>((float*)g.C + m * g.ldc + n), v);
         } else {
           v8h y = *US_LDS_PTR(const v8h, p);
           epilogue_row8<EPI, AUX_FMT>(g, m * g.ldc + n, y, zpre[NEEDS_Z ? i : 0][NEEDS_Z ? u : 0], lut);
