@@ -155,18 +155,23 @@ def time_graph(torch, fn, steps, warmup):
 
 
 def time_calls(torch, calls, steps):
-    """Average duration of each call of the step, from HIP events on the launch stream, over `steps` passes."""
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in calls] for _ in range(steps)]
-    torch.cuda.synchronize()
-    for s in range(steps):
-        for (name, kind, flop, nbytes, thunk), (e0, e1) in zip(calls, ev[s]):
-            e0.record()
-            thunk()
-            e1.record()
-    torch.cuda.synchronize()
+    """Average duration of each launch of the step, from HIP events on the launch stream.  One call is bracketed
+    at a time (the whole step still runs in order, so caches are in the state of a real step): an event pair
+    around every launch would put a small bubble between all of them."""
+    steps = min(steps, 200)
     res = []
     for i, (name, kind, flop, nbytes, _) in enumerate(calls):
-        ms = sum(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(steps)) / steps
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        torch.cuda.synchronize()
+        for s in range(steps):
+            for k, c in enumerate(calls):
+                if k == i:
+                    ev[s][0].record()
+                c[4]()
+                if k == i:
+                    ev[s][1].record()
+        torch.cuda.synchronize()
+        ms = sum(e0.elapsed_time(e1) for e0, e1 in ev) / steps
         res.append(dict(name=name, kind=kind, ms=ms, flop=flop, bytes=nbytes))
     return res
 
