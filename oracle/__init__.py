@@ -61,6 +61,8 @@ def _load():
     lib.uso_gelu_bwd.restype = None
     lib.uso_linear_scales.argtypes = [l, l, l, i, vp, vp, vp]
     lib.uso_linear_scales.restype = None
+    lib.uso_weighted_add2.argtypes = [vp, vp, vp, sz, i, f, f]
+    lib.uso_weighted_add2.restype = None
     _lib = lib
     return lib
 
@@ -274,4 +276,48 @@ def ffn_bwd(X16, W1_16, W2_16, G16, fwd: dict, fp8: bool, beta_g=None):
         r["dZ"] = gelu_bwd(fwd["Z"], r["dH"], beta_g)
         r["dX"] = linear_bwd_dx(r["dZ"], W1_16, bx1)
         r["dW1"] = linear_bwd_dw(X16, r["dZ"], bw1)
+    return r
+
+
+# ---- weighted addition and the residual FFN layer (Sec. 5.3) --------------------------------------
+def weighted_add_scales(gammas):
+    """Table A.2 "weighted_add": sum_i gamma_i x_i has alpha = (sum gamma_i^2)^-1/2, beta_i = 1/gamma_i."""
+    g = [float(x) for x in gammas]
+    return 1.0 / math.sqrt(sum(x * x for x in g)), [1.0 / x for x in g]
+
+
+def residual_weights(tau: float):
+    """fixed(tau) interpolation of Sec. 5.3: (skip, branch) = (sqrt(1-tau), sqrt(tau)), as the floats the library uses.
+    The branch weight is rounded to float first and the skip weight derived from it, sqrt(1 - branch^2), the way the
+    library derives it from the one scale it is given."""
+    branch = np.float32(math.sqrt(tau))
+    skip = np.float32(math.sqrt(1.0 - float(branch) * float(branch)))
+    return skip, branch
+
+
+def weighted_add2(a, b, ca, cb):
+    """round(ca*a + cb*b) in the storage type of a and b."""
+    a, b = _c(a), _c(b)
+    dt = _dt_of(a, None)
+    assert a.dtype == b.dtype and a.shape == b.shape
+    out = np.empty_like(a)
+    _load().uso_weighted_add2(_p(a), _p(b), _p(out), a.size, dt, float(np.float32(ca)), float(np.float32(cb)))
+    return out
+
+
+def ffn_res_fwd(X16, W1_16, W2_16, tau: float, fp8: bool):
+    """Residual FFN layer (Fig. 3, right): out = sqrt(1-tau) x + sqrt(tau) FFN(x).  r["Y"] is the branch output
+    FFN(x) as stored FP16, r["Out"] the layer output."""
+    r = ffn_fwd(X16, W1_16, W2_16, fp8)
+    skip, branch = residual_weights(tau)
+    r["Out"] = weighted_add2(X16, r["Y"], skip, branch)
+    return r
+
+
+def ffn_res_bwd(X16, W1_16, W2_16, G16, fwd: dict, tau: float, fp8: bool):
+    """Backward of the residual layer: the branch receives the incoming gradient unscaled (so dW1, dW2 and dZ are
+    those of the plain FFN), and grad_x = sqrt(1-tau) g + sqrt(tau) grad_x_branch."""
+    r = ffn_bwd(X16, W1_16, W2_16, G16, fwd, fp8)
+    skip, branch = residual_weights(tau)
+    r["dXin"] = weighted_add2(G16, r["dX"], skip, branch)
     return r

@@ -15,6 +15,10 @@
  *   gelu      Table A.2 "Activations": gelu(x) = x*Phi(x); backward by the f_grad definition of
  *             Sec. 5.1 (incoming gradient times the derivative), each with its own fixed scale.
  *
+ *   residual  Sec. 5.3 "Weighted addition": the fixed(tau) interpolation sqrt(1-tau)*x + sqrt(tau)*f(x),
+ *             with the residual branch's weight moved out of its backward pass (the id* rewrite of
+ *             that section); Table A.2 "weighted_add" for the general scale rule.
+ *
  * Readings of points the paper leaves open are listed next to each function.
  */
 #include <math.h>
@@ -291,6 +295,24 @@ void uso_gelu_bwd(const void* z, const void* gh, void* gz, size_t n, int dt, flo
     double zi = uso_decode_bits(load_bits(z, dt, i), dt);
     double gi = uso_decode_bits(load_bits(gh, dt, i), dt);
     store_bits(gz, dt, i, round_out((double)beta_g * (Phi(zi) + zi * phi(zi)) * gi, dt));
+  }
+}
+
+/*
+ * ---- weighted addition of two tensors (Sec. 5.3; Table A.2 "weighted_add") --------------------
+ *   out = round( ca * a + cb * b ),  a and b of storage type dt, arithmetic in double, one rounding.
+ * Used for the residual layer: forward (a, b) = (skip input x, branch output f(x)) with
+ * (ca, cb) = (sqrt(1-tau), sqrt(tau)); backward (a, b) = (incoming gradient g, branch input gradient)
+ * with the same weights, because the rewrite gamma*f(x) -> id*(f(id*(x, 1, gamma)), gamma, 1) applies
+ * gamma = sqrt(tau) to the branch's OUTPUT in the forward pass and to the gradient leaving the branch's
+ * INPUT in the backward pass, so that the gradient entering the branch is the unscaled g.
+ * Reading: the weights arrive as floats (what the library gets) and are widened to double.
+ */
+void uso_weighted_add2(const void* a, const void* b, void* out, size_t n, int dt, float ca, float cb) {
+  for (size_t i = 0; i < n; ++i) {
+    double ai = uso_decode_bits(load_bits(a, dt, i), dt);
+    double bi = uso_decode_bits(load_bits(b, dt, i), dt);
+    store_bits(out, dt, i, round_out((double)ca * ai + (double)cb * bi, dt));
   }
 }
 
