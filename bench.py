@@ -109,6 +109,22 @@ class Ffn:
         us.ffn_bwd(p(X), p(W1), p(W2), p(self.Z), p(self.H), p(G), p(self.dZ16), p(self.dZ8), p(self.dX), p(self.dW1),
                    p(self.dW2), T, d, f, self.mode, p(self.ws), self.wsb, st)
 
+    def step_residual(self, tau=0.5):
+        """The same step for the residual layer out = sqrt(1-tau) x + sqrt(tau) FFN(x) (interpolation fused into the
+        second projection and into grad_X of the first): a side measurement, not `value`."""
+        us, p, st = self.us, self.p, self.torch.cuda.current_stream().cuda_stream
+        T, d, f = self.T, self.d, self.f
+        if self.fp8:
+            us.cast_fp8_batch([p(self.X), p(self.W1), p(self.W2), p(self.G)], [p(self.X8), p(self.W1_8), p(self.W2_8), p(self.G8)],
+                              [self.X.numel(), self.W1.numel(), self.W2.numel(), self.G.numel()],
+                              [us.E4M3, us.E4M3, us.E4M3, us.E5M2], st)
+            X, W1, W2, G = self.X8, self.W1_8, self.W2_8, self.G8
+        else:
+            X, W1, W2, G = self.X, self.W1, self.W2, self.G
+        us.ffn_res_fwd(p(self.X), p(X), p(W1), p(W2), p(self.Z), p(self.H), p(self.Y), T, d, f, tau, self.mode, p(self.ws), self.wsb, st)
+        us.ffn_res_bwd(p(X), p(W1), p(W2), p(self.Z), p(self.H), p(self.G), p(G), p(self.dZ16), p(self.dZ8), p(self.dX), p(self.dW1),
+                       p(self.dW2), T, d, f, tau, self.mode, p(self.ws), self.wsb, st)
+
 
 def ramp_up(torch, fn, seconds=0.15):
     """Untimed: keeps the GPU busy with the step until its clocks have settled.  The first ~30 ms of work
@@ -279,6 +295,11 @@ def main():
         cb, cm = sum(c["bytes"] for c in casts), sum(c["ms"] for c in casts)
         out["cast"] = {"GBps": cb / (cm * 1e-3) * 1e-9, "frac_of_hbm_peak": cb / (cm * 1e-3) * 1e-9 / PEAK_HBM_GBS,
                        "bytes_per_elem": 3}
+    if not args.no_secondary:
+        ms_res = time_steps(torch, ffn.step_residual, args.steps, args.warmup)
+        out["residual_layer"] = {"what": "same workload with the fixed(tau=0.5) residual interpolation fused into the step "
+                                         "(forward output and grad_X read one more FP16 [tokens, d_model] tensor each)",
+                                 "ms_per_step": ms_res, "TFLOPs": ffn.flop / (ms_res * 1e-3) * 1e-12}
     if not args.no_secondary and args.workload != "C2":
         w2 = WORKLOADS["C2"]
         f2 = Ffn(torch, us, synth, w2["T"], w2["d"], w2["f"], False, synth.BASE_SEED + 1)

@@ -39,7 +39,8 @@ typedef enum {
   US_ERR_ALIGN = 3,      /* a pointer is not 16-byte aligned                              */
   US_ERR_DTYPE = 4,      /* unsupported storage-type combination                          */
   US_ERR_WORKSPACE = 5,  /* workspace missing or smaller than us_workspace_bytes()        */
-  US_ERR_LAUNCH = 6      /* the HIP runtime refused a launch                              */
+  US_ERR_LAUNCH = 6,     /* the HIP runtime refused a launch                              */
+  US_ERR_VALUE = 7       /* a scalar argument outside its domain (e.g. a residual weight)   */
 } us_status;
 
 typedef enum { US_F32 = 0, US_F16 = 1, US_E4M3 = 2, US_E5M2 = 3 } us_dtype;
@@ -48,6 +49,7 @@ typedef enum {
   US_EPI_NONE = 0,
   US_EPI_GELU = 1,       /* forward: also emit the unit-scaled GELU of the output            */
   US_EPI_GELU_GRAD = 2,  /* grad_X: multiply by the unit-scaled GELU derivative of Zpre     */
+  US_EPI_RESIDUAL = 3,   /* forward / grad_X: interpolate with a skip input (Sec. 5.3)      */
   /* flag, OR-ed onto one of the two above: the table area of the workspace already holds the GELU
    * tables for this epi_scale (us_gelu_tables) and must not be rebuilt by the call                */
   US_EPI_TABLES_READY = 0x100
@@ -110,6 +112,10 @@ us_status us_cast_fp8_batch(int count, const void* const* src, void* const* dst,
  * stores H to aux16 (FP16 [b,n]) if aux16 != NULL and the E4M3 cast of that FP16 H (scale 1) to aux8
  * ([b,n] bytes) if aux8 != NULL; at least one of them must be given.  epi_scale <= 0 selects the
  * unit-scaling factor 1.7009.  Y itself is always written (the backward pass needs it).
+ * epi = US_EPI_RESIDUAL (y_dt must be F16) is the residual layer's weighted addition (Sec. 5.3
+ * "Weighted addition", fixed(tau) with epi_scale = sqrt(tau) in (0, 1]):
+ *   Y = fp16( sqrt(1 - epi_scale^2) * R + epi_scale * fp16(alpha * X W) ),
+ * R = aux16, here an INPUT: the FP16 [b,n] skip tensor (Y itself is the only output; aux8 is ignored).
  * workspace may be NULL.  With epi = US_EPI_GELU, exactly one of aux16 / aux8 and a workspace of at
  * least US_TABLE_AREA_BYTES (16-byte aligned) large problems take the activation from a table over
  * the FP16 values of Y; the result is the same as without a workspace.  By default the call first
@@ -135,6 +141,11 @@ us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, l
  * i.e. the scaled-GELU backward of Sec. 5.1 applied to the FP16-rounded matmul gradient; if aux8 !=
  * NULL the E5M2 cast of that FP16 dX is written there, and dX itself may then be NULL (only the
  * codes are stored: the values are the same).  epi_scale <= 0 selects 1.4811.
+ * epi = US_EPI_RESIDUAL applies to dX only (out_dt must be F16): the backward pass of a residual layer
+ * whose branch starts with this projection.  The branch weight sqrt(tau) = epi_scale in (0, 1] acts on
+ * the gradient LEAVING the branch's input, not on the one entering the branch (the id* rewrite of
+ * Sec. 5.3), and the skip path carries the incoming layer gradient R = Zpre (FP16 [b,m]):
+ *   dX = fp16( sqrt(1 - epi_scale^2) * R + epi_scale * fp16(beta_x * G W^T) ).
  * Workspace (16-byte aligned): us_workspace_bytes(b, m, n) is the size that serves every use.  Its
  * first US_TABLE_AREA_BYTES are the table area (the table-driven GELU' epilogue gives the same results
  * as the arithmetic one and is used for large problems when the area is there; it is rebuilt by the
@@ -169,6 +180,7 @@ us_status us_gelu_tables(void* workspace, size_t workspace_bytes, float alpha_g,
  * In-place use (h == z, gz == gh) is allowed.
  */
 us_status us_gelu_fwd(const void* z, void* h, size_t n, us_dtype dt, float alpha_g, void* stream);
+
 us_status us_gelu_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtype dt, float beta_g,
                       void* stream);
 
@@ -199,6 +211,32 @@ us_status us_ffn_bwd(const void* X, const void* W1, const void* W2, const void* 
                      long T, long d, long f, int mode, void* workspace, size_t workspace_bytes,
                      void* stream);
 size_t us_ffn_workspace_bytes(long T, long d, long f);
+
+/*
+ * Stand-alone weighted addition of two tensors (Table A.2 "weighted_add" with two inputs; Sec. 5.3):
+ *   out[i] = round( ca * a[i] + cb * b[i] ),  dt = US_F16 or US_F32 for all three arrays; out may alias a or b.
+ * The unit-scaling factor alpha = (ca^2 + cb^2)^-1/2 is the caller's to fold into ca, cb (it is 1 for the
+ * interpolation weights sqrt(1-tau), sqrt(tau)).
+ */
+us_status us_weighted_add(const void* a, const void* b, void* out, size_t n, us_dtype dt, float ca, float cb,
+                          void* stream);
+
+/*
+ * The residual FFN layer of Fig. 3 (right):  Out = sqrt(1-tau) * x + sqrt(tau) * FFN(x), 0 < tau <= 1, as
+ * us_ffn_fwd / us_ffn_bwd with the interpolation fused into the second projection (forward) and into
+ * grad_X of the first projection (backward).  Xskip / Gskip are the FP16 layer input / incoming
+ * gradient [T,d]; X / G are the matmul operands (the same tensors when mode has no US_FFN_FP8, their
+ * FP8 casts otherwise).  The branch output FFN(x) is not stored.  In the backward pass the branch
+ * receives G unscaled (dZ, dW1, dW2 are those of us_ffn_bwd) and
+ *   dXin = fp16( sqrt(1-tau) * Gskip + sqrt(tau) * fp16(f^-1/2 dZ W1^T) ).
+ */
+us_status us_ffn_res_fwd(const void* Xskip, const void* X, const void* W1, const void* W2, void* Z, void* H,
+                         void* Out, long T, long d, long f, float tau, int mode, void* workspace,
+                         size_t workspace_bytes, void* stream);
+us_status us_ffn_res_bwd(const void* X, const void* W1, const void* W2, const void* Z, const void* H,
+                         const void* Gskip, const void* G, void* dZ16, void* dZ8, void* dXin, void* dW1,
+                         void* dW2, long T, long d, long f, float tau, int mode, void* workspace,
+                         size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

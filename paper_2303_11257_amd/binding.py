@@ -10,12 +10,12 @@ import ctypes
 import os
 
 F32, F16, E4M3, E5M2 = 0, 1, 2, 3
-EPI_NONE, EPI_GELU, EPI_GELU_GRAD = 0, 1, 2
+EPI_NONE, EPI_GELU, EPI_GELU_GRAD, EPI_RESIDUAL = 0, 1, 2, 3
 EPI_TABLES_READY = 0x100            # flag for EPI_GELU / EPI_GELU_GRAD: tables prebuilt by gelu_tables()
 FFN_FP8, FFN_TABLES_READY = 1, 2    # mode bits of ffn_fwd / ffn_bwd
 TABLE_AREA_BYTES = 256 * 1024
 STATUS = {0: "US_OK", 1: "US_ERR_NULL", 2: "US_ERR_SHAPE", 3: "US_ERR_ALIGN", 4: "US_ERR_DTYPE",
-          5: "US_ERR_WORKSPACE", 6: "US_ERR_LAUNCH"}
+          5: "US_ERR_WORKSPACE", 6: "US_ERR_LAUNCH", 7: "US_ERR_VALUE"}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libus_mi355x.so")
@@ -51,6 +51,9 @@ def lib() -> ctypes.CDLL:
     L.us_linear_bwd.argtypes = [vp, vp, vp, vp, vp, l, l, l, i, i, i, i, f, f, i, f, vp, vp, vp, sz, vp]
     L.us_workspace_bytes.argtypes = [l, l, l]
     L.us_gelu_tables.argtypes = [vp, sz, f, f, vp]
+    L.us_weighted_add.argtypes = [vp, vp, vp, sz, i, f, f, vp]
+    L.us_ffn_res_fwd.argtypes = [vp] * 7 + [l, l, l, f, i, vp, sz, vp]
+    L.us_ffn_res_bwd.argtypes = [vp] * 12 + [l, l, l, f, i, vp, sz, vp]
     L.us_workspace_bytes.restype = sz
     L.us_gelu_fwd.argtypes = [vp, vp, sz, i, f, vp]
     L.us_gelu_bwd.argtypes = [vp, vp, vp, sz, i, f, vp]
@@ -59,7 +62,7 @@ def lib() -> ctypes.CDLL:
     L.us_ffn_workspace_bytes.argtypes = [l, l, l]
     L.us_ffn_workspace_bytes.restype = sz
     for name in ("us_linear_scales", "us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd",
-                 "us_gelu_tables", "us_ffn_fwd", "us_ffn_bwd"):
+                 "us_gelu_tables", "us_ffn_fwd", "us_ffn_bwd", "us_weighted_add", "us_ffn_res_fwd", "us_ffn_res_bwd"):
         getattr(L, name).restype = i
     _lib = L
     return L
@@ -132,3 +135,18 @@ def ffn_bwd(X, W1, W2, Z, H, G, dZ16, dZ8, dX, dW1, dW2, T, d, f, mode, workspac
 
 def ffn_workspace_bytes(T: int, d: int, f: int) -> int:
     return int(lib().us_ffn_workspace_bytes(T, d, f))
+
+
+def weighted_add(a, b, out, n, dt=F16, ca=1.0, cb=1.0, stream=None):
+    _check(lib().us_weighted_add(a, b, out, n, dt, ca, cb, stream), "us_weighted_add")
+
+
+def ffn_res_fwd(Xskip, X, W1, W2, Z, H, Out, T, d, f, tau, mode, workspace=None, workspace_bytes=0, stream=None):
+    _check(lib().us_ffn_res_fwd(Xskip, X, W1, W2, Z, H, Out, T, d, f, tau, int(mode), workspace, workspace_bytes, stream),
+           "us_ffn_res_fwd")
+
+
+def ffn_res_bwd(X, W1, W2, Z, H, Gskip, G, dZ16, dZ8, dXin, dW1, dW2, T, d, f, tau, mode, workspace=None, workspace_bytes=0,
+                stream=None):
+    _check(lib().us_ffn_res_bwd(X, W1, W2, Z, H, Gskip, G, dZ16, dZ8, dXin, dW1, dW2, T, d, f, tau, int(mode), workspace,
+                                workspace_bytes, stream), "us_ffn_res_bwd")

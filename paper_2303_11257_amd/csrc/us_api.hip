@@ -15,6 +15,9 @@ inline bool mult16(long v) { return (v & 15) == 0; }
 inline bool is_fp8(us_dtype d) { return d == US_E4M3 || d == US_E5M2; }
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 inline us_status from_hip(hipError_t e) { return e == hipSuccess ? US_OK : US_ERR_LAUNCH; }
+// weight of the skip input of a residual interpolation whose branch weight is w (0 < w <= 1)
+inline float skip_weight(float w) { return (float)sqrt(1.0 - (double)w * (double)w); }
+inline bool residual_weight_ok(float w) { return w > 0.0f && w <= 1.0f; }
 
 }  // namespace
 
@@ -29,6 +32,7 @@ const char* us_status_string(us_status s) {
     case US_ERR_DTYPE: return "unsupported storage-type combination";
     case US_ERR_WORKSPACE: return "workspace missing or too small";
     case US_ERR_LAUNCH: return "HIP launch failed";
+    case US_ERR_VALUE: return "scalar argument outside its domain";
   }
   return "unknown status";
 }
@@ -114,12 +118,14 @@ us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, l
   const bool fp8 = (x_dt == US_E4M3 && w_dt == US_E4M3);
   if (!f16 && !fp8) return US_ERR_DTYPE;
   if (y_dt != US_F16 && y_dt != US_F32) return US_ERR_DTYPE;
-  if (epi != US_EPI_NONE && epi != US_EPI_GELU) return US_ERR_DTYPE;
-  if (epi == US_EPI_GELU && y_dt != US_F16) return US_ERR_DTYPE;
+  if (epi != US_EPI_NONE && epi != US_EPI_GELU && epi != US_EPI_RESIDUAL) return US_ERR_DTYPE;
+  if (epi != US_EPI_NONE && y_dt != US_F16) return US_ERR_DTYPE;
+  if (epi == US_EPI_RESIDUAL && !residual_weight_ok(epi_scale)) return US_ERR_VALUE;
   if (b < 0 || m < 0 || n < 0 || !mult16(b) || !mult16(m) || !mult16(n)) return US_ERR_SHAPE;
   if (b == 0 || n == 0) return US_OK;
   if (!Y || (m > 0 && (!X || !W))) return US_ERR_NULL;
   if (epi == US_EPI_GELU && !aux16 && !aux8) return US_ERR_NULL;
+  if (epi == US_EPI_RESIDUAL && !aux16) return US_ERR_NULL;
   if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || !aligned16(aux16) || !aligned16(aux8) || !aligned16(workspace))
     return US_ERR_ALIGN;
   GemmProblem p{};
@@ -131,6 +137,10 @@ us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, l
   p.scale = (alpha > 0.0f) ? alpha : (float)(1.0 / sqrt((double)(m > 0 ? m : 1)));
   p.epi = epi;
   p.epi_scale = (epi_scale > 0.0f) ? epi_scale : kGeluAlpha;
+  if (epi == US_EPI_RESIDUAL) {
+    p.skip_scale = skip_weight(epi_scale);
+    p.Zpre = aux16;                                    // the skip input
+  }
   p.aux16 = (epi == US_EPI_GELU) ? aux16 : nullptr;
   p.aux8 = (epi == US_EPI_GELU) ? aux8 : nullptr;
   p.table = (workspace && workspace_bytes >= (size_t)kTableAreaBytes) ? workspace : nullptr;
@@ -148,8 +158,9 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
   const bool fp8 = (x_dt == US_E4M3 && w_dt == US_E4M3 && g_dt == US_E5M2);
   if (!f16 && !fp8) return US_ERR_DTYPE;
   if (out_dt != US_F16 && out_dt != US_F32) return US_ERR_DTYPE;
-  if (epi != US_EPI_NONE && epi != US_EPI_GELU_GRAD) return US_ERR_DTYPE;
-  if (epi == US_EPI_GELU_GRAD && out_dt != US_F16) return US_ERR_DTYPE;
+  if (epi != US_EPI_NONE && epi != US_EPI_GELU_GRAD && epi != US_EPI_RESIDUAL) return US_ERR_DTYPE;
+  if (epi != US_EPI_NONE && out_dt != US_F16) return US_ERR_DTYPE;
+  if (epi == US_EPI_RESIDUAL && !residual_weight_ok(epi_scale)) return US_ERR_VALUE;
   if (b < 0 || m < 0 || n < 0 || !mult16(b) || !mult16(m) || !mult16(n)) return US_ERR_SHAPE;
   // with the GELU' epilogue the FP16 result is optional: its E5M2 copy alone may be asked for
   const bool do_dx = (dX || (epi == US_EPI_GELU_GRAD && aux8)) && b > 0 && m > 0;
@@ -157,7 +168,8 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
   if (!do_dx && !do_dw) return US_OK;
   if (do_dx && n > 0 && (!G || !W)) return US_ERR_NULL;
   if (do_dw && b > 0 && (!G || !X)) return US_ERR_NULL;
-  if (do_dx && epi == US_EPI_GELU_GRAD && !Zpre) return US_ERR_NULL;
+  if (do_dx && epi != US_EPI_NONE && !Zpre) return US_ERR_NULL;
+  if (epi == US_EPI_RESIDUAL && do_dx && !dX) return US_ERR_NULL;
   if (!aligned16(X) || !aligned16(W) || !aligned16(G) || !aligned16(dX) || !aligned16(dW) || !aligned16(Zpre) ||
       !aligned16(aux8) || !aligned16(workspace))
     return US_ERR_ALIGN;
@@ -177,7 +189,8 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
     p.scale = (beta_x > 0.0f) ? beta_x : (float)(1.0 / sqrt((double)(n > 0 ? n : 1)));
     p.epi = epi;
     p.epi_scale = (epi_scale > 0.0f) ? epi_scale : kGeluBeta;
-    p.Zpre = (epi == US_EPI_GELU_GRAD) ? Zpre : nullptr;
+    p.Zpre = (epi != US_EPI_NONE) ? Zpre : nullptr;
+    p.skip_scale = (epi == US_EPI_RESIDUAL) ? skip_weight(epi_scale) : 0.0f;
     p.aux8 = (epi == US_EPI_GELU_GRAD) ? aux8 : nullptr;
     p.table = table;
     p.tables_ready = tables_ready;
@@ -198,6 +211,48 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
   if (do_dx && launch_gemm(pdx, st) != hipSuccess) return US_ERR_LAUNCH;
   if (do_dw && launch_gemm(pdw, st) != hipSuccess) return US_ERR_LAUNCH;
   return US_OK;
+}
+
+us_status us_weighted_add(const void* a, const void* b, void* out, size_t n, us_dtype dt, float ca, float cb, void* stream) {
+  if (dt != US_F16 && dt != US_F32) return US_ERR_DTYPE;
+  if (n == 0) return US_OK;
+  if (!a || !b || !out) return US_ERR_NULL;
+  if (!aligned16(a) || !aligned16(b) || !aligned16(out)) return US_ERR_ALIGN;
+  return from_hip(launch_weighted_add(a, b, out, n, dt, ca, cb, as_stream(stream)));
+}
+
+us_status us_ffn_res_fwd(const void* Xskip, const void* X, const void* W1, const void* W2, void* Z, void* H, void* Out,
+                         long T, long d, long f, float tau, int mode, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!(tau > 0.0f && tau <= 1.0f)) return US_ERR_VALUE;
+  const bool fp8 = (mode & US_FFN_FP8) != 0;
+  const int ready = (mode & US_FFN_TABLES_READY) ? US_EPI_TABLES_READY : 0;
+  const us_dtype op = fp8 ? US_E4M3 : US_F16;
+  us_status s = us_linear_fwd(X, W1, Z, T, d, f, op, op, US_F16, 0.0f, (us_epilogue)(US_EPI_GELU | ready), 0.0f, fp8 ? nullptr : H,
+                              fp8 ? H : nullptr, workspace, workspace_bytes, stream);
+  if (s != US_OK) return s;
+  // layer 2 with the interpolation fused: Out = sqrt(1-tau) Xskip + sqrt(tau) fp16(f^-1/2 H W2)
+  return us_linear_fwd(H, W2, Out, T, f, d, op, op, US_F16, 0.0f, US_EPI_RESIDUAL, (float)sqrt((double)tau), const_cast<void*>(Xskip),
+                       nullptr, nullptr, 0, stream);
+}
+
+us_status us_ffn_res_bwd(const void* X, const void* W1, const void* W2, const void* Z, const void* H, const void* Gskip,
+                         const void* G, void* dZ16, void* dZ8, void* dXin, void* dW1, void* dW2, long T, long d, long f,
+                         float tau, int mode, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!(tau > 0.0f && tau <= 1.0f)) return US_ERR_VALUE;
+  const bool fp8 = (mode & US_FFN_FP8) != 0;
+  const int ready = (mode & US_FFN_TABLES_READY) ? US_EPI_TABLES_READY : 0;
+  const us_dtype op = fp8 ? US_E4M3 : US_F16;
+  const us_dtype gr = fp8 ? US_E5M2 : US_F16;
+  if (fp8 ? !dZ8 : !dZ16) return US_ERR_NULL;
+  // the branch sees the incoming gradient unscaled: layer 2 backward exactly as in us_ffn_bwd
+  us_status s = us_linear_bwd(H, W2, G, dZ16, dW2, T, f, d, op, op, gr, US_F16, 0.0f, 0.0f,
+                              (us_epilogue)(US_EPI_GELU_GRAD | ready), 0.0f, Z, fp8 ? dZ8 : nullptr, workspace, workspace_bytes,
+                              stream);
+  if (s != US_OK) return s;
+  // layer 1 backward; grad_X leaves the branch through the interpolation with the skip path's gradient
+  const void* dZ = fp8 ? dZ8 : dZ16;
+  return us_linear_bwd(X, W1, dZ, dXin, dW1, T, d, f, op, op, gr, US_F16, 0.0f, 0.0f, US_EPI_RESIDUAL, (float)sqrt((double)tau),
+                       Gskip, nullptr, workspace, workspace_bytes, stream);
 }
 
 size_t us_ffn_workspace_bytes(long T, long d, long f) {

@@ -275,6 +275,41 @@ hipError_t launch_gelu_fwd(const void* z, void* h, size_t n, us_dtype dt, float 
   return hipGetLastError();
 }
 
+// out = round( ca * a + cb * b ): the product ca * a rounded to FP32, then one fused multiply-add (the
+// same arithmetic as the residual epilogue of the matmul kernels).
+template <typename T>
+__global__ void __launch_bounds__(kThreads) weighted_add_kernel(const T* a, const T* b, T* out, size_t n, float ca, float cb) {
+  constexpr int V = 16 / sizeof(T);
+  typedef T vec_t __attribute__((ext_vector_type(V)));
+  const size_t nvec = n / V;
+  const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  const size_t nthr = (size_t)gridDim.x * kThreads;
+  auto one = [&](T x, T y) -> T {
+    const float r = __builtin_fmaf(cb, (float)y, ca * (float)x);
+    if constexpr (sizeof(T) == 2) return to_half(r);
+    else return r;
+  };
+  for (size_t v = tid; v < nvec; v += nthr) {
+    const vec_t av = *reinterpret_cast<const vec_t*>(a + v * V), bv = *reinterpret_cast<const vec_t*>(b + v * V);
+    vec_t o;
+#pragma unroll
+    for (int k = 0; k < V; ++k) o[k] = one(av[k], bv[k]);
+    *reinterpret_cast<vec_t*>(out + v * V) = o;
+  }
+  const size_t tail0 = nvec * V;
+  if (tid < n - tail0) out[tail0 + tid] = one(a[tail0 + tid], b[tail0 + tid]);
+}
+
+hipError_t launch_weighted_add(const void* a, const void* b, void* out, size_t n, us_dtype dt, float ca, float cb,
+                               hipStream_t st) {
+  if (dt == US_F16) {
+    weighted_add_kernel<_Float16><<<grid_for(n / 8), kThreads, 0, st>>>((const _Float16*)a, (const _Float16*)b, (_Float16*)out, n, ca, cb);
+  } else {
+    weighted_add_kernel<float><<<grid_for(n / 4), kThreads, 0, st>>>((const float*)a, (const float*)b, (float*)out, n, ca, cb);
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_gelu_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtype dt, float beta_g,
                            hipStream_t st) {
   if (dt == US_F16) {

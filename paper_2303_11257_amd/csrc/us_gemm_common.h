@@ -10,8 +10,10 @@ namespace us {
 // EPI_GELU_TAB / EPI_GELU_GRAD_TAB: same results as EPI_GELU (FP8 activation only) / EPI_GELU_GRAD,
 // taken from a table over the FP16 pre-activation that the workgroup copies into LDS.
 // EPI_GELU_TAB16: EPI_GELU with an FP16 activation output (and optionally its FP8 copy), from a table.
+// EPI_RESIDUAL: C = fp16( skip_scale * R + epi_scale * fp16(scale * acc) ), R an FP16 [M,N] input (Zpre).
 enum GemmEpi : int {
-  EPI_STORE = 0, EPI_GELU = 1, EPI_GELU_GRAD = 2, EPI_PARTIAL = 3, EPI_GELU_TAB = 4, EPI_GELU_GRAD_TAB = 5, EPI_GELU_TAB16 = 6
+  EPI_STORE = 0, EPI_GELU = 1, EPI_GELU_GRAD = 2, EPI_PARTIAL = 3, EPI_GELU_TAB = 4, EPI_GELU_GRAD_TAB = 5, EPI_GELU_TAB16 = 6,
+  EPI_RESIDUAL = 7
 };
 
 //   C[M,N] = epilogue( scale * sum_k A(m,k) * B(n,k) )
@@ -25,7 +27,8 @@ struct GemmArgs {
   long lda, ldb, ldc;    // elements
   long k_per_split;      // reduction range of one slice (blockIdx.y); a multiple of 128 elements
   float scale, epi_scale;
-  const _Float16* Zpre;  // EPI_GELU_GRAD: saved pre-activation [M,N], leading dimension ldc
+  float skip_scale;      // EPI_RESIDUAL: weight of the skip input
+  const _Float16* Zpre;  // EPI_GELU_GRAD: saved pre-activation; EPI_RESIDUAL: skip input; [M,N], leading dimension ldc
   _Float16* aux16;       // EPI_GELU: optional FP16 activation output
   uint8_t* aux8;         // optional FP8 copy of the epilogue's FP16 result
   float* partial;        // EPI_PARTIAL: [splits][M][N] FP32
@@ -167,6 +170,15 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
     stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), y);
     return;
   }
+  if (EPI == EPI_RESIDUAL) {
+    // weighted addition of the skip input and the FP16-rounded matmul result (the residual layer's
+    // interpolation): skip * R rounded to FP32, then one fused multiply-add, then the FP16 rounding
+    v8h r;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) r[k] = to_half(__builtin_fmaf(g.epi_scale, (float)y[k], g.skip_scale * (float)z[k]));
+    stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), r);
+    return;
+  }
   v8h r;
   if (EPI == EPI_GELU) {
     stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), y);   // the FP16 matmul result, kept for backward
@@ -193,7 +205,7 @@ template <class Cfg, bool WIDE, int EPI = EPI_STORE>
 struct EpiStrip {
   static constexpr int ES = WIDE ? 4 : 2;
   static constexpr int PITCH = Cfg::WN * ES + 16;
-  static constexpr int STRIP_BYTES = 32 * PITCH * Cfg::WAVES_MN;
+  static constexpr int STRIP_BYTES = 32 * PITCH * Cfg::WAVES;
   static constexpr int TABLE_BYTES = EPI == EPI_GELU_TAB ? kGeluTableBytes
                                      : EPI == EPI_GELU_GRAD_TAB ? kGeluSlopeTableBytes
                                      : EPI == EPI_GELU_TAB16 ? kGeluHalfTableBytes : 0;
@@ -204,9 +216,10 @@ struct EpiStrip {
 // 32x32 accumulator block holds (row l%32, column 8q + 4(l/32) + e).  Each wave pushes 32 rows of
 // its block at a time through its LDS strip and reads them back row-contiguously: all global stores
 // (and the read of the saved pre-activation) are 128-bit accesses sweeping whole rows.
-// Must be entered by all waves that hold accumulators (the first WAVES_M x WAVES_N of the workgroup)
-// after a workgroup barrier (the strips overlay the operand tiles).
-template <class Cfg, int EPI, bool WIDE>
+// Must be entered after a workgroup barrier (the strips overlay the operand tiles).  A wave works on
+// the 32-row blocks I0 .. I1-1 of its accumulators (all of them unless two wave groups share a tile:
+// then each group finishes one half of the rows, see the wave-split reduction of the direct kernel).
+template <class Cfg, int EPI, bool WIDE, int I0 = 0, int I1 = Cfg::FM>
 __device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&acc)[Cfg::FM][Cfg::FN], uint8_t* lds,
                                                      long m0, long n0, long split) {
   static_assert(WIDE ? (EPI == EPI_STORE || EPI == EPI_PARTIAL) : (EPI != EPI_PARTIAL), "");
@@ -226,38 +239,48 @@ __device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&a
   constexpr int EP = S::PITCH;
   const int wave = threadIdx.x >> 6;
   const int lane = threadIdx.x & 63;
-  const int wm0 = (wave % Cfg::WAVES_M) * Cfg::WM;
-  const int wn0 = (wave / Cfg::WAVES_M) * Cfg::WN;
+  const int wmn = wave % Cfg::WAVES_MN;
+  const int wm0 = (wmn % Cfg::WAVES_M) * Cfg::WM;
+  const int wn0 = (wmn / Cfg::WAVES_M) * Cfg::WN;
   uint8_t* strip = lds + wave * (32 * EP);
   const float scale = (EPI == EPI_PARTIAL) ? 1.0f : g.scale;
+  constexpr int NI = I1 - I0;                        // 32-row blocks this wave finishes
   constexpr int CPR = Cfg::WN * S::ES / 16;          // 16-byte chunks per strip row
   constexpr int PER_LANE = 32 * CPR / 64;
-  // GELU': the wave's whole share of the saved pre-activation is requested up front, before any store.
-  // Loads and stores share one in-order completion counter here, so a load issued between stores
-  // could only be waited for together with every store before it (each one an HBM round trip); with
-  // all loads first, the stores below are never waited for.
-  constexpr bool NEEDS_Z = (EPI == EPI_GELU_GRAD || EPI == EPI_GELU_GRAD_TAB);
-  v8h zpre[NEEDS_Z ? Cfg::FM : 1][NEEDS_Z ? PER_LANE : 1] = {};
-  if constexpr (NEEDS_Z) {
+  // GELU' / residual: the second input of the epilogue (saved pre-activation, skip tensor) is requested
+  // ahead of its use, for ZGROUP strips at a time and before any store of that group.  Loads and stores
+  // share one in-order completion counter here, so a load issued between stores could only be waited for
+  // together with every store before it (each one an HBM round trip); GELU' therefore fetches its whole
+  // share first and never waits for a store.  The residual epilogue has little arithmetic to hide
+  // behind and a tighter register budget (its kernels also hold the wave-split reduction), so it
+  // fetches two strips at a time and accepts one store drain in the middle.
+  constexpr bool NEEDS_Z = (EPI == EPI_GELU_GRAD || EPI == EPI_GELU_GRAD_TAB || EPI == EPI_RESIDUAL);
+  constexpr int ZGROUP = !NEEDS_Z ? 1 : (EPI == EPI_RESIDUAL && NI > 2) ? 2 : NI;
+  static_assert(NI % ZGROUP == 0, "");
+  v8h zpre[ZGROUP][NEEDS_Z ? PER_LANE : 1] = {};
+  auto fetch_group = [&](int i0) {
+    if constexpr (NEEDS_Z) {
 #pragma unroll
-    for (int i = 0; i < Cfg::FM; ++i)
+      for (int ii = 0; ii < ZGROUP; ++ii)
 #pragma unroll
-      for (int u = 0; u < PER_LANE; ++u) {
-        const int c = lane + u * 64;
-        const long m = m0 + wm0 + i * 32 + c / CPR;
-        const long n = n0 + wn0 + (c % CPR) * 8;
-        if (m < g.M && n < g.N) zpre[i][u] = *reinterpret_cast<const v8h*>(g.Zpre + m * g.ldc + n);
-      }
-  }
+        for (int u = 0; u < PER_LANE; ++u) {
+          const int c = lane + u * 64;
+          const long m = m0 + wm0 + (I0 + i0 + ii) * 32 + c / CPR;
+          const long n = n0 + wn0 + (c % CPR) * 8;
+          if (m < g.M && n < g.N) zpre[ii][u] = *reinterpret_cast<const v8h*>(g.Zpre + m * g.ldc + n);
+        }
+    }
+  };
+  fetch_group(0);
 #pragma unroll
-  for (int i = 0; i < Cfg::FM; ++i) {
+  for (int i = 0; i < NI; ++i) {
 #pragma unroll
     for (int j = 0; j < Cfg::FN; ++j) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int col = j * 32 + 8 * q + 4 * (lane >> 5);
-        const float v0 = acc[i][j][4 * q] * scale, v1 = acc[i][j][4 * q + 1] * scale;
-        const float v2 = acc[i][j][4 * q + 2] * scale, v3 = acc[i][j][4 * q + 3] * scale;
+        const float v0 = acc[I0 + i][j][4 * q] * scale, v1 = acc[I0 + i][j][4 * q + 1] * scale;
+        const float v2 = acc[I0 + i][j][4 * q + 2] * scale, v3 = acc[I0 + i][j][4 * q + 3] * scale;
         uint8_t* p = strip + (lane & 31) * EP + col * S::ES;
         if (WIDE) {
           v4f o = {v0, v1, v2, v3};
@@ -272,12 +295,15 @@ __device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&a
     __builtin_amdgcn_wave_barrier();
     // one unconditional wait for the pre-activation loads: the uses below sit in bounds-checked
     // branches, where the compiler would otherwise wait again and again, by then for the stores too
-    if (NEEDS_Z && i == 0) __builtin_amdgcn_s_waitcnt(0x0F70);
+    if (NEEDS_Z && i % ZGROUP == 0) {
+      if (i > 0) fetch_group(i);
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+    }
 #pragma unroll
     for (int u = 0; u < PER_LANE; ++u) {
       const int c = lane + u * 64;
       const int row = c / CPR, cc = c % CPR;
-      const long m = m0 + wm0 + i * 32 + row;
+      const long m = m0 + wm0 + (I0 + i) * 32 + row;
       const long n = n0 + wn0 + cc * (16 / S::ES);
       const uint8_t* p = strip + row * EP + cc * 16;
       if (m < g.M && n < g.N) {
@@ -289,7 +315,7 @@ __device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&a
             stream_store(reinterpret_cast<v4f*>((float*)g.C + m * g.ldc + n), v);
         } else {
           v8h y = *US_LDS_PTR(const v8h, p);
-          epilogue_row8<EPI, AUX_FMT>(g, m * g.ldc + n, y, zpre[NEEDS_Z ? i : 0][NEEDS_Z ? u : 0], lut);
+          epilogue_row8<EPI, AUX_FMT>(g, m * g.ldc + n, y, zpre[NEEDS_Z ? i % ZGROUP : 0][NEEDS_Z ? u : 0], lut);
         }
       }
     }

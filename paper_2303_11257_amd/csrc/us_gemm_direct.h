@@ -36,11 +36,11 @@ struct DirectTile {
   static constexpr int A_LOADS = A_BYTES / 16 / Cfg::THREADS;   // 16-byte loads per thread and stage
   static constexpr int B_LOADS = B_BYTES / 16 / Cfg::THREADS;
   static constexpr int RING_BYTES = Cfg::NST * STAGE_BYTES;
-  // WAVES_K > 1: the accumulators of the extra wave groups (FP32, one 256-byte row per register) sit
-  // behind the strips while they are added up
-  static constexpr int REDUCE_BYTES = (Cfg::WAVES_K - 1) * Cfg::WAVES_MN * Cfg::FM * Cfg::FN * 16 * 64 * 4;
-  static constexpr int REDUCE_OFFSET = EpiStrip<Cfg, WIDE, EPI>::BYTES;
-  static constexpr int EPI_BYTES = REDUCE_OFFSET + REDUCE_BYTES;
+  // WAVES_K = 2: the half of every wave's accumulators that its partner finishes (FP32, one 256-byte row
+  // per register) passes through LDS before the strips take the same space
+  static constexpr int REDUCE_BYTES = Cfg::WAVES_K == 1 ? 0 : Cfg::WAVES * (Cfg::FM / 2) * Cfg::FN * 16 * 64 * 4;
+  static constexpr int STRIP_TABLE_BYTES = EpiStrip<Cfg, WIDE, EPI>::BYTES;
+  static constexpr int EPI_BYTES = REDUCE_BYTES > STRIP_TABLE_BYTES ? REDUCE_BYTES : STRIP_TABLE_BYTES;
   static constexpr int LDS_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
   static_assert(A_BYTES % (16 * Cfg::THREADS) == 0 && B_BYTES % (16 * Cfg::THREADS) == 0, "whole wave loads only");
   static_assert(Cfg::NST >= 2 && Cfg::NST <= 5, "");
@@ -349,32 +349,45 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs& g, int bid, lon
 
   __syncthreads();       // every wave is past its last fragment read before the strips overlay the ring
   if constexpr (Cfg::WAVES_K > 1) {
-    // add the wave groups' accumulators in group order (a fixed order: the result is deterministic);
-    // register r of lane l of group wk >= 1 travels through red[wk-1][wmn][r][l]
-    constexpr int NR = FM * FN * 16;
-    float* red = reinterpret_cast<float*>(lds + T::REDUCE_OFFSET);
+    // Two wave groups hold partial sums of the same tile.  Each group finishes one half of the rows:
+    // it hands the other half of its accumulators to its partner through LDS and adds the partner's
+    // half to its own (one addition of two terms per element, so the order does not matter and the
+    // result is deterministic).  Register r of lane l travels through red[wk][wmn][r][l].
+    static_assert(Cfg::WAVES_K == 2 && FM % 2 == 0, "two groups, an even number of 32-row blocks");
+    constexpr int HALF = FM / 2, NR = HALF * FN * 16;
+    float* red = reinterpret_cast<float*>(lds);
     const int lane = threadIdx.x & 63;
-    if (wk > 0) {
-      float* mine = red + ((size_t)((wk - 1) * Cfg::WAVES_MN + wmn) * NR) * 64 + lane;
+    float* mine = red + ((size_t)(wk * Cfg::WAVES_MN + wmn) * NR) * 64 + lane;
+    const float* theirs = red + ((size_t)((wk ^ 1) * Cfg::WAVES_MN + wmn) * NR) * 64 + lane;
+    auto send = [&](auto I0c) {          // the rows the partner finishes
+      constexpr int I0 = decltype(I0c)::value;
 #pragma unroll
-      for (int i = 0; i < FM; ++i)
+      for (int i = 0; i < HALF; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) *US_LDS_PTR(float, mine + ((i * FN + j) * 16 + r) * 64) = acc[i][j][r];
-    }
+          for (int r = 0; r < 16; ++r) *US_LDS_PTR(float, mine + ((i * FN + j) * 16 + r) * 64) = acc[I0 + i][j][r];
+    };
+    auto receive = [&](auto I0c) {       // the rows this wave finishes
+      constexpr int I0 = decltype(I0c)::value;
+#pragma unroll
+      for (int i = 0; i < HALF; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[I0 + i][j][r] += *US_LDS_PTR(const float, theirs + ((i * FN + j) * 16 + r) * 64);
+          __builtin_amdgcn_sched_barrier(0);   // one block of 16 at a time keeps the register count down
+        }
+    };
+    if (wk == 0) send(std::integral_constant<int, HALF>{});
+    else send(std::integral_constant<int, 0>{});
     __syncthreads();
-    if (wk > 0) return;
-#pragma unroll
-    for (int k = 1; k < Cfg::WAVES_K; ++k) {
-      const float* theirs = red + ((size_t)((k - 1) * Cfg::WAVES_MN + wmn) * NR) * 64 + lane;
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc[i][j][r] += *US_LDS_PTR(const float, theirs + ((i * FN + j) * 16 + r) * 64);
-    }
+    if (wk == 0) receive(std::integral_constant<int, 0>{});
+    else receive(std::integral_constant<int, HALF>{});
+    __syncthreads();     // everything exchanged: the strips may overlay the exchange area
+    if (wk == 0) store_block_epilogue<Cfg, EPI, WIDE, 0, HALF>(g, acc, lds, m0, n0, split);
+    else store_block_epilogue<Cfg, EPI, WIDE, HALF, FM>(g, acc, lds, m0, n0, split);
+    return;
   }
   store_block_epilogue<Cfg, EPI, WIDE>(g, acc, lds, m0, n0, split);
 }

@@ -46,6 +46,7 @@ inline GemmArgs make_args(const GemmProblem& p, long k_per_split, int BM, int BN
   g.k_per_split = k_per_split;
   g.scale = p.scale;
   g.epi_scale = p.epi_scale;
+  g.skip_scale = p.skip_scale;
   g.Zpre = (const _Float16*)p.Zpre;
   g.aux16 = (_Float16*)p.aux16;
   g.aux8 = (uint8_t*)p.aux8;

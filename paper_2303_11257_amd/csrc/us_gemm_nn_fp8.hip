@@ -14,6 +14,7 @@ hipError_t gemm_nn_fp8(const GemmProblem& p, hipStream_t st) {
     return launch_one<true, CfgD256, true, 0, 0, true, false, EPI_GELU_TAB, false>(q, 1, p.K, st);
   }
   if (p.epi == US_EPI_GELU) return launch_sized<true, 0, 0, true, false, EPI_GELU, false>(p, 1, p.K, st);
+  if (p.epi == US_EPI_RESIDUAL) return launch_sized<true, 0, 0, true, false, EPI_RESIDUAL, false>(p, 1, p.K, st);
   return launch_store<true, 0, 0, true, false>(p, st);
 }
 

@@ -14,6 +14,7 @@ hipError_t gemm_nt_f16(const GemmProblem& p, hipStream_t st) {
     return launch_one<true, CfgD256, false, 0, 0, true, true, EPI_GELU_GRAD_TAB, false>(q, 1, p.K, st);
   }
   if (p.epi == US_EPI_GELU_GRAD) return launch_sized<false, 0, 0, true, true, EPI_GELU_GRAD, false>(p, 1, p.K, st);
+  if (p.epi == US_EPI_RESIDUAL) return launch_sized<false, 0, 0, true, true, EPI_RESIDUAL, false>(p, 1, p.K, st);
   return launch_store<false, 0, 0, true, true>(p, st);
 }
 

@@ -14,6 +14,7 @@ hipError_t gemm_nt_fp8(const GemmProblem& p, hipStream_t st) {
     return launch_one<true, CfgD256, true, 1, 0, true, true, EPI_GELU_GRAD_TAB, false>(q, 1, p.K, st);
   }
   if (p.epi == US_EPI_GELU_GRAD) return launch_sized<true, 1, 0, true, true, EPI_GELU_GRAD, false>(p, 1, p.K, st);
+  if (p.epi == US_EPI_RESIDUAL) return launch_sized<true, 1, 0, true, true, EPI_RESIDUAL, false>(p, 1, p.K, st);
   return launch_store<true, 1, 0, true, true>(p, st);
 }
 

@@ -35,14 +35,19 @@ hipError_t launch_pair_typed(const GemmProblem& dx, const GemmProblem& dw, hipSt
     }
     return launch_pair<GemmKind<CfgD256, FP8, FG, 0, true, true, EPI_GELU_GRAD_TAB, false>, KW>(q, dw, st);
   }
-  if (use_big_tile(dx.M, dx.N, 1)) return launch_pair<GemmKind<CfgD256, FP8, FG, 0, true, true, EPI_STORE, false>, KW>(dx, dw, st);
+  const bool big = use_big_tile(dx.M, dx.N, 1);
+  if (dx.epi == US_EPI_RESIDUAL) {
+    if (big) return launch_pair<GemmKind<CfgD256, FP8, FG, 0, true, true, EPI_RESIDUAL, false>, KW>(dx, dw, st);
+    return launch_pair<GemmKind<CfgM256, FP8, FG, 0, true, true, EPI_RESIDUAL, false>, KW>(dx, dw, st);
+  }
+  if (big) return launch_pair<GemmKind<CfgD256, FP8, FG, 0, true, true, EPI_STORE, false>, KW>(dx, dw, st);
   return launch_pair<GemmKind<CfgM256, FP8, FG, 0, true, true, EPI_STORE, false>, KW>(dx, dw, st);
 }
 
 // grad_X without an epilogue whose 256 x 128 tiles cover the CUs about once
 bool mid_tile_ok(const GemmProblem& dx) {
   const long t = ceil_div(dx.M, 256) * ceil_div(dx.N, 128);
-  return dx.epi == US_EPI_NONE && t >= 192 && t <= 320;
+  return (dx.epi == US_EPI_NONE || dx.epi == US_EPI_RESIDUAL) && t >= 192 && t <= 320;
 }
 
 }  // namespace
@@ -55,7 +60,7 @@ bool gemm_pair_applicable(const GemmProblem& dx, const GemmProblem& dw) {
   const long bk = fp8 ? 128 : 64;
   if (dx.K <= 0 || dx.K % bk || !(use_big_tile(dx.M, dx.N, 1) || mid_tile_ok(dx))) return false;
   if (dx.epi == US_EPI_GELU_GRAD && !dx.table) return false;       // the arithmetic epilogue is launched on its own
-  if (dx.epi != US_EPI_NONE && dx.epi != US_EPI_GELU_GRAD) return false;
+  if (dx.epi != US_EPI_NONE && dx.epi != US_EPI_GELU_GRAD && dx.epi != US_EPI_RESIDUAL) return false;
   if (!use_wave_split_tile(dw.M, dw.N, dw.K)) return false;
   return (ceil_div(dw.M, 128) * ceil_div(dw.N, 128)) % 8 == 0;
 }

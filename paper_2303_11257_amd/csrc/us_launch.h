@@ -16,6 +16,8 @@ hipError_t launch_cast_batch(int count, const void* const* src, void* const* dst
 hipError_t launch_gelu_fwd(const void* z, void* h, size_t n, us_dtype dt, float alpha_g, hipStream_t stream);
 hipError_t launch_gelu_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtype dt, float beta_g,
                            hipStream_t stream);
+hipError_t launch_weighted_add(const void* a, const void* b, void* out, size_t n, us_dtype dt, float ca, float cb,
+                               hipStream_t stream);
 
 // One GEMM problem  C[M,N] = epilogue( scale * sum_k A(m,k) B(n,k) ).
 //   a_kc / b_kc: operand is K-contiguous (element (r,k) at base[r*ld + k]) or K-strided
@@ -35,7 +37,8 @@ struct GemmProblem {
   float scale;
   us_epilogue epi;
   float epi_scale;
-  const void* Zpre;        // GELU_GRAD: FP16 [M,N], leading dimension ldc
+  float skip_scale;        // RESIDUAL: weight of the skip input (epi_scale is the weight of the matmul result)
+  const void* Zpre;        // GELU_GRAD: saved pre-activation; RESIDUAL: skip input; FP16 [M,N], leading dimension ldc
   void* aux16;             // GELU: FP16 [M,N] or NULL
   void* aux8;              // GELU: E4M3 [M,N]; GELU_GRAD: E5M2 [M,N]; or NULL
   void* workspace;         // split-K partial sums (FP32), or NULL

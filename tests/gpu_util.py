@@ -50,12 +50,14 @@ def cast_fp8(x: np.ndarray, dst_dt: int, scale: float = 1.0, want_stats: bool = 
 
 
 def linear_fwd(X, W, x_dt, w_dt, alpha=0.0, out_dt=us.F16, epi=us.EPI_NONE, epi_scale=0.0, want16=True, want8=False,
-               workspace_bytes=0):
+               workspace_bytes=0, skip=None):
     b, m = X.shape
     n = W.shape[1]
     dX_, dW_ = to_dev(X), to_dev(W)
     Y = empty((b, n), np.float16 if out_dt == us.F16 else np.float32)
     a16 = empty((b, n), np.float16) if (epi == us.EPI_GELU and want16) else None
+    if epi == us.EPI_RESIDUAL:
+        a16 = to_dev(skip)                          # an input here: the skip tensor of the interpolation
     a8 = empty((b, n), np.uint8) if (epi == us.EPI_GELU and want8) else None
     ws = torch.empty(workspace_bytes, dtype=torch.uint8, device=DEV) if workspace_bytes else None
     us.linear_fwd(ptr(dX_), ptr(dW_), ptr(Y), b, m, n, x_dt, w_dt, out_dt, alpha, epi, epi_scale, ptr(a16), ptr(a8),

@@ -20,7 +20,8 @@ def _declared():
 def test_every_declared_symbol_is_exported():
     names = _declared()
     assert {"us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd", "us_linear_scales",
-            "us_workspace_bytes", "us_status_string", "us_ffn_fwd", "us_ffn_bwd", "us_gelu_tables"} <= set(names)
+            "us_workspace_bytes", "us_status_string", "us_ffn_fwd", "us_ffn_bwd", "us_gelu_tables", "us_weighted_add",
+            "us_ffn_res_fwd", "us_ffn_res_bwd"} <= set(names)
     L = ctypes.CDLL(us.library_path())
     for n in names:
         assert hasattr(L, n), n
@@ -33,7 +34,7 @@ def test_scales_and_status_strings():
     with pytest.raises(us.UsError) as e:
         us.linear_scales(0, 4, 4)
     assert e.value.status == 2
-    for code in range(7):
+    for code in range(8):
         assert us.status_string(code)
 
 
@@ -67,6 +68,16 @@ def test_argument_errors_are_detected_on_the_host():
         (lambda: us.linear_bwd(16, 16, 16, 16, 16, 4096, 768, 3072, F16, F16, F16), 5),   # workspace missing
         (lambda: us.linear_bwd(16, 16, 16, 16, None, 16, 16, 16, F16, F16, F16, F16, 0, 0, us.EPI_GELU_GRAD), 1),
         (lambda: us.linear_bwd(16, 16, 8, 16, 16, 16, 16, 16, F16, F16, F16), 3),
+        (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, F16, F16, F16, 0.0, us.EPI_RESIDUAL, 0.5), 1),          # no skip input
+        (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, F16, F16, F16, 0.0, us.EPI_RESIDUAL, 1.5, 16), 7),     # weight > 1
+        (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, F16, F16, F16, 0.0, us.EPI_RESIDUAL, 0.0, 16), 7),
+        (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, F16, F16, F32, 0.0, us.EPI_RESIDUAL, 0.5, 16), 4),
+        (lambda: us.linear_bwd(16, 16, 16, 16, 16, 16, 16, 16, F16, F16, F16, F16, 0, 0, us.EPI_RESIDUAL, 0.5), 1),
+        (lambda: us.linear_bwd(16, 16, 16, 16, 16, 16, 16, 16, F16, F16, F16, F16, 0, 0, us.EPI_RESIDUAL, -1.0, 16), 7),
+        (lambda: us.weighted_add(16, None, 32, 8), 1),
+        (lambda: us.weighted_add(16, 16, 32, 8, E4), 4),
+        (lambda: us.ffn_res_fwd(16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 0.0, 0), 7),                          # tau must be in (0, 1]
+        (lambda: us.ffn_res_bwd(16, 16, 16, 16, 16, 16, 16, 16, None, 16, 16, 16, 16, 16, 16, 1.5, 0), 7),
         (lambda: us.gelu_tables(None, 1 << 20), 1),
         (lambda: us.gelu_tables(16, 1000), 5),                       # smaller than the table area
         (lambda: us.gelu_tables(24, 1 << 20), 3),

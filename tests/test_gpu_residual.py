@@ -1,0 +1,153 @@
+"""GPU parity: weighted addition and the residual FFN layer (interpolation fused into the matmul epilogues)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2303_11257_amd as us
+import synth
+from gpu_util import DEV, RTOL, TAU, assert_close, cast_fp8, empty, linear_bwd, linear_fwd, ptr, stream, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+O = oracle
+
+
+def _ulps(a, b):
+    """Largest distance, in FP16 steps, between two finite FP16 arrays."""
+    def key(x):
+        u = x.view(np.uint16).astype(np.int32)
+        return np.where(u & 0x8000, -(u & 0x7fff), u)
+    return int(np.max(np.abs(key(a) - key(b))))
+
+
+@pytest.mark.parametrize("dt", [np.float16, np.float32])
+def test_weighted_add_stand_alone(dt):
+    n = 1_000_003                                        # ragged tail
+    a = synth.normal(151, 1, (n,)).astype(dt)
+    b = synth.normal(151, 2, (n,), sigma=2.0).astype(dt)
+    ta, tb, out = to_dev(a), to_dev(b), empty((n,), dt)
+    skip, branch = O.residual_weights(0.3)
+    us.weighted_add(ptr(ta), ptr(tb), ptr(out), n, us.F16 if dt == np.float16 else us.F32, float(skip), float(branch), stream())
+    got, ref = to_np(out), O.weighted_add2(a, b, skip, branch)
+    if dt == np.float16:
+        assert _ulps(got, ref) <= 1 and np.mean(got != ref) < 1e-3      # FP32 arithmetic vs double: rare ties only
+    else:
+        mag = np.abs(float(skip) * a.astype(np.float64)) + np.abs(float(branch) * b.astype(np.float64))
+        assert np.max(np.abs(got.astype(np.float64) - ref.astype(np.float64)) / mag) < 2e-7     # FP32 roundings of the terms
+    # empty input, and in-place on the first operand
+    us.weighted_add(None, None, None, 0, us.F16, 1.0, 1.0, stream())
+    us.weighted_add(ptr(ta), ptr(tb), ptr(ta), n, us.F16 if dt == np.float16 else us.F32, float(skip), float(branch), stream())
+    assert np.array_equal(to_np(ta), got)
+
+
+@pytest.mark.parametrize("fp8", [False, True])
+@pytest.mark.parametrize("shape", [(272, 144, 400), (8192, 256, 1024)])
+def test_linear_with_residual_epilogues(fp8, shape):
+    """Forward: Y = skip*R + w*fp16(alpha X W); grad_X: dX = skip*R + w*fp16(beta_x G W^T).  Stage-wise against the
+    oracle: the interpolation is checked on the GPU's own FP16 matmul result (the plain-epilogue output)."""
+    b, m, n = shape
+    X, W, G = synth.linear_inputs(b, m, n, 157)
+    Rf, Rb = synth.normal(157, 8, (b, n)), synth.normal(157, 9, (b, m))
+    if fp8:
+        Xo, Wo, Go = cast_fp8(X, us.E4M3), cast_fp8(W, us.E4M3), cast_fp8(G, us.E5M2)
+        gdt = (us.E4M3, us.E4M3, us.E5M2)
+    else:
+        Xo, Wo, Go, gdt = X, W, G, (us.F16,) * 3
+    # (tau = 0.36 would give the weights 0.8, 0.6: FP16 inputs then put many exact sums next to FP16 rounding ties,
+    # which the FP32 arithmetic of the kernel resolves the other way in about 1 % of the elements)
+    skip, w = O.residual_weights(0.3)
+    Y0 = linear_fwd(Xo, Wo, gdt[0], gdt[1])
+    Y = linear_fwd(Xo, Wo, gdt[0], gdt[1], epi=us.EPI_RESIDUAL, epi_scale=float(w), skip=Rf)
+    ref = O.weighted_add2(Rf, Y0, skip, w)
+    assert _ulps(Y, ref) <= 1 and np.mean(Y != ref) < 2e-3
+    dX0, dW0, _ = linear_bwd(Xo, Wo, Go, *gdt)
+    dX, dW, _ = linear_bwd(Xo, Wo, Go, *gdt, epi=us.EPI_RESIDUAL, epi_scale=float(w), Zpre=Rb)
+    ref = O.weighted_add2(Rb, dX0, skip, w)
+    assert _ulps(dX, ref) <= 1 and np.mean(dX != ref) < 2e-3
+    assert np.array_equal(dW, dW0)                                          # grad_W is untouched by the epilogue
+
+
+class ResRun:
+    def __init__(self, X, W1, W2, G, tau, fp8):
+        T, d = X.shape
+        f = W1.shape[1]
+        dev = {k: to_dev(v) for k, v in dict(X=X, W1=W1, W2=W2, G=G).items()}
+        st = stream()
+        for k, fmt in (("X", us.E4M3), ("W1", us.E4M3), ("W2", us.E4M3), ("G", us.E5M2)):
+            if fp8:
+                dev[k + "op"] = torch.empty(dev[k].shape, dtype=torch.uint8, device=DEV)
+                us.cast_fp8(ptr(dev[k]), us.F16, ptr(dev[k + "op"]), fmt, dev[k].numel(), 1.0, None, st)
+            else:
+                dev[k + "op"] = dev[k]
+        e = lambda shape, dt=torch.float16: torch.empty(shape, dtype=dt, device=DEV)
+        dev["Z"], dev["Out"], dev["H"] = e((T, f)), e((T, d)), e((T, f), torch.uint8 if fp8 else torch.float16)
+        dev["dZ16"], dev["dXin"], dev["dW1"], dev["dW2"] = (None if fp8 else e((T, f))), e((T, d)), e((d, f)), e((f, d))
+        dev["dZ8"] = e((T, f), torch.uint8) if fp8 else None
+        wsb = us.ffn_workspace_bytes(T, d, f)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=DEV)
+        mode = us.FFN_FP8 if fp8 else 0
+        us.ffn_res_fwd(ptr(dev["X"]), ptr(dev["Xop"]), ptr(dev["W1op"]), ptr(dev["W2op"]), ptr(dev["Z"]), ptr(dev["H"]),
+                       ptr(dev["Out"]), T, d, f, tau, mode, ptr(ws), wsb, st)
+        us.ffn_res_bwd(ptr(dev["Xop"]), ptr(dev["W1op"]), ptr(dev["W2op"]), ptr(dev["Z"]), ptr(dev["H"]), ptr(dev["G"]),
+                       ptr(dev["Gop"]), ptr(dev["dZ16"]), ptr(dev["dZ8"]), ptr(dev["dXin"]), ptr(dev["dW1"]), ptr(dev["dW2"]),
+                       T, d, f, tau, mode, ptr(ws), wsb, st)
+        torch.cuda.synchronize()
+        self.dev = dev
+
+
+@pytest.mark.parametrize("fp8", [False, True])
+def test_small_residual_layer_against_the_oracle_chain(fp8):
+    """Whole layer, every element.  The interpolation outputs are compared with the oracle applied to the GPU's own
+    stage inputs (branch output and branch input gradient recomputed by the plain-epilogue kernels)."""
+    T, d, f, tau = 272, 144, 400, 0.3
+    X, W1, W2, G = synth.ffn_inputs(T, d, f, seed=163)
+    run = ResRun(X, W1, W2, G, tau, fp8)
+    g = lambda k: run.dev[k].cpu().numpy()
+    skip, w = O.residual_weights(tau)
+    act, grad = (O.E4M3, O.E5M2) if fp8 else (O.F16, O.F16)
+    gact, ggrad = (us.E4M3, us.E5M2) if fp8 else (us.F16, us.F16)
+    # forward: branch output from the GPU's stored H and W2 operand, then the oracle's interpolation
+    Ybranch = linear_fwd(g("H"), g("W2op"), gact, gact)
+    assert_close(Ybranch, O.linear_fwd(g("H"), g("W2op"), f ** -0.5, act, act), "branch output")
+    ref = O.weighted_add2(X, Ybranch, skip, w)
+    assert _ulps(g("Out"), ref) <= 1
+    # backward: dZ as in the plain FFN (checked there); grad_X of the branch from the GPU's stored dZ operand
+    dZop = g("dZ8") if fp8 else g("dZ16")
+    dXbranch, dW1, _ = linear_bwd(g("Xop"), g("W1op"), dZop, gact, gact, ggrad)
+    assert np.array_equal(g("dW1"), dW1)
+    assert _ulps(g("dXin"), O.weighted_add2(G, dXbranch, skip, w)) <= 1
+    # end to end against the oracle's own chain (its intermediates differ by rounding flips: tolerance of the matmuls)
+    fw = O.ffn_res_fwd(X, W1, W2, tau, fp8)
+    bw = O.ffn_res_bwd(X, W1, W2, G, fw, tau, fp8)
+    for k, ref in (("Out", fw["Out"]), ("dW2", bw["dW2"]), ("dW1", bw["dW1"]), ("dXin", bw["dXin"])):
+        e = np.abs(g(k).astype(np.float64) - ref.astype(np.float64))
+        assert np.sqrt(np.mean(e ** 2)) < (0.03 if fp8 else 3e-3), k           # FP8 chain: a flipped code upstream moves a sum
+
+
+def test_c3_residual_layer_fp8_sampled_and_variances():
+    c = synth.CONFIGS["C3"]
+    T, d, f, tau = c["T"], c["d"], c["f"], 0.5
+    X, W1, W2, G = synth.ffn_inputs(T, d, f, c["seed"])
+    run = ResRun(X, W1, W2, G, tau, True)
+    skip, w = O.residual_weights(tau)
+    rows = np.array([0, 1, 255, 256, 4097, 8191])
+    idx = torch.as_tensor(rows, device=DEV)
+    H_r, dZ_r = run.dev["H"][idx].cpu().numpy(), run.dev["dZ8"][idx].cpu().numpy()
+    W2op, W1op = run.dev["W2op"].cpu().numpy(), run.dev["W1op"].cpu().numpy()
+    # The branch's own FP16 result is not stored, so the reference uses the oracle's matmul on the GPU's stored
+    # operands: the GPU's value may sit within the matmul tolerance of it, and that error enters the output times w.
+    def close(got, skip_in, branch_ref, what):
+        ref = O.weighted_add2(skip_in, branch_ref, skip, w).astype(np.float64)
+        tol = float(w) * RTOL * np.maximum(np.abs(branch_ref.astype(np.float64)), TAU) + 2.0 ** -10 * np.maximum(np.abs(ref), TAU)
+        assert np.all(np.abs(got.astype(np.float64) - ref) <= tol), what
+    Yb = O.linear_fwd(H_r, W2op, f ** -0.5, O.E4M3, O.E4M3)
+    close(run.dev["Out"][idx].cpu().numpy(), X[rows], Yb, "Out rows")
+    dXb = O.linear_bwd_dx(dZ_r, W1op, f ** -0.5, O.E5M2, O.E4M3)
+    close(run.dev["dXin"][idx].cpu().numpy(), G[rows], dXb, "dXin rows")
+    v = lambda k: float(torch.var(run.dev[k].float()).item())
+    eh2 = float(O.gelu_scales()[0]) ** 2 * (1 / 3 + 1 / (2 * np.pi * np.sqrt(3)))
+    assert abs(v("Out") / ((1 - tau) + tau * eh2) - 1.0) < 0.05             # skip and branch are nearly independent
+    assert abs(v("dXin") - 1.0) < 0.05
+    assert abs(v("dW1") - 1.0) < 0.05 and abs(v("dW2") / eh2 - 1.0) < 0.05   # the branch's gradients carry no sqrt(tau)
