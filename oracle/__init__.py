@@ -63,6 +63,10 @@ def _load():
     lib.uso_linear_scales.restype = None
     lib.uso_weighted_add2.argtypes = [vp, vp, vp, sz, i, f, f]
     lib.uso_weighted_add2.restype = None
+    lib.uso_act_fwd.argtypes = [vp, vp, sz, i, i, f, f]
+    lib.uso_act_fwd.restype = None
+    lib.uso_act_bwd.argtypes = [vp, vp, vp, sz, i, i, f, f]
+    lib.uso_act_bwd.restype = None
     _lib = lib
     return lib
 
@@ -321,3 +325,46 @@ def ffn_res_bwd(X16, W1_16, W2_16, G16, fwd: dict, tau: float, fp8: bool):
     skip, branch = residual_weights(tau)
     r["dXin"] = weighted_add2(G16, r["dX"], skip, branch)
     return r
+
+
+# ---- the other activations of Table A.2 ------------------------------------------------------------
+GELU, RELU, TANH, SIGMOID = 0, 1, 2, 3
+
+
+def act_scales(kind: int):
+    """(alpha, beta) of an activation under z ~ N(0,1), by the rule of Sec. 5.2: alpha = 1/std(f(z)),
+    beta = 1/rms(f'(z)).  relu has closed forms (App. E.1): Var = (1 - 1/pi)/2 and E[f'^2] = 1/2; gelu: gelu_scales();
+    tanh and sigmoid by Gauss-Hermite quadrature (the paper found them "empirically": 1.593/1.467 and 4.802/4.722)."""
+    if kind == GELU:
+        return gelu_scales()
+    if kind == RELU:
+        return np.float32(math.sqrt(2.0 / (1.0 - 1.0 / math.pi))), np.float32(math.sqrt(2.0))
+    x, w = np.polynomial.hermite_e.hermegauss(200)
+    w = w / math.sqrt(2.0 * math.pi)
+    if kind == TANH:
+        f, df = np.tanh(x), 1.0 / np.cosh(x) ** 2
+    elif kind == SIGMOID:
+        sg = 1.0 / (1.0 + np.exp(-x))
+        f, df = sg, sg * (1.0 - sg)
+    else:
+        raise ValueError(kind)
+    mean = float(np.sum(w * f))
+    var = float(np.sum(w * f * f)) - mean * mean
+    return np.float32(1.0 / math.sqrt(var)), np.float32(1.0 / math.sqrt(float(np.sum(w * df * df))))
+
+
+def act_fwd(z, kind: int, scale, s1=1.0):
+    """h = round(scale * f(s1 * z)), storage type of z."""
+    z = _c(z)
+    h = np.empty_like(z)
+    _load().uso_act_fwd(_p(z), _p(h), z.size, _dt_of(z, None), kind, float(np.float32(s1)), float(np.float32(scale)))
+    return h
+
+
+def act_bwd(z, gh, kind: int, scale, s1=1.0):
+    """gz = round(scale * f'(s1 * z) * gh)."""
+    z, gh = _c(z), _c(gh)
+    assert gh.dtype == z.dtype and gh.shape == z.shape
+    gz = np.empty_like(z)
+    _load().uso_act_bwd(_p(z), _p(gh), _p(gz), z.size, _dt_of(z, None), kind, float(np.float32(s1)), float(np.float32(scale)))
+    return gz

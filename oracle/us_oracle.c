@@ -15,6 +15,8 @@
  *   gelu      Table A.2 "Activations": gelu(x) = x*Phi(x); backward by the f_grad definition of
  *             Sec. 5.1 (incoming gradient times the derivative), each with its own fixed scale.
  *
+ *   act       Table A.2 "Activations" (relu, tanh, sigmoid next to gelu), each with its own forward and
+ *             backward scale, and App. H "Activation functions" for the aligned form f(s1*x)*s2.
  *   residual  Sec. 5.3 "Weighted addition": the fixed(tau) interpolation sqrt(1-tau)*x + sqrt(tau)*f(x),
  *             with the residual branch's weight moved out of its backward pass (the id* rewrite of
  *             that section); Table A.2 "weighted_add" for the general scale rule.
@@ -295,6 +297,44 @@ void uso_gelu_bwd(const void* z, const void* gh, void* gz, size_t n, int dt, flo
     double zi = uso_decode_bits(load_bits(z, dt, i), dt);
     double gi = uso_decode_bits(load_bits(gh, dt, i), dt);
     store_bits(gz, dt, i, round_out((double)beta_g * (Phi(zi) + zi * phi(zi)) * gi, dt));
+  }
+}
+
+/*
+ * ---- the other activations of Table A.2, aligned form of App. H ----------------------------------
+ *   kind 0 gelu(x) = x*Phi(x), 1 relu(x) = max(x, 0), 2 tanh(x), 3 sigmoid(x) = 1/(1+exp(-x))
+ *   fwd  h  = round( scale * f(s1 * z) )              (scale = alpha, or s2 of the aligned form)
+ *   bwd  gz = round( scale * f'(s1 * z) * gh )        (scale = beta; the caller folds s1 into it)
+ * Readings: relu'(0) = 0 (the derivative is taken as the indicator of x > 0, whose mean square 1/2 is what
+ * App. E.1 uses for beta = sqrt 2); tanh and sigmoid by libm in double.
+ */
+static double act_f(int kind, double x) {
+  switch (kind) {
+    case 1: return x > 0.0 ? x : 0.0;
+    case 2: return tanh(x);
+    case 3: return 1.0 / (1.0 + exp(-x));
+    default: return x * Phi(x);
+  }
+}
+static double act_df(int kind, double x) {
+  switch (kind) {
+    case 1: return x > 0.0 ? 1.0 : 0.0;
+    case 2: { double c = cosh(x); return 1.0 / (c * c); }
+    case 3: { double s = 1.0 / (1.0 + exp(-fabs(x))); return s * (1.0 - s); }
+    default: return Phi(x) + x * phi(x);
+  }
+}
+void uso_act_fwd(const void* z, void* h, size_t n, int dt, int kind, float s1, float scale) {
+  for (size_t i = 0; i < n; ++i) {
+    double zi = uso_decode_bits(load_bits(z, dt, i), dt);
+    store_bits(h, dt, i, round_out((double)scale * act_f(kind, (double)s1 * zi), dt));
+  }
+}
+void uso_act_bwd(const void* z, const void* gh, void* gz, size_t n, int dt, int kind, float s1, float scale) {
+  for (size_t i = 0; i < n; ++i) {
+    double zi = uso_decode_bits(load_bits(z, dt, i), dt);
+    double gi = uso_decode_bits(load_bits(gh, dt, i), dt);
+    store_bits(gz, dt, i, round_out((double)scale * act_df(kind, (double)s1 * zi) * gi, dt));
   }
 }
 
