@@ -300,6 +300,22 @@ def main():
         out["residual_layer"] = {"what": "same workload with the fixed(tau=0.5) residual interpolation fused into the step "
                                          "(forward output and grad_X read one more FP16 [tokens, d_model] tensor each)",
                                  "ms_per_step": ms_res, "TFLOPs": ffn.flop / (ms_res * 1e-3) * 1e-12}
+    if not args.no_secondary:
+        # stand-alone elementwise kernels (HBM bound): 32 Mi FP16 elements, algorithmic bytes 4 B (forward) / 6 B (backward) / 6 B (add)
+        n = 32 << 20
+        za, zb, zo = (torch.randn(n, dtype=torch.float16, device="cuda:0") for _ in range(3))
+        st = torch.cuda.current_stream().cuda_stream
+        ew = {}
+        for name, kind in (("gelu", us.ACT_GELU), ("relu", us.ACT_RELU), ("tanh", us.ACT_TANH), ("sigmoid", us.ACT_SIGMOID)):
+            ms = time_steps(torch, lambda: us.act_fwd(za.data_ptr(), zo.data_ptr(), n, us.F16, kind, 0.0, 0.0, st), 50, 5)
+            ew[name + "_fwd_GBps"] = round(4.0 * n / (ms * 1e-3) * 1e-9, 1)
+            ms = time_steps(torch, lambda: us.act_bwd(za.data_ptr(), zb.data_ptr(), zo.data_ptr(), n, us.F16, kind, 0.0, 0.0, st), 50, 5)
+            ew[name + "_bwd_GBps"] = round(6.0 * n / (ms * 1e-3) * 1e-9, 1)
+        ms = time_steps(torch, lambda: us.weighted_add(za.data_ptr(), zb.data_ptr(), zo.data_ptr(), n, us.F16, 0.8, 0.6, st), 50, 5)
+        ew["weighted_add_GBps"] = round(6.0 * n / (ms * 1e-3) * 1e-9, 1)
+        ew["peak_GBps"] = PEAK_HBM_GBS
+        out["elementwise"] = ew
+        del za, zb, zo
     if not args.no_secondary and args.workload != "C2":
         w2 = WORKLOADS["C2"]
         f2 = Ffn(torch, us, synth, w2["T"], w2["d"], w2["f"], False, synth.BASE_SEED + 1)

@@ -50,6 +50,11 @@ typedef enum {
   US_EPI_GELU = 1,       /* forward: also emit the unit-scaled GELU of the output            */
   US_EPI_GELU_GRAD = 2,  /* grad_X: multiply by the unit-scaled GELU derivative of Zpre     */
   US_EPI_RESIDUAL = 3,   /* forward / grad_X: interpolate with a skip input (Sec. 5.3)      */
+  /* activation of US_EPI_GELU / US_EPI_GELU_GRAD when not gelu: OR one of these onto it (Table A.2
+   * "Activations"; epi_scale <= 0 then selects that activation's own unit-scaling factor)            */
+  US_EPI_ACT_RELU = 0x10,
+  US_EPI_ACT_TANH = 0x20,
+  US_EPI_ACT_SIGMOID = 0x30,
   /* flag, OR-ed onto one of the two above: the table area of the workspace already holds the GELU
    * tables for this epi_scale (us_gelu_tables) and must not be rebuilt by the call                */
   US_EPI_TABLES_READY = 0x100
@@ -211,6 +216,20 @@ us_status us_ffn_bwd(const void* X, const void* W1, const void* W2, const void* 
                      long T, long d, long f, int mode, void* workspace, size_t workspace_bytes,
                      void* stream);
 size_t us_ffn_workspace_bytes(long T, long d, long f);
+
+/*
+ * Stand-alone unit-scaled activation, any of Table A.2's (us_activation), in the aligned form of App. H
+ * "Activation functions", f_hat(x) = f(s1 x) s2:
+ *   fwd: h[i]  = round( scale * f(s1 * z[i]) )             scale <= 0: the activation's alpha (s1 = 1 assumed)
+ *   bwd: gz[i] = round( scale * f'(s1 * z[i]) * gh[i] )    scale <= 0: the activation's beta; relu'(0) = 0
+ * s1 <= 0 selects 1.  dt = US_F16 or US_F32; in-place use is allowed.  For a given scale, kind US_ACT_GELU
+ * with s1 = 1 computes what us_gelu_fwd / us_gelu_bwd compute.
+ */
+typedef enum { US_ACT_GELU = 0, US_ACT_RELU = 1, US_ACT_TANH = 2, US_ACT_SIGMOID = 3 } us_activation;
+us_status us_act_fwd(const void* z, void* h, size_t n, us_dtype dt, us_activation kind, float s1, float scale,
+                     void* stream);
+us_status us_act_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtype dt, us_activation kind,
+                     float s1, float scale, void* stream);
 
 /*
  * Stand-alone weighted addition of two tensors (Table A.2 "weighted_add" with two inputs; Sec. 5.3):

@@ -11,6 +11,8 @@ import os
 
 F32, F16, E4M3, E5M2 = 0, 1, 2, 3
 EPI_NONE, EPI_GELU, EPI_GELU_GRAD, EPI_RESIDUAL = 0, 1, 2, 3
+EPI_ACT_RELU, EPI_ACT_TANH, EPI_ACT_SIGMOID = 0x10, 0x20, 0x30   # OR-ed onto EPI_GELU / EPI_GELU_GRAD
+ACT_GELU, ACT_RELU, ACT_TANH, ACT_SIGMOID = 0, 1, 2, 3
 EPI_TABLES_READY = 0x100            # flag for EPI_GELU / EPI_GELU_GRAD: tables prebuilt by gelu_tables()
 FFN_FP8, FFN_TABLES_READY = 1, 2    # mode bits of ffn_fwd / ffn_bwd
 TABLE_AREA_BYTES = 256 * 1024
@@ -52,6 +54,8 @@ def lib() -> ctypes.CDLL:
     L.us_workspace_bytes.argtypes = [l, l, l]
     L.us_gelu_tables.argtypes = [vp, sz, f, f, vp]
     L.us_weighted_add.argtypes = [vp, vp, vp, sz, i, f, f, vp]
+    L.us_act_fwd.argtypes = [vp, vp, sz, i, i, f, f, vp]
+    L.us_act_bwd.argtypes = [vp, vp, vp, sz, i, i, f, f, vp]
     L.us_ffn_res_fwd.argtypes = [vp] * 7 + [l, l, l, f, i, vp, sz, vp]
     L.us_ffn_res_bwd.argtypes = [vp] * 12 + [l, l, l, f, i, vp, sz, vp]
     L.us_workspace_bytes.restype = sz
@@ -62,7 +66,7 @@ def lib() -> ctypes.CDLL:
     L.us_ffn_workspace_bytes.argtypes = [l, l, l]
     L.us_ffn_workspace_bytes.restype = sz
     for name in ("us_linear_scales", "us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd",
-                 "us_gelu_tables", "us_ffn_fwd", "us_ffn_bwd", "us_weighted_add", "us_ffn_res_fwd", "us_ffn_res_bwd"):
+                 "us_gelu_tables", "us_ffn_fwd", "us_ffn_bwd", "us_weighted_add", "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd"):
         getattr(L, name).restype = i
     _lib = L
     return L
@@ -150,3 +154,11 @@ def ffn_res_bwd(X, W1, W2, Z, H, Gskip, G, dZ16, dZ8, dXin, dW1, dW2, T, d, f, t
                 stream=None):
     _check(lib().us_ffn_res_bwd(X, W1, W2, Z, H, Gskip, G, dZ16, dZ8, dXin, dW1, dW2, T, d, f, tau, int(mode), workspace,
                                 workspace_bytes, stream), "us_ffn_res_bwd")
+
+
+def act_fwd(z, h, n, dt=F16, kind=ACT_GELU, s1=0.0, scale=0.0, stream=None):
+    _check(lib().us_act_fwd(z, h, n, dt, kind, s1, scale, stream), "us_act_fwd")
+
+
+def act_bwd(z, gh, gz, n, dt=F16, kind=ACT_GELU, s1=0.0, scale=0.0, stream=None):
+    _check(lib().us_act_bwd(z, gh, gz, n, dt, kind, s1, scale, stream), "us_act_bwd")

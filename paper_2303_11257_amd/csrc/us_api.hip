@@ -113,7 +113,9 @@ us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, l
                         us_dtype y_dt, float alpha, us_epilogue epi, float epi_scale, void* aux16, void* aux8,
                         void* workspace, size_t workspace_bytes, void* stream) {
   const bool tables_ready = ((int)epi & US_EPI_TABLES_READY) != 0;
-  epi = (us_epilogue)((int)epi & ~US_EPI_TABLES_READY);
+  const int act = ((int)epi >> 4) & 0xf;
+  epi = (us_epilogue)((int)epi & 0xf);
+  if (act > 3 || (act != 0 && epi != US_EPI_GELU && epi != US_EPI_GELU_GRAD)) return US_ERR_DTYPE;
   const bool f16 = (x_dt == US_F16 && w_dt == US_F16);
   const bool fp8 = (x_dt == US_E4M3 && w_dt == US_E4M3);
   if (!f16 && !fp8) return US_ERR_DTYPE;
@@ -136,7 +138,8 @@ us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, l
   p.a_dt = x_dt; p.b_dt = w_dt; p.c_dt = y_dt;
   p.scale = (alpha > 0.0f) ? alpha : (float)(1.0 / sqrt((double)(m > 0 ? m : 1)));
   p.epi = epi;
-  p.epi_scale = (epi_scale > 0.0f) ? epi_scale : kGeluAlpha;
+  p.epi_scale = (epi_scale > 0.0f) ? epi_scale : kActAlpha[act];
+  p.act = act;
   if (epi == US_EPI_RESIDUAL) {
     p.skip_scale = skip_weight(epi_scale);
     p.Zpre = aux16;                                    // the skip input
@@ -153,7 +156,9 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
                         us_epilogue epi, float epi_scale, const void* Zpre, void* aux8, void* workspace,
                         size_t workspace_bytes, void* stream) {
   const bool tables_ready = ((int)epi & US_EPI_TABLES_READY) != 0;
-  epi = (us_epilogue)((int)epi & ~US_EPI_TABLES_READY);
+  const int act = ((int)epi >> 4) & 0xf;
+  epi = (us_epilogue)((int)epi & 0xf);
+  if (act > 3 || (act != 0 && epi != US_EPI_GELU && epi != US_EPI_GELU_GRAD)) return US_ERR_DTYPE;
   const bool f16 = (x_dt == US_F16 && w_dt == US_F16 && g_dt == US_F16);
   const bool fp8 = (x_dt == US_E4M3 && w_dt == US_E4M3 && g_dt == US_E5M2);
   if (!f16 && !fp8) return US_ERR_DTYPE;
@@ -188,7 +193,8 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
     p.a_dt = g_dt; p.b_dt = w_dt; p.c_dt = out_dt;
     p.scale = (beta_x > 0.0f) ? beta_x : (float)(1.0 / sqrt((double)(n > 0 ? n : 1)));
     p.epi = epi;
-    p.epi_scale = (epi_scale > 0.0f) ? epi_scale : kGeluBeta;
+    p.epi_scale = (epi_scale > 0.0f) ? epi_scale : kActBeta[act];
+    p.act = act;
     p.Zpre = (epi != US_EPI_NONE) ? Zpre : nullptr;
     p.skip_scale = (epi == US_EPI_RESIDUAL) ? skip_weight(epi_scale) : 0.0f;
     p.aux8 = (epi == US_EPI_GELU_GRAD) ? aux8 : nullptr;
@@ -211,6 +217,25 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
   if (do_dx && launch_gemm(pdx, st) != hipSuccess) return US_ERR_LAUNCH;
   if (do_dw && launch_gemm(pdw, st) != hipSuccess) return US_ERR_LAUNCH;
   return US_OK;
+}
+
+us_status us_act_fwd(const void* z, void* h, size_t n, us_dtype dt, us_activation kind, float s1, float scale, void* stream) {
+  if ((dt != US_F16 && dt != US_F32) || (int)kind < 0 || (int)kind > 3) return US_ERR_DTYPE;
+  if (n == 0) return US_OK;
+  if (!z || !h) return US_ERR_NULL;
+  if (!aligned16(z) || !aligned16(h)) return US_ERR_ALIGN;
+  return from_hip(launch_act(z, nullptr, h, n, dt, (int)kind, false, s1 > 0.0f ? s1 : 1.0f, scale > 0.0f ? scale : kActAlpha[kind],
+                             as_stream(stream)));
+}
+
+us_status us_act_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtype dt, us_activation kind, float s1, float scale,
+                     void* stream) {
+  if ((dt != US_F16 && dt != US_F32) || (int)kind < 0 || (int)kind > 3) return US_ERR_DTYPE;
+  if (n == 0) return US_OK;
+  if (!z || !gh || !gz) return US_ERR_NULL;
+  if (!aligned16(z) || !aligned16(gh) || !aligned16(gz)) return US_ERR_ALIGN;
+  return from_hip(launch_act(z, gh, gz, n, dt, (int)kind, true, s1 > 0.0f ? s1 : 1.0f, scale > 0.0f ? scale : kActBeta[kind],
+                             as_stream(stream)));
 }
 
 us_status us_weighted_add(const void* a, const void* b, void* out, size_t n, us_dtype dt, float ca, float cb, void* stream) {

@@ -120,6 +120,60 @@ __device__ __forceinline__ float gelu_grad_scaled(float z, float gh, float beta_
   return r * gh;
 }
 
+// ---- the other activations of Table A.2 ---------------------------------------------------------------
+// kind: 0 gelu, 1 relu, 2 tanh, 3 sigmoid (us_activation).  Unit-scaling factors by the rule of Sec. 5.2
+// (alpha = 1/std f(z), beta = 1/rms f'(z), z ~ N(0,1)): relu in closed form (App. E.1), tanh and sigmoid
+// by quadrature (Table A.2 prints 1.593 / 1.467 and 4.802 / 4.722).
+constexpr float kActAlpha[4] = {kGeluAlpha, 1.7128585577011108f, 1.5925374031066895f, 4.801313400268555f};
+constexpr float kActBeta[4] = {kGeluBeta, 1.4142135381698608f, 1.4674135446548462f, 4.722646236419678f};
+
+// exp(-a) for a >= 0
+__device__ __forceinline__ float exp_neg(float a) { return __builtin_amdgcn_exp2f(-1.4426950408889634f * a); }
+
+__device__ __forceinline__ float tanh_f32(float x) {
+  const float ax = __builtin_fabsf(x);
+  float t;
+  if (ax < 0.25f) {
+    // odd Taylor polynomial: (1 - u)/(1 + u) below would cancel for small arguments
+    const float x2 = ax * ax;
+    float p = __builtin_fmaf(x2, 62.0f / 2835.0f, -17.0f / 315.0f);
+    p = __builtin_fmaf(p, x2, 2.0f / 15.0f);
+    p = __builtin_fmaf(p, x2, -1.0f / 3.0f);
+    t = __builtin_fmaf(p * x2, ax, ax);
+  } else {
+    const float u = exp_neg(2.0f * ax);
+    t = (1.0f - u) * __builtin_amdgcn_rcpf(1.0f + u);
+  }
+  return __builtin_copysignf(t, x);
+}
+
+// scale * f(x)
+__device__ __forceinline__ float act_scaled(int kind, float x, float scale) {
+  if (kind == 1) return scale * (x > 0.0f ? x : 0.0f);
+  if (kind == 2) return scale * tanh_f32(x);
+  if (kind == 3) {
+    const float u = exp_neg(__builtin_fabsf(x));
+    const float r = __builtin_amdgcn_rcpf(1.0f + u);
+    return scale * (x >= 0.0f ? r : u * r);
+  }
+  return gelu_scaled(x, scale);
+}
+// scale * f'(z) * gh   (relu'(0) = 0)
+__device__ __forceinline__ float act_grad_scaled(int kind, float z, float gh, float scale) {
+  if (kind == 1) return (z > 0.0f ? scale : 0.0f) * gh;
+  if (kind == 2) {                                    // sech^2 = 4u / (1 + u)^2, u = exp(-2|z|)
+    const float u = exp_neg(2.0f * __builtin_fabsf(z));
+    const float r = __builtin_amdgcn_rcpf(1.0f + u);
+    return scale * (4.0f * u * r * r) * gh;
+  }
+  if (kind == 3) {                                    // s (1 - s) = u / (1 + u)^2, u = exp(-|z|)
+    const float u = exp_neg(__builtin_fabsf(z));
+    const float r = __builtin_amdgcn_rcpf(1.0f + u);
+    return scale * (u * r * r) * gh;
+  }
+  return gelu_grad_scaled(z, gh, scale);
+}
+
 // ---- tables over the FP16 pre-activation (65536 possible inputs) ----------------------------------------
 // Forward: the E4M3 code of fp16(alpha_g * gelu(z)) for every bit pattern of z.
 // Backward: beta_g * gelu'(|z|) in FP32 for |z| <= 8 (bit patterns 0 .. 0x4800; the slope is exactly

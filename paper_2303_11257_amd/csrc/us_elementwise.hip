@@ -275,6 +275,46 @@ hipError_t launch_gelu_fwd(const void* z, void* h, size_t n, us_dtype dt, float 
   return hipGetLastError();
 }
 
+// out = round( scale * f(s1 * z) )  or  round( scale * f'(s1 * z) * gh )  for the activations of us_device.h
+template <typename T, bool BWD>
+__global__ void __launch_bounds__(kThreads) act_kernel(const T* z, const T* gh, T* out, size_t n, int kind, float s1, float scale) {
+  constexpr int V = 16 / sizeof(T);
+  typedef T vec_t __attribute__((ext_vector_type(V)));
+  const size_t nvec = n / V;
+  const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  const size_t nthr = (size_t)gridDim.x * kThreads;
+  auto one = [&](T zi, T gi) -> T {
+    const float r = BWD ? act_grad_scaled(kind, s1 * (float)zi, (float)gi, scale) : act_scaled(kind, s1 * (float)zi, scale);
+    if constexpr (sizeof(T) == 2) return to_half(r);
+    else return r;
+  };
+  for (size_t v = tid; v < nvec; v += nthr) {
+    const vec_t zv = *reinterpret_cast<const vec_t*>(z + v * V);
+    vec_t gv = zv;
+    if (BWD) gv = *reinterpret_cast<const vec_t*>(gh + v * V);
+    vec_t o;
+#pragma unroll
+    for (int k = 0; k < V; ++k) o[k] = one(zv[k], gv[k]);
+    *reinterpret_cast<vec_t*>(out + v * V) = o;
+  }
+  const size_t tail0 = nvec * V;
+  if (tid < n - tail0) out[tail0 + tid] = one(z[tail0 + tid], BWD ? gh[tail0 + tid] : z[tail0 + tid]);
+}
+
+hipError_t launch_act(const void* z, const void* gh, void* out, size_t n, us_dtype dt, int kind, bool bwd, float s1, float scale,
+                      hipStream_t st) {
+  if (dt == US_F16) {
+    const int grid = grid_for(n / 8);
+    if (bwd) act_kernel<_Float16, true><<<grid, kThreads, 0, st>>>((const _Float16*)z, (const _Float16*)gh, (_Float16*)out, n, kind, s1, scale);
+    else act_kernel<_Float16, false><<<grid, kThreads, 0, st>>>((const _Float16*)z, nullptr, (_Float16*)out, n, kind, s1, scale);
+  } else {
+    const int grid = grid_for(n / 4);
+    if (bwd) act_kernel<float, true><<<grid, kThreads, 0, st>>>((const float*)z, (const float*)gh, (float*)out, n, kind, s1, scale);
+    else act_kernel<float, false><<<grid, kThreads, 0, st>>>((const float*)z, nullptr, (float*)out, n, kind, s1, scale);
+  }
+  return hipGetLastError();
+}
+
 // out = round( ca * a + cb * b ): the product ca * a rounded to FP32, then one fused multiply-add (the
 // same arithmetic as the residual epilogue of the matmul kernels).
 template <typename T>

@@ -28,6 +28,7 @@ struct GemmArgs {
   long k_per_split;      // reduction range of one slice (blockIdx.y); a multiple of 128 elements
   float scale, epi_scale;
   float skip_scale;      // EPI_RESIDUAL: weight of the skip input
+  int act;               // EPI_GELU / EPI_GELU_GRAD (arithmetic forms): which activation, 0 = gelu (us_device.h)
   const _Float16* Zpre;  // EPI_GELU_GRAD: saved pre-activation; EPI_RESIDUAL: skip input; [M,N], leading dimension ldc
   _Float16* aux16;       // EPI_GELU: optional FP16 activation output
   uint8_t* aux8;         // optional FP8 copy of the epilogue's FP16 result
@@ -183,11 +184,11 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
   if (EPI == EPI_GELU) {
     stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), y);   // the FP16 matmul result, kept for backward
 #pragma unroll
-    for (int k = 0; k < 8; ++k) r[k] = to_half(gelu_scaled((float)y[k], g.epi_scale));
+    for (int k = 0; k < 8; ++k) r[k] = to_half(act_scaled(g.act, (float)y[k], g.epi_scale));
     if (g.aux16) stream_store(reinterpret_cast<v8h*>(g.aux16 + idx), r);
   } else {  // EPI_GELU_GRAD: y is the FP16-rounded matmul gradient
 #pragma unroll
-    for (int k = 0; k < 8; ++k) r[k] = to_half(gelu_grad_scaled((float)z[k], (float)y[k], g.epi_scale));
+    for (int k = 0; k < 8; ++k) r[k] = to_half(act_grad_scaled(g.act, (float)z[k], (float)y[k], g.epi_scale));
     if (g.C) stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), r);      // optional: the FP8 copy may be all that is wanted
   }
   if (g.aux8) {

@@ -47,6 +47,7 @@ inline GemmArgs make_args(const GemmProblem& p, long k_per_split, int BM, int BN
   g.scale = p.scale;
   g.epi_scale = p.epi_scale;
   g.skip_scale = p.skip_scale;
+  g.act = p.act;
   g.Zpre = (const _Float16*)p.Zpre;
   g.aux16 = (_Float16*)p.aux16;
   g.aux8 = (uint8_t*)p.aux8;
@@ -97,7 +98,7 @@ hipError_t launch_sized(const GemmProblem& p, int splits, long k_per_split, hipS
 template <bool FP8>
 inline bool table_path_ok(const GemmProblem& p) {
   const long bk = FP8 ? 128 : 64;
-  return p.table != nullptr && p.K > 0 && p.K % bk == 0 && use_big_tile(p.M, p.N, 1);
+  return p.table != nullptr && p.act == 0 && p.K > 0 && p.K % bk == 0 && use_big_tile(p.M, p.N, 1);   // the tables are gelu's
 }
 
 // Plain store epilogue: FP16 or FP32 output.

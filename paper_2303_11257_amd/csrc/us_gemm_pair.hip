@@ -59,7 +59,7 @@ bool gemm_pair_applicable(const GemmProblem& dx, const GemmProblem& dw) {
   if (dx.c_dt != US_F16 || dw.c_dt != US_F16 || dw.epi != US_EPI_NONE) return false;
   const long bk = fp8 ? 128 : 64;
   if (dx.K <= 0 || dx.K % bk || !(use_big_tile(dx.M, dx.N, 1) || mid_tile_ok(dx))) return false;
-  if (dx.epi == US_EPI_GELU_GRAD && !dx.table) return false;       // the arithmetic epilogue is launched on its own
+  if (dx.epi == US_EPI_GELU_GRAD && (!dx.table || dx.act != 0)) return false;   // the arithmetic epilogues are launched on their own
   if (dx.epi != US_EPI_NONE && dx.epi != US_EPI_GELU_GRAD && dx.epi != US_EPI_RESIDUAL) return false;
   if (!use_wave_split_tile(dw.M, dw.N, dw.K)) return false;
   return (ceil_div(dw.M, 128) * ceil_div(dw.N, 128)) % 8 == 0;

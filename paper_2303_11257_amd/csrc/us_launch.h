@@ -16,6 +16,8 @@ hipError_t launch_cast_batch(int count, const void* const* src, void* const* dst
 hipError_t launch_gelu_fwd(const void* z, void* h, size_t n, us_dtype dt, float alpha_g, hipStream_t stream);
 hipError_t launch_gelu_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtype dt, float beta_g,
                            hipStream_t stream);
+hipError_t launch_act(const void* z, const void* gh, void* out, size_t n, us_dtype dt, int kind, bool bwd, float s1, float scale,
+                      hipStream_t stream);
 hipError_t launch_weighted_add(const void* a, const void* b, void* out, size_t n, us_dtype dt, float ca, float cb,
                                hipStream_t stream);
 
@@ -37,6 +39,7 @@ struct GemmProblem {
   float scale;
   us_epilogue epi;
   float epi_scale;
+  int act;                 // GELU / GELU_GRAD epilogues: activation kind, 0 = gelu
   float skip_scale;        // RESIDUAL: weight of the skip input (epi_scale is the weight of the matmul result)
   const void* Zpre;        // GELU_GRAD: saved pre-activation; RESIDUAL: skip input; FP16 [M,N], leading dimension ldc
   void* aux16;             // GELU: FP16 [M,N] or NULL

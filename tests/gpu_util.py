@@ -55,15 +55,16 @@ def linear_fwd(X, W, x_dt, w_dt, alpha=0.0, out_dt=us.F16, epi=us.EPI_NONE, epi_
     n = W.shape[1]
     dX_, dW_ = to_dev(X), to_dev(W)
     Y = empty((b, n), np.float16 if out_dt == us.F16 else np.float32)
-    a16 = empty((b, n), np.float16) if (epi == us.EPI_GELU and want16) else None
-    if epi == us.EPI_RESIDUAL:
+    base = epi & 0xf                                # without the activation-kind and table flags
+    a16 = empty((b, n), np.float16) if (base == us.EPI_GELU and want16) else None
+    if base == us.EPI_RESIDUAL:
         a16 = to_dev(skip)                          # an input here: the skip tensor of the interpolation
-    a8 = empty((b, n), np.uint8) if (epi == us.EPI_GELU and want8) else None
+    a8 = empty((b, n), np.uint8) if (base == us.EPI_GELU and want8) else None
     ws = torch.empty(workspace_bytes, dtype=torch.uint8, device=DEV) if workspace_bytes else None
     us.linear_fwd(ptr(dX_), ptr(dW_), ptr(Y), b, m, n, x_dt, w_dt, out_dt, alpha, epi, epi_scale, ptr(a16), ptr(a8),
                   ptr(ws), workspace_bytes, stream())
     out = [to_np(Y)]
-    if epi == us.EPI_GELU:
+    if base == us.EPI_GELU:
         out += [to_np(a16) if a16 is not None else None, to_np(a8) if a8 is not None else None]
     return out[0] if len(out) == 1 else tuple(out)
 

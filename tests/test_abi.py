@@ -21,7 +21,7 @@ def test_every_declared_symbol_is_exported():
     names = _declared()
     assert {"us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd", "us_linear_scales",
             "us_workspace_bytes", "us_status_string", "us_ffn_fwd", "us_ffn_bwd", "us_gelu_tables", "us_weighted_add",
-            "us_ffn_res_fwd", "us_ffn_res_bwd"} <= set(names)
+            "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd"} <= set(names)
     L = ctypes.CDLL(us.library_path())
     for n in names:
         assert hasattr(L, n), n
@@ -74,6 +74,10 @@ def test_argument_errors_are_detected_on_the_host():
         (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, F16, F16, F32, 0.0, us.EPI_RESIDUAL, 0.5, 16), 4),
         (lambda: us.linear_bwd(16, 16, 16, 16, 16, 16, 16, 16, F16, F16, F16, F16, 0, 0, us.EPI_RESIDUAL, 0.5), 1),
         (lambda: us.linear_bwd(16, 16, 16, 16, 16, 16, 16, 16, F16, F16, F16, F16, 0, 0, us.EPI_RESIDUAL, -1.0, 16), 7),
+        (lambda: us.act_fwd(16, 32, 8, F16, 4), 4),                                                          # unknown activation
+        (lambda: us.act_bwd(16, None, 32, 8, F16, us.ACT_RELU), 1),
+        (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, F16, F16, F16, 0.0, us.EPI_NONE | us.EPI_ACT_RELU), 4),  # kind without an activation epilogue
+        (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, F16, F16, F16, 0.0, us.EPI_GELU | 0x40, 0.0, 16), 4),
         (lambda: us.weighted_add(16, None, 32, 8), 1),
         (lambda: us.weighted_add(16, 16, 32, 8, E4), 4),
         (lambda: us.ffn_res_fwd(16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 0.0, 0), 7),                          # tau must be in (0, 1]
