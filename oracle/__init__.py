@@ -63,6 +63,10 @@ def _load():
     lib.uso_linear_scales.restype = None
     lib.uso_weighted_add2.argtypes = [vp, vp, vp, sz, i, f, f]
     lib.uso_weighted_add2.restype = None
+    lib.uso_layer_norm_fwd.argtypes = [vp, vp, vp, vp, vp, vp, l, l, i, ctypes.c_double]
+    lib.uso_layer_norm_fwd.restype = None
+    lib.uso_layer_norm_bwd.argtypes = [vp, vp, vp, vp, vp, vp, l, l, i, ctypes.c_double, f]
+    lib.uso_layer_norm_bwd.restype = None
     lib.uso_act_fwd.argtypes = [vp, vp, sz, i, i, f, f]
     lib.uso_act_fwd.restype = None
     lib.uso_act_bwd.argtypes = [vp, vp, vp, sz, i, i, f, f]
@@ -368,3 +372,33 @@ def act_bwd(z, gh, kind: int, scale, s1=1.0):
     gz = np.empty_like(z)
     _load().uso_act_bwd(_p(z), _p(gh), _p(gz), z.size, _dt_of(z, None), kind, float(np.float32(s1)), float(np.float32(scale)))
     return gz
+
+
+# ---- scaled layer norm (Table A.2 "Other") -----------------------------------------------------------
+def layer_norm_scales(b: int):
+    """alpha = 1, beta_x = 1, beta_w = beta_c = b^-1/2 (b = rows, i.e. tokens)."""
+    return 1.0, 1.0, np.float32(1.0 / math.sqrt(b))
+
+
+def layer_norm_fwd(X, w, c, eps: float = 0.0):
+    """Returns (Y, mean, rstd): Y in the storage type of X, the row statistics in float64."""
+    X, w, c = _c(X), _c(w), _c(c)
+    b, n = X.shape
+    assert w.shape == (n,) and c.shape == (n,) and w.dtype == X.dtype and c.dtype == X.dtype
+    Y = np.empty_like(X)
+    mean, rstd = np.empty(b, np.float64), np.empty(b, np.float64)
+    _load().uso_layer_norm_fwd(_p(X), _p(w), _p(c), _p(Y), _p(mean), _p(rstd), b, n, _dt_of(X, None), float(eps))
+    return Y, mean, rstd
+
+
+def layer_norm_bwd(X, w, G, eps: float = 0.0, beta_wc=None):
+    """Returns (dX, dw, dc) for the incoming gradient G[b,n]."""
+    X, w, G = _c(X), _c(w), _c(G)
+    b, n = X.shape
+    assert G.shape == X.shape and G.dtype == X.dtype and w.shape == (n,)
+    if beta_wc is None:
+        beta_wc = layer_norm_scales(b)[2]
+    dX, dw, dc = np.empty_like(X), np.empty_like(w), np.empty_like(w)
+    _load().uso_layer_norm_bwd(_p(X), _p(w), _p(G), _p(dX), _p(dw), _p(dc), b, n, _dt_of(X, None), float(eps),
+                               float(np.float32(beta_wc)))
+    return dX, dw, dc

@@ -17,6 +17,9 @@
  *
  *   act       Table A.2 "Activations" (relu, tanh, sigmoid next to gelu), each with its own forward and
  *             backward scale, and App. H "Activation functions" for the aligned form f(s1*x)*s2.
+ *   layernorm Table A.2 "Other": layer_norm(X, w, c)_ij = c_j + w_j (X_ij - mu_i)/sigma_i with
+ *             mu_i = mean_j X_ij, sigma_i = sqrt(mean_j X_ij^2 - mu_i^2); alpha = beta_x = 1,
+ *             beta_w = beta_c = b^-1/2 (weights are cut-edges, activations are not: App. I.1).
  *   residual  Sec. 5.3 "Weighted addition": the fixed(tau) interpolation sqrt(1-tau)*x + sqrt(tau)*f(x),
  *             with the residual branch's weight moved out of its backward pass (the id* rewrite of
  *             that section); Table A.2 "weighted_add" for the general scale rule.
@@ -336,6 +339,78 @@ void uso_act_bwd(const void* z, const void* gh, void* gz, size_t n, int dt, int 
     double gi = uso_decode_bits(load_bits(gh, dt, i), dt);
     store_bits(gz, dt, i, round_out((double)scale * act_df(kind, (double)s1 * zi) * gi, dt));
   }
+}
+
+/*
+ * ---- scaled layer norm (Table A.2 "Other") ------------------------------------------------------
+ * X[b,n], w[n], c[n], Y[b,n] of storage type dt; mean[b], rstd[b] are doubles handed back for tests.
+ *   fwd:  Y_ij = round( c_j + w_j * (X_ij - mu_i) * rstd_i ),  rstd_i = 1/sqrt(mean_j X_ij^2 - mu_i^2 + eps)
+ *   bwd:  with xh = (X - mu) rstd and gh_ij = G_ij w_j (f_grad of the formula above, times beta):
+ *         dX_ij = round( rstd_i * (gh_ij - mean_j gh_ij - xh_ij * mean_j(gh_ij xh_ij)) )           beta_x = 1
+ *         dw_j  = round( beta_wc * sum_i G_ij xh_ij ),  dc_j = round( beta_wc * sum_i G_ij )       beta_wc = b^-1/2
+ * Readings: the paper's variance formula as printed (second moment minus squared mean, in double); it has no
+ * epsilon, so eps is an argument (0 gives the printed formula); every sum in index order.
+ */
+void uso_layer_norm_fwd(const void* X, const void* w, const void* c, void* Y, double* mean, double* rstd, long b, long n,
+                        int dt, double eps) {
+  for (long i = 0; i < b; ++i) {
+    double s1 = 0.0, s2 = 0.0;
+    for (long j = 0; j < n; ++j) {
+      double x = uso_decode_bits(load_bits(X, dt, (size_t)(i * n + j)), dt);
+      s1 += x;
+      s2 += x * x;
+    }
+    double mu = s1 / (double)n, var = s2 / (double)n - mu * mu;
+    double rs = 1.0 / sqrt(var + eps);
+    if (mean) mean[i] = mu;
+    if (rstd) rstd[i] = rs;
+    for (long j = 0; j < n; ++j) {
+      double x = uso_decode_bits(load_bits(X, dt, (size_t)(i * n + j)), dt);
+      double wj = uso_decode_bits(load_bits(w, dt, (size_t)j), dt), cj = uso_decode_bits(load_bits(c, dt, (size_t)j), dt);
+      store_bits(Y, dt, (size_t)(i * n + j), round_out(cj + wj * (x - mu) * rs, dt));
+    }
+  }
+}
+
+void uso_layer_norm_bwd(const void* X, const void* w, const void* G, void* dX, void* dw, void* dc, long b, long n, int dt,
+                        double eps, float beta_wc) {
+  double* aw = (double*)calloc((size_t)n, sizeof(double));
+  double* ac = (double*)calloc((size_t)n, sizeof(double));
+  for (long i = 0; i < b; ++i) {
+    double s1 = 0.0, s2 = 0.0;
+    for (long j = 0; j < n; ++j) {
+      double x = uso_decode_bits(load_bits(X, dt, (size_t)(i * n + j)), dt);
+      s1 += x;
+      s2 += x * x;
+    }
+    double mu = s1 / (double)n, rs = 1.0 / sqrt(s2 / (double)n - mu * mu + eps);
+    double m1 = 0.0, m2 = 0.0;
+    for (long j = 0; j < n; ++j) {
+      double x = uso_decode_bits(load_bits(X, dt, (size_t)(i * n + j)), dt);
+      double g = uso_decode_bits(load_bits(G, dt, (size_t)(i * n + j)), dt);
+      double wj = uso_decode_bits(load_bits(w, dt, (size_t)j), dt);
+      double xh = (x - mu) * rs, gh = g * wj;
+      m1 += gh;
+      m2 += gh * xh;
+      aw[j] += g * xh;
+      ac[j] += g;
+    }
+    m1 /= (double)n;
+    m2 /= (double)n;
+    for (long j = 0; j < n; ++j) {
+      double x = uso_decode_bits(load_bits(X, dt, (size_t)(i * n + j)), dt);
+      double g = uso_decode_bits(load_bits(G, dt, (size_t)(i * n + j)), dt);
+      double wj = uso_decode_bits(load_bits(w, dt, (size_t)j), dt);
+      double xh = (x - mu) * rs;
+      store_bits(dX, dt, (size_t)(i * n + j), round_out(rs * (g * wj - m1 - xh * m2), dt));
+    }
+  }
+  for (long j = 0; j < n; ++j) {
+    store_bits(dw, dt, (size_t)j, round_out((double)beta_wc * aw[j], dt));
+    store_bits(dc, dt, (size_t)j, round_out((double)beta_wc * ac[j], dt));
+  }
+  free(aw);
+  free(ac);
 }
 
 /*
