@@ -313,6 +313,16 @@ def main():
             ew[name + "_bwd_GBps"] = round(6.0 * n / (ms * 1e-3) * 1e-9, 1)
         ms = time_steps(torch, lambda: us.weighted_add(za.data_ptr(), zb.data_ptr(), zo.data_ptr(), n, us.F16, 0.8, 0.6, st), 50, 5)
         ew["weighted_add_GBps"] = round(6.0 * n / (ms * 1e-3) * 1e-9, 1)
+        # scaled layer norm on [32768, 1024] FP16 (the BERT-large hidden size): 4 B / element forward, 6 B backward
+        lb, ln = n // 1024, 1024
+        lw, lc, ldw, ldc = (torch.ones(ln, dtype=torch.float16, device="cuda:0") for _ in range(4))
+        lwsb = us.layer_norm_workspace_bytes(lb, ln)
+        lws = torch.empty(lwsb, dtype=torch.uint8, device="cuda:0")
+        ms = time_steps(torch, lambda: us.layer_norm_fwd(za.data_ptr(), lw.data_ptr(), lc.data_ptr(), zo.data_ptr(), lb, ln, 1e-5, st), 50, 5)
+        ew["layer_norm_fwd_GBps"] = round(4.0 * n / (ms * 1e-3) * 1e-9, 1)
+        ms = time_steps(torch, lambda: us.layer_norm_bwd(za.data_ptr(), lw.data_ptr(), zb.data_ptr(), zo.data_ptr(), ldw.data_ptr(),
+                                                         ldc.data_ptr(), lb, ln, 1e-5, 0.0, lws.data_ptr(), lwsb, st), 50, 5)
+        ew["layer_norm_bwd_GBps"] = round(6.0 * n / (ms * 1e-3) * 1e-9, 1)
         ew["peak_GBps"] = PEAK_HBM_GBS
         out["elementwise"] = ew
         del za, zb, zo

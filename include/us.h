@@ -232,6 +232,26 @@ us_status us_act_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtype
                      float s1, float scale, void* stream);
 
 /*
+ * Scaled layer norm over the last dimension (Table A.2 "Other"), FP16 storage, FP32 arithmetic:
+ *   fwd:  Y[i,j] = fp16( c[j] + w[j] * (X[i,j] - mu_i) * rstd_i ),  mu_i = mean_j X[i,j],
+ *         rstd_i = (mean_j (X[i,j] - mu_i)^2 + eps)^-1/2            (alpha = 1; the paper's formula has eps = 0)
+ *   bwd:  xh = (X - mu) rstd, gh = G * w:
+ *         dX[i,j] = fp16( rstd_i * (gh[i,j] - mean_j gh[i,j] - xh[i,j] * mean_j(gh[i,j] xh[i,j])) )    (beta_x = 1)
+ *         dw[j] = fp16( beta_wc * sum_i G[i,j] xh[i,j] ),  dc[j] = fp16( beta_wc * sum_i G[i,j] )
+ *         beta_wc <= 0 selects b^-1/2 (Table A.2: weight and bias are cut-edges, scaled by the row count).
+ * X, Y, G, dX: [b,n]; w, c, dw, dc: [n]; n a multiple of 16 and at most 4096 (a wave keeps a row in registers).
+ * The backward pass recomputes the row statistics from X.  Its workspace (us_layer_norm_workspace_bytes,
+ * 16-byte aligned, contents undefined on entry and exit) holds per-32-row column sums that a second kernel
+ * adds in order, so the result does not depend on scheduling.
+ */
+us_status us_layer_norm_fwd(const void* X, const void* w, const void* c, void* Y, long b, long n, float eps,
+                            void* stream);
+us_status us_layer_norm_bwd(const void* X, const void* w, const void* G, void* dX, void* dw, void* dc, long b,
+                            long n, float eps, float beta_wc, void* workspace, size_t workspace_bytes,
+                            void* stream);
+size_t us_layer_norm_workspace_bytes(long b, long n);
+
+/*
  * Stand-alone weighted addition of two tensors (Table A.2 "weighted_add" with two inputs; Sec. 5.3):
  *   out[i] = round( ca * a[i] + cb * b[i] ),  dt = US_F16 or US_F32 for all three arrays; out may alias a or b.
  * The unit-scaling factor alpha = (ca^2 + cb^2)^-1/2 is the caller's to fold into ca, cb (it is 1 for the

@@ -54,6 +54,10 @@ def lib() -> ctypes.CDLL:
     L.us_workspace_bytes.argtypes = [l, l, l]
     L.us_gelu_tables.argtypes = [vp, sz, f, f, vp]
     L.us_weighted_add.argtypes = [vp, vp, vp, sz, i, f, f, vp]
+    L.us_layer_norm_fwd.argtypes = [vp, vp, vp, vp, l, l, f, vp]
+    L.us_layer_norm_bwd.argtypes = [vp, vp, vp, vp, vp, vp, l, l, f, f, vp, sz, vp]
+    L.us_layer_norm_workspace_bytes.argtypes = [l, l]
+    L.us_layer_norm_workspace_bytes.restype = sz
     L.us_act_fwd.argtypes = [vp, vp, sz, i, i, f, f, vp]
     L.us_act_bwd.argtypes = [vp, vp, vp, sz, i, i, f, f, vp]
     L.us_ffn_res_fwd.argtypes = [vp] * 7 + [l, l, l, f, i, vp, sz, vp]
@@ -66,7 +70,7 @@ def lib() -> ctypes.CDLL:
     L.us_ffn_workspace_bytes.argtypes = [l, l, l]
     L.us_ffn_workspace_bytes.restype = sz
     for name in ("us_linear_scales", "us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd",
-                 "us_gelu_tables", "us_ffn_fwd", "us_ffn_bwd", "us_weighted_add", "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd"):
+                 "us_gelu_tables", "us_ffn_fwd", "us_ffn_bwd", "us_weighted_add", "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd", "us_layer_norm_fwd", "us_layer_norm_bwd"):
         getattr(L, name).restype = i
     _lib = L
     return L
@@ -162,3 +166,15 @@ def act_fwd(z, h, n, dt=F16, kind=ACT_GELU, s1=0.0, scale=0.0, stream=None):
 
 def act_bwd(z, gh, gz, n, dt=F16, kind=ACT_GELU, s1=0.0, scale=0.0, stream=None):
     _check(lib().us_act_bwd(z, gh, gz, n, dt, kind, s1, scale, stream), "us_act_bwd")
+
+
+def layer_norm_fwd(X, w, c, Y, b, n, eps=0.0, stream=None):
+    _check(lib().us_layer_norm_fwd(X, w, c, Y, b, n, eps, stream), "us_layer_norm_fwd")
+
+
+def layer_norm_bwd(X, w, G, dX, dw, dc, b, n, eps=0.0, beta_wc=0.0, workspace=None, workspace_bytes=0, stream=None):
+    _check(lib().us_layer_norm_bwd(X, w, G, dX, dw, dc, b, n, eps, beta_wc, workspace, workspace_bytes, stream), "us_layer_norm_bwd")
+
+
+def layer_norm_workspace_bytes(b: int, n: int) -> int:
+    return int(lib().us_layer_norm_workspace_bytes(b, n))

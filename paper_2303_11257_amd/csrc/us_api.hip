@@ -238,6 +238,30 @@ us_status us_act_bwd(const void* z, const void* gh, void* gz, size_t n, us_dtype
                              as_stream(stream)));
 }
 
+us_status us_layer_norm_fwd(const void* X, const void* w, const void* c, void* Y, long b, long n, float eps, void* stream) {
+  if (b < 0 || n < 0 || !mult16(n) || n > 4096) return US_ERR_SHAPE;
+  if (!(eps >= 0.0f)) return US_ERR_VALUE;
+  if (b == 0 || n == 0) return US_OK;
+  if (!X || !w || !c || !Y) return US_ERR_NULL;
+  if (!aligned16(X) || !aligned16(w) || !aligned16(c) || !aligned16(Y)) return US_ERR_ALIGN;
+  return from_hip(launch_layer_norm_fwd(X, w, c, Y, b, n, eps, as_stream(stream)));
+}
+
+size_t us_layer_norm_workspace_bytes(long b, long n) { return (b < 1 || n < 1) ? 0 : layer_norm_workspace_bytes(b, n); }
+
+us_status us_layer_norm_bwd(const void* X, const void* w, const void* G, void* dX, void* dw, void* dc, long b, long n, float eps,
+                            float beta_wc, void* workspace, size_t workspace_bytes, void* stream) {
+  if (b < 0 || n < 0 || !mult16(n) || n > 4096) return US_ERR_SHAPE;
+  if (!(eps >= 0.0f)) return US_ERR_VALUE;
+  if (b == 0 || n == 0) return US_OK;
+  if (!X || !w || !G || !dX || !dw || !dc) return US_ERR_NULL;
+  if (!aligned16(X) || !aligned16(w) || !aligned16(G) || !aligned16(dX) || !aligned16(dw) || !aligned16(dc) || !aligned16(workspace))
+    return US_ERR_ALIGN;
+  if (!workspace || workspace_bytes < layer_norm_workspace_bytes(b, n)) return US_ERR_WORKSPACE;
+  if (!(beta_wc > 0.0f)) beta_wc = (float)(1.0 / sqrt((double)b));
+  return from_hip(launch_layer_norm_bwd(X, w, G, dX, dw, dc, b, n, eps, beta_wc, workspace, as_stream(stream)));
+}
+
 us_status us_weighted_add(const void* a, const void* b, void* out, size_t n, us_dtype dt, float ca, float cb, void* stream) {
   if (dt != US_F16 && dt != US_F32) return US_ERR_DTYPE;
   if (n == 0) return US_OK;

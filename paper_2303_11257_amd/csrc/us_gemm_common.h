@@ -184,11 +184,25 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
   if (EPI == EPI_GELU) {
     stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), y);   // the FP16 matmul result, kept for backward
 #pragma unroll
-    for (int k = 0; k < 8; ++k) r[k] = to_half(act_scaled(g.act, (float)y[k], g.epi_scale));
+    for (int k = 0; k < 8; ++k) r[k] = half_from_bits(0);
+    if (g.act == 0) {      // uniform branch: gelu keeps its own short path, the other activations of Table A.2 share one
+#pragma unroll
+      for (int k = 0; k < 8; ++k) r[k] = to_half(gelu_scaled((float)y[k], g.epi_scale));
+    } else {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) r[k] = to_half(act_scaled(g.act, (float)y[k], g.epi_scale));
+    }
     if (g.aux16) stream_store(reinterpret_cast<v8h*>(g.aux16 + idx), r);
   } else {  // EPI_GELU_GRAD: y is the FP16-rounded matmul gradient
 #pragma unroll
-    for (int k = 0; k < 8; ++k) r[k] = to_half(act_grad_scaled(g.act, (float)z[k], (float)y[k], g.epi_scale));
+    for (int k = 0; k < 8; ++k) r[k] = half_from_bits(0);
+    if (g.act == 0) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) r[k] = to_half(gelu_grad_scaled((float)z[k], (float)y[k], g.epi_scale));
+    } else {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) r[k] = to_half(act_grad_scaled(g.act, (float)z[k], (float)y[k], g.epi_scale));
+    }
     if (g.C) stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), r);      // optional: the FP8 copy may be all that is wanted
   }
   if (g.aux8) {

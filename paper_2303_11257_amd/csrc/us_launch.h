@@ -21,6 +21,11 @@ hipError_t launch_act(const void* z, const void* gh, void* out, size_t n, us_dty
 hipError_t launch_weighted_add(const void* a, const void* b, void* out, size_t n, us_dtype dt, float ca, float cb,
                                hipStream_t stream);
 
+size_t layer_norm_workspace_bytes(long b, long n);
+hipError_t launch_layer_norm_fwd(const void* X, const void* w, const void* c, void* Y, long b, long n, float eps, hipStream_t stream);
+hipError_t launch_layer_norm_bwd(const void* X, const void* w, const void* G, void* dX, void* dw, void* dc, long b, long n, float eps,
+                                 float beta_wc, void* workspace, hipStream_t stream);
+
 // One GEMM problem  C[M,N] = epilogue( scale * sum_k A(m,k) B(n,k) ).
 //   a_kc / b_kc: operand is K-contiguous (element (r,k) at base[r*ld + k]) or K-strided
 //   (element (r,k) at base[k*ld + r]).  The three layer-level products map to

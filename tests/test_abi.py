@@ -21,7 +21,8 @@ def test_every_declared_symbol_is_exported():
     names = _declared()
     assert {"us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd", "us_linear_scales",
             "us_workspace_bytes", "us_status_string", "us_ffn_fwd", "us_ffn_bwd", "us_gelu_tables", "us_weighted_add",
-            "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd"} <= set(names)
+            "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd", "us_layer_norm_fwd", "us_layer_norm_bwd",
+            "us_layer_norm_workspace_bytes"} <= set(names)
     L = ctypes.CDLL(us.library_path())
     for n in names:
         assert hasattr(L, n), n
@@ -48,6 +49,7 @@ def test_workspace_rule():
     assert wb > 0 and wb % (768 * 3072 * 4) == 0                    # whole FP32 slices of the output
     assert us.ffn_workspace_bytes(4096, 768, 3072) >= wb + table_area
     assert us.workspace_bytes(0, 16, 16) == 0
+    assert us.layer_norm_workspace_bytes(8192, 1024) == 256 * 2 * 1024 * 4 and us.layer_norm_workspace_bytes(33, 16) == 2 * 2 * 16 * 4
 
 
 def test_argument_errors_are_detected_on_the_host():
@@ -78,6 +80,11 @@ def test_argument_errors_are_detected_on_the_host():
         (lambda: us.act_bwd(16, None, 32, 8, F16, us.ACT_RELU), 1),
         (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, F16, F16, F16, 0.0, us.EPI_NONE | us.EPI_ACT_RELU), 4),  # kind without an activation epilogue
         (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, F16, F16, F16, 0.0, us.EPI_GELU | 0x40, 0.0, 16), 4),
+        (lambda: us.layer_norm_fwd(16, 16, 16, 16, 4, 24), 2),                                               # n not a multiple of 16
+        (lambda: us.layer_norm_fwd(16, 16, 16, 16, 4, 8192), 2),                                             # row too long
+        (lambda: us.layer_norm_fwd(16, 16, None, 16, 4, 32), 1),
+        (lambda: us.layer_norm_fwd(16, 16, 16, 16, 4, 32, -1.0), 7),
+        (lambda: us.layer_norm_bwd(16, 16, 16, 16, 16, 16, 64, 32, 0.0, 0.0, 16, 100), 5),                   # workspace too small
         (lambda: us.weighted_add(16, None, 32, 8), 1),
         (lambda: us.weighted_add(16, 16, 32, 8, E4), 4),
         (lambda: us.ffn_res_fwd(16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 0.0, 0), 7),                          # tau must be in (0, 1]
