@@ -105,6 +105,13 @@ inline void choose_xcd_grid(long tiles_m, long tiles_n, int& gm, int& gn) {
 template <class V>
 __device__ __forceinline__ void stream_store(V* p, V v) { __builtin_nontemporal_store(v, p); }
 
+// FP16 result of a GELU' epilogue: the operand of the next two matmuls unless an FP8 copy is written too.
+__device__ __forceinline__ void store_grad(const GemmArgs& g, long idx, v8h r) {
+  v8h* p = reinterpret_cast<v8h*>((_Float16*)g.C + idx);
+  if (g.aux8) stream_store(p, r);
+  else *p = r;
+}
+
 // ---- epilogue on eight consecutive columns of one row (FP16 strip) ---------------------------------
 // z: the saved pre-activation at the same eight positions (GELU' epilogues only; fetched by the caller
 // well ahead of its use).
@@ -135,7 +142,7 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
       const _Float16 far = neg ? half_from_bits(a >= 0x7c00u ? 0x7e00u : 0x8000u) : to_half(g.epi_scale * (float)y[k]);
       r[k] = (a > (uint32_t)kGeluHalfLast) ? far : t;
     }
-    if (g.aux16) stream_store(reinterpret_cast<v8h*>(g.aux16 + idx), r);
+    if (g.aux16) *reinterpret_cast<v8h*>(g.aux16 + idx) = r;   // read by the next matmul: a normal store
     if (g.aux8) {
       const v2h p0 = {r[0], r[1]}, p1 = {r[2], r[3]}, p2 = {r[4], r[5]}, p3 = {r[6], r[7]};
       v2i w;
@@ -157,7 +164,7 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
       t = (a >= 0x7c00u) ? __builtin_nanf("") : t;       // +-inf and NaN, as the arithmetic form gives
       r[k] = to_half(t * (float)y[k]);
     }
-    if (g.C) stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), r);
+    if (g.C) store_grad(g, idx, r);
     if (g.aux8) {
       const v2h p0 = {r[0], r[1]}, p1 = {r[2], r[3]}, p2 = {r[4], r[5]}, p3 = {r[6], r[7]};
       v2i w;
@@ -192,7 +199,7 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
 #pragma unroll
       for (int k = 0; k < 8; ++k) r[k] = to_half(act_scaled(g.act, (float)y[k], g.epi_scale));
     }
-    if (g.aux16) stream_store(reinterpret_cast<v8h*>(g.aux16 + idx), r);
+    if (g.aux16) *reinterpret_cast<v8h*>(g.aux16 + idx) = r;   // read by the next matmul: a normal store
   } else {  // EPI_GELU_GRAD: y is the FP16-rounded matmul gradient
 #pragma unroll
     for (int k = 0; k < 8; ++k) r[k] = half_from_bits(0);
@@ -203,7 +210,7 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
 #pragma unroll
       for (int k = 0; k < 8; ++k) r[k] = to_half(act_grad_scaled(g.act, (float)z[k], (float)y[k], g.epi_scale));
     }
-    if (g.C) stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), r);      // optional: the FP8 copy may be all that is wanted
+    if (g.C) store_grad(g, idx, r);      // optional: the FP8 copy may be all that is wanted
   }
   if (g.aux8) {
     // FP8 copy of the FP16 value just stored: identical to casting the stored tensor afterwards

@@ -38,9 +38,11 @@ def test_c1_linear_fwd_bwd(fp8):
 
 
 @pytest.mark.parametrize("fp8", [False, True])
-@pytest.mark.parametrize("shape", [(16, 16, 16), (272, 144, 400), (48, 1040, 16), (528, 16, 272), (1040, 272, 528)])
+@pytest.mark.parametrize("shape", [(16, 16, 16), (272, 144, 400), (48, 1040, 16), (528, 16, 272), (1040, 272, 528),
+                                   (1040, 1152, 528), (528, 272, 1152)])
 def test_ragged_shapes(fp8, shape):
-    """Dimensions that are not multiples of any tile: several tiles plus a ragged tail in M, N and K."""
+    """Dimensions that are not multiples of any tile: several tiles plus a ragged tail in M, N and K.  The last two
+    have a long reduction over few output tiles (forward resp. grad_X): the wave-split small tile with ragged edges."""
     b, m, n = shape
     (X, W, G), gdt, odt = _operands(b, m, n, 101 + b, fp8)
     a, bx, bw = us.linear_scales(b, m, n)
