@@ -67,6 +67,10 @@ def _load():
     lib.uso_layer_norm_fwd.restype = None
     lib.uso_layer_norm_bwd.argtypes = [vp, vp, vp, vp, vp, vp, l, l, i, ctypes.c_double, f]
     lib.uso_layer_norm_bwd.restype = None
+    lib.uso_exponent_histogram.argtypes = [vp, i, sz, vp]
+    lib.uso_exponent_histogram.restype = None
+    lib.uso_cast_snr.argtypes = [vp, i, sz, i, f, vp]
+    lib.uso_cast_snr.restype = None
     lib.uso_act_fwd.argtypes = [vp, vp, sz, i, i, f, f]
     lib.uso_act_fwd.restype = None
     lib.uso_act_bwd.argtypes = [vp, vp, vp, sz, i, i, f, f]
@@ -402,3 +406,23 @@ def layer_norm_bwd(X, w, G, eps: float = 0.0, beta_wc=None):
     _load().uso_layer_norm_bwd(_p(X), _p(w), _p(G), _p(dX), _p(dw), _p(dc), b, n, _dt_of(X, None), float(eps),
                                float(np.float32(beta_wc)))
     return dX, dw, dc
+
+
+# ---- diagnostics: exponent histogram (Fig. 1, App. K) and SNR of a cast (Sec. 3.1) ---------------------
+HIST_BINS = 35
+
+
+def exponent_histogram(a: np.ndarray) -> np.ndarray:
+    """Counts per bin: 0 zero, 1 below 2^-24, 2 [2^-24, 2^-14), 3 + (e + 14) for exponent e = -14..15, 33 >= 2^16 / inf, 34 NaN."""
+    a = _c(a)
+    hist = np.zeros(HIST_BINS, np.uint64)
+    _load().uso_exponent_histogram(_p(a), _dt_of(a, None), a.size, _p(hist))
+    return hist
+
+
+def cast_snr(a: np.ndarray, dst_dt: int, scale: float = 1.0):
+    """(sum x^2, sum (q(x*scale)/scale - x)^2); their ratio is the SNR of Sec. 3.1."""
+    a = _c(a)
+    sums = np.zeros(2, np.float64)
+    _load().uso_cast_snr(_p(a), _dt_of(a, None), a.size, dst_dt, float(np.float32(scale)), _p(sums))
+    return float(sums[0]), float(sums[1])

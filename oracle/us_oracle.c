@@ -20,6 +20,8 @@
  *   layernorm Table A.2 "Other": layer_norm(X, w, c)_ij = c_j + w_j (X_ij - mu_i)/sigma_i with
  *             mu_i = mean_j X_ij, sigma_i = sqrt(mean_j X_ij^2 - mu_i^2); alpha = beta_x = 1,
  *             beta_w = beta_c = b^-1/2 (weights are cut-edges, activations are not: App. I.1).
+ *   diagnostics  Fig. 1 / App. K: histogram of exponent values on the FP16 grid (with the bins for zero,
+ *             subnormal and infinite values of App. K); Sec. 3.1: SNR = E[X^2] / E[(q(X) - X)^2] of a cast.
  *   residual  Sec. 5.3 "Weighted addition": the fixed(tau) interpolation sqrt(1-tau)*x + sqrt(tau)*f(x),
  *             with the residual branch's weight moved out of its backward pass (the id* rewrite of
  *             that section); Table A.2 "weighted_add" for the general scale rule.
@@ -411,6 +413,47 @@ void uso_layer_norm_bwd(const void* X, const void* w, const void* G, void* dX, v
   }
   free(aw);
   free(ac);
+}
+
+/*
+ * ---- diagnostics: exponent histogram and signal-to-noise ratio of a cast ---------------------------
+ * Histogram bins (35), by the magnitude of each value on the FP16 exponent grid of Fig. 1 / App. K:
+ *   0 zero | 1 non-zero below 2^-24 (lost in FP16) | 2 FP16-subnormal range [2^-24, 2^-14) |
+ *   3 + (e + 14) for 2^e <= |x| < 2^(e+1), e = -14 .. 15 | 33 |x| >= 2^16 or infinite | 34 NaN
+ * Counts are added to hist (the caller clears it).
+ * SNR: sums[0] += sum x^2, sums[1] += sum (q(x*scale)/scale - x)^2 with q the saturating cast of uso_cast_fp8
+ * (its product rounded to FP32 first, as there); NaN inputs are skipped.  Sec. 3.1 defines SNR as sums[0]/sums[1].
+ */
+void uso_exponent_histogram(const void* src, int dt, size_t n, unsigned long long* hist) {
+  for (size_t i = 0; i < n; ++i) {
+    double a = fabs(uso_decode_bits(load_bits(src, dt, i), dt));
+    int bin;
+    if (a != a) bin = 34;
+    else if (a == 0.0) bin = 0;
+    else if (a >= 65536.0) bin = 33;
+    else if (a < ldexp(1.0, -24)) bin = 1;
+    else if (a < ldexp(1.0, -14)) bin = 2;
+    else {
+      int e;
+      frexp(a, &e); /* a = f * 2^e, f in [0.5, 1): exponent of the leading bit is e - 1 */
+      bin = 3 + (e - 1 + 14);
+    }
+    hist[bin] += 1;
+  }
+}
+
+void uso_cast_snr(const void* src, int src_dt, size_t n, int dst_dt, float scale, double* sums) {
+  double s0 = 0.0, s1 = 0.0;
+  for (size_t i = 0; i < n; ++i) {
+    double x = uso_decode_bits(load_bits(src, src_dt, i), src_dt);
+    if (x != x) continue;
+    float p = (float)(x * (double)scale);
+    double q = uso_decode_bits(encode_f64((double)p, dst_dt, 1, NULL), dst_dt) / (double)scale;
+    s0 += x * x;
+    s1 += (q - x) * (q - x);
+  }
+  sums[0] += s0;
+  sums[1] += s1;
 }
 
 /*
