@@ -323,6 +323,14 @@ def main():
         ms = time_steps(torch, lambda: us.layer_norm_bwd(za.data_ptr(), lw.data_ptr(), zb.data_ptr(), zo.data_ptr(), ldw.data_ptr(),
                                                          ldc.data_ptr(), lb, ln, 1e-5, 0.0, lws.data_ptr(), lwsb, st), 50, 5)
         ew["layer_norm_bwd_GBps"] = round(6.0 * n / (ms * 1e-3) * 1e-9, 1)
+        # diagnostics: read-only, 2 B / element
+        hist = torch.zeros(us.HIST_BINS, dtype=torch.int64, device="cuda:0")
+        sums = torch.zeros(2, dtype=torch.float64, device="cuda:0")
+        ms = time_steps(torch, lambda: us.exponent_histogram(za.data_ptr(), us.F16, n, hist.data_ptr(), st), 50, 5)
+        ew["exponent_histogram_GBps"] = round(2.0 * n / (ms * 1e-3) * 1e-9, 1)
+        ms = time_steps(torch, lambda: us.cast_snr(za.data_ptr(), us.F16, n, us.E4M3, 1.0, sums.data_ptr(), st), 50, 5)
+        ew["cast_snr_GBps"] = round(2.0 * n / (ms * 1e-3) * 1e-9, 1)
+        ew["snr_e4m3_unit_normal"] = round(float(sums[0] / sums[1]), 1)
         ew["peak_GBps"] = PEAK_HBM_GBS
         out["elementwise"] = ew
         del za, zb, zo

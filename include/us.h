@@ -252,6 +252,23 @@ us_status us_layer_norm_bwd(const void* X, const void* w, const void* G, void* d
 size_t us_layer_norm_workspace_bytes(long b, long n);
 
 /*
+ * Diagnostics (device memory in and out; the results are ADDED to hist / sums, which the caller clears).
+ *
+ * us_exponent_histogram: where a tensor's values sit on the FP16 exponent grid (the histograms of Fig. 1 and
+ * App. K, with their extra bins).  src: F16 or F32, n elements; hist: US_HIST_BINS 64-bit counters:
+ *   0 zero | 1 non-zero below 2^-24 | 2 FP16-subnormal range [2^-24, 2^-14) | 3 + (e + 14) for
+ *   2^e <= |x| < 2^(e+1), e = -14 .. 15 | 33 |x| >= 2^16 or infinite | 34 NaN
+ *
+ * us_cast_snr: signal and noise of the scaled saturating cast of us_cast_fp8 (Sec. 3.1 "Quantisation error"):
+ *   sums[0] += sum x^2,  sums[1] += sum (q(x*scale)/scale - x)^2   (two doubles; NaN inputs skipped; scale > 0)
+ * SNR = sums[0] / sums[1].  The order of the additions is not fixed (floating-point atomics).
+ */
+#define US_HIST_BINS 35
+us_status us_exponent_histogram(const void* src, us_dtype src_dt, size_t n, unsigned long long* hist, void* stream);
+us_status us_cast_snr(const void* src, us_dtype src_dt, size_t n, us_dtype dst_dt, float scale, double* sums,
+                      void* stream);
+
+/*
  * Stand-alone weighted addition of two tensors (Table A.2 "weighted_add" with two inputs; Sec. 5.3):
  *   out[i] = round( ca * a[i] + cb * b[i] ),  dt = US_F16 or US_F32 for all three arrays; out may alias a or b.
  * The unit-scaling factor alpha = (ca^2 + cb^2)^-1/2 is the caller's to fold into ca, cb (it is 1 for the

@@ -16,6 +16,7 @@ ACT_GELU, ACT_RELU, ACT_TANH, ACT_SIGMOID = 0, 1, 2, 3
 EPI_TABLES_READY = 0x100            # flag for EPI_GELU / EPI_GELU_GRAD: tables prebuilt by gelu_tables()
 FFN_FP8, FFN_TABLES_READY = 1, 2    # mode bits of ffn_fwd / ffn_bwd
 TABLE_AREA_BYTES = 256 * 1024
+HIST_BINS = 35
 STATUS = {0: "US_OK", 1: "US_ERR_NULL", 2: "US_ERR_SHAPE", 3: "US_ERR_ALIGN", 4: "US_ERR_DTYPE",
           5: "US_ERR_WORKSPACE", 6: "US_ERR_LAUNCH", 7: "US_ERR_VALUE"}
 
@@ -58,6 +59,8 @@ def lib() -> ctypes.CDLL:
     L.us_layer_norm_bwd.argtypes = [vp, vp, vp, vp, vp, vp, l, l, f, f, vp, sz, vp]
     L.us_layer_norm_workspace_bytes.argtypes = [l, l]
     L.us_layer_norm_workspace_bytes.restype = sz
+    L.us_exponent_histogram.argtypes = [vp, i, sz, vp, vp]
+    L.us_cast_snr.argtypes = [vp, i, sz, i, f, vp, vp]
     L.us_act_fwd.argtypes = [vp, vp, sz, i, i, f, f, vp]
     L.us_act_bwd.argtypes = [vp, vp, vp, sz, i, i, f, f, vp]
     L.us_ffn_res_fwd.argtypes = [vp] * 7 + [l, l, l, f, i, vp, sz, vp]
@@ -70,7 +73,7 @@ def lib() -> ctypes.CDLL:
     L.us_ffn_workspace_bytes.argtypes = [l, l, l]
     L.us_ffn_workspace_bytes.restype = sz
     for name in ("us_linear_scales", "us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd",
-                 "us_gelu_tables", "us_ffn_fwd", "us_ffn_bwd", "us_weighted_add", "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd", "us_layer_norm_fwd", "us_layer_norm_bwd"):
+                 "us_gelu_tables", "us_ffn_fwd", "us_ffn_bwd", "us_weighted_add", "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd", "us_layer_norm_fwd", "us_layer_norm_bwd", "us_exponent_histogram", "us_cast_snr"):
         getattr(L, name).restype = i
     _lib = L
     return L
@@ -178,3 +181,13 @@ def layer_norm_bwd(X, w, G, dX, dw, dc, b, n, eps=0.0, beta_wc=0.0, workspace=No
 
 def layer_norm_workspace_bytes(b: int, n: int) -> int:
     return int(lib().us_layer_norm_workspace_bytes(b, n))
+
+
+def exponent_histogram(src, src_dt, n, hist, stream=None):
+    """hist: device pointer to HIST_BINS uint64 counters (added to)."""
+    _check(lib().us_exponent_histogram(src, src_dt, n, hist, stream), "us_exponent_histogram")
+
+
+def cast_snr(src, src_dt, n, dst_dt, scale, sums, stream=None):
+    """sums: device pointer to two float64 (added to): sum x^2 and sum (q(x*scale)/scale - x)^2."""
+    _check(lib().us_cast_snr(src, src_dt, n, dst_dt, scale, sums, stream), "us_cast_snr")

@@ -262,6 +262,25 @@ us_status us_layer_norm_bwd(const void* X, const void* w, const void* G, void* d
   return from_hip(launch_layer_norm_bwd(X, w, G, dX, dw, dc, b, n, eps, beta_wc, workspace, as_stream(stream)));
 }
 
+us_status us_exponent_histogram(const void* src, us_dtype src_dt, size_t n, unsigned long long* hist, void* stream) {
+  if (src_dt != US_F16 && src_dt != US_F32) return US_ERR_DTYPE;
+  if (!hist) return US_ERR_NULL;
+  if (n == 0) return US_OK;
+  if (!src) return US_ERR_NULL;
+  if (!aligned16(src) || (reinterpret_cast<uintptr_t>(hist) & 7u)) return US_ERR_ALIGN;
+  return from_hip(launch_exponent_histogram(src, src_dt, n, hist, as_stream(stream)));
+}
+
+us_status us_cast_snr(const void* src, us_dtype src_dt, size_t n, us_dtype dst_dt, float scale, double* sums, void* stream) {
+  if ((src_dt != US_F16 && src_dt != US_F32) || !is_fp8(dst_dt)) return US_ERR_DTYPE;
+  if (!(scale > 0.0f)) return US_ERR_VALUE;
+  if (!sums) return US_ERR_NULL;
+  if (n == 0) return US_OK;
+  if (!src) return US_ERR_NULL;
+  if (!aligned16(src) || (reinterpret_cast<uintptr_t>(sums) & 7u)) return US_ERR_ALIGN;
+  return from_hip(launch_cast_snr(src, src_dt, n, dst_dt, scale, sums, as_stream(stream)));
+}
+
 us_status us_weighted_add(const void* a, const void* b, void* out, size_t n, us_dtype dt, float ca, float cb, void* stream) {
   if (dt != US_F16 && dt != US_F32) return US_ERR_DTYPE;
   if (n == 0) return US_OK;

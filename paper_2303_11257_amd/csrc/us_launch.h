@@ -21,6 +21,8 @@ hipError_t launch_act(const void* z, const void* gh, void* out, size_t n, us_dty
 hipError_t launch_weighted_add(const void* a, const void* b, void* out, size_t n, us_dtype dt, float ca, float cb,
                                hipStream_t stream);
 
+hipError_t launch_exponent_histogram(const void* src, us_dtype dt, size_t n, unsigned long long* hist, hipStream_t stream);
+hipError_t launch_cast_snr(const void* src, us_dtype src_dt, size_t n, us_dtype dst_dt, float scale, double* sums, hipStream_t stream);
 size_t layer_norm_workspace_bytes(long b, long n);
 hipError_t launch_layer_norm_fwd(const void* X, const void* w, const void* c, void* Y, long b, long n, float eps, hipStream_t stream);
 hipError_t launch_layer_norm_bwd(const void* X, const void* w, const void* G, void* dX, void* dw, void* dc, long b, long n, float eps,

@@ -22,7 +22,7 @@ def test_every_declared_symbol_is_exported():
     assert {"us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd", "us_linear_scales",
             "us_workspace_bytes", "us_status_string", "us_ffn_fwd", "us_ffn_bwd", "us_gelu_tables", "us_weighted_add",
             "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd", "us_layer_norm_fwd", "us_layer_norm_bwd",
-            "us_layer_norm_workspace_bytes"} <= set(names)
+            "us_layer_norm_workspace_bytes", "us_exponent_histogram", "us_cast_snr"} <= set(names)
     L = ctypes.CDLL(us.library_path())
     for n in names:
         assert hasattr(L, n), n
@@ -85,6 +85,10 @@ def test_argument_errors_are_detected_on_the_host():
         (lambda: us.layer_norm_fwd(16, 16, None, 16, 4, 32), 1),
         (lambda: us.layer_norm_fwd(16, 16, 16, 16, 4, 32, -1.0), 7),
         (lambda: us.layer_norm_bwd(16, 16, 16, 16, 16, 16, 64, 32, 0.0, 0.0, 16, 100), 5),                   # workspace too small
+        (lambda: us.exponent_histogram(16, E4, 8, 64), 4),
+        (lambda: us.exponent_histogram(16, F16, 8, None), 1),
+        (lambda: us.cast_snr(16, F32, 8, E4, 0.0, 64), 7),                                                   # scale must be positive
+        (lambda: us.cast_snr(16, F32, 8, F16, 1.0, 64), 4),
         (lambda: us.weighted_add(16, None, 32, 8), 1),
         (lambda: us.weighted_add(16, 16, 32, 8, E4), 4),
         (lambda: us.ffn_res_fwd(16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 0.0, 0), 7),                          # tau must be in (0, 1]
