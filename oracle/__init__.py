@@ -55,6 +55,10 @@ def _load():
         fn = getattr(lib, name)
         fn.argtypes = [vp, i, vp, i, vp, i, l, l, l, f]
         fn.restype = i
+    lib.uso_linear_bias_fwd.argtypes = [vp, i, vp, i, vp, vp, i, l, l, l, f]
+    lib.uso_linear_bias_fwd.restype = i
+    lib.uso_bias_grad.argtypes = [vp, i, vp, i, l, l, f]
+    lib.uso_bias_grad.restype = None
     lib.uso_gelu_fwd.argtypes = [vp, vp, sz, i, f]
     lib.uso_gelu_fwd.restype = None
     lib.uso_gelu_bwd.argtypes = [vp, vp, vp, sz, i, f]
@@ -167,16 +171,38 @@ def _check(rc):
         raise MemoryError("oracle could not allocate its temporaries")
 
 
-def linear_fwd(X, W, alpha, x_dt=None, w_dt=None, out_dt=F16):
-    """Y[b,n] = round(alpha * X[b,m] W[m,n])."""
+def linear_fwd(X, W, alpha, x_dt=None, w_dt=None, out_dt=F16, bias=None):
+    """Y[b,n] = round(alpha * X[b,m] W[m,n] (+ bias[n], an FP16 row, App. J.1's ffn))."""
     X, W = _c(X), _c(W)
     b, m = X.shape
     m2, n = W.shape
     assert m == m2
     Y = np.empty((b, n), _NP[out_dt])
-    _check(_load().uso_linear_fwd(_p(X), _dt_of(X, x_dt), _p(W), _dt_of(W, w_dt), _p(Y), out_dt,
-                                  b, m, n, float(np.float32(alpha))))
+    if bias is None:
+        _check(_load().uso_linear_fwd(_p(X), _dt_of(X, x_dt), _p(W), _dt_of(W, w_dt), _p(Y), out_dt,
+                                      b, m, n, float(np.float32(alpha))))
+    else:
+        bias = _c(bias)
+        assert bias.dtype == np.float16 and bias.shape == (n,)
+        _check(_load().uso_linear_bias_fwd(_p(X), _dt_of(X, x_dt), _p(W), _dt_of(W, w_dt), _p(bias), _p(Y), out_dt,
+                                           b, m, n, float(np.float32(alpha))))
     return Y
+
+
+def bias_scale(b: int):
+    """beta for the gradient of a bias row summed over b rows: b^-1/2 (as layer norm's beta_c, Table A.2)."""
+    return np.float32(1.0 / math.sqrt(b))
+
+
+def bias_grad(G, beta_c=None, g_dt=None, out_dt=F16):
+    """dc[n] = round(beta_c * sum over the b rows of G[b,n])."""
+    G = _c(G)
+    b, n = G.shape
+    if beta_c is None:
+        beta_c = bias_scale(b)
+    dc = np.empty((n,), _NP[out_dt])
+    _load().uso_bias_grad(_p(G), _dt_of(G, g_dt), _p(dc), out_dt, b, n, float(np.float32(beta_c)))
+    return dc
 
 
 def linear_bwd_dx(G, W, beta_x, g_dt=None, w_dt=None, out_dt=F16):
@@ -238,10 +264,11 @@ def gelu_bwd(z, gh, beta_g):
 
 
 # ---- FFN chain: Linear -> unit-scaled GELU -> Linear, forward and backward -----------------------
-def ffn_fwd(X16, W1_16, W2_16, fp8: bool, alpha_g=None):
+def ffn_fwd(X16, W1_16, W2_16, fp8: bool, alpha_g=None, b1=None, b2=None):
     """Stage-by-stage forward pass with every stored intermediate kept (all roundings included).
 
-    FP8 mode quantises only the matmul inputs (X, W1, H, W2 -> E4M3); Z, H, Y stay FP16.
+    FP8 mode quantises only the matmul inputs (X, W1, H, W2 -> E4M3); Z, H, Y stay FP16.  b1[f], b2[d]: optional
+    FP16 bias rows (App. J.1: W2 act(W1 z + b1) + b2); they are not matmul inputs and stay FP16.
     """
     if alpha_g is None:
         alpha_g = gelu_scales()[0]
@@ -254,19 +281,21 @@ def ffn_fwd(X16, W1_16, W2_16, fp8: bool, alpha_g=None):
         r["X8"], _ = cast_fp8(X16, E4M3)
         r["W1_8"], _ = cast_fp8(W1_16, E4M3)
         r["W2_8"], _ = cast_fp8(W2_16, E4M3)
-        r["Z"] = linear_fwd(r["X8"], r["W1_8"], a1, E4M3, E4M3)
+        r["Z"] = linear_fwd(r["X8"], r["W1_8"], a1, E4M3, E4M3, bias=b1)
         r["H"] = gelu_fwd(r["Z"], alpha_g)
         r["H8"], _ = cast_fp8(r["H"], E4M3)
-        r["Y"] = linear_fwd(r["H8"], r["W2_8"], a2, E4M3, E4M3)
+        r["Y"] = linear_fwd(r["H8"], r["W2_8"], a2, E4M3, E4M3, bias=b2)
     else:
-        r["Z"] = linear_fwd(X16, W1_16, a1)
+        r["Z"] = linear_fwd(X16, W1_16, a1, bias=b1)
         r["H"] = gelu_fwd(r["Z"], alpha_g)
-        r["Y"] = linear_fwd(r["H"], W2_16, a2)
+        r["Y"] = linear_fwd(r["H"], W2_16, a2, bias=b2)
     return r
 
 
-def ffn_bwd(X16, W1_16, W2_16, G16, fwd: dict, fp8: bool, beta_g=None):
-    """Backward pass given the forward intermediates; gradients are E5M2 matmul inputs in FP8 mode."""
+def ffn_bwd(X16, W1_16, W2_16, G16, fwd: dict, fp8: bool, beta_g=None, with_bias=False):
+    """Backward pass given the forward intermediates; gradients are E5M2 matmul inputs in FP8 mode.  with_bias:
+    also db2 = beta * column sums of G and db1 = beta * column sums of dZ, both from the FP16 gradients (the FP8
+    copies exist for the matmuls only, App. J.2)."""
     if beta_g is None:
         beta_g = gelu_scales()[1]
     T, d = X16.shape
@@ -288,6 +317,9 @@ def ffn_bwd(X16, W1_16, W2_16, G16, fwd: dict, fp8: bool, beta_g=None):
         r["dZ"] = gelu_bwd(fwd["Z"], r["dH"], beta_g)
         r["dX"] = linear_bwd_dx(r["dZ"], W1_16, bx1)
         r["dW1"] = linear_bwd_dw(X16, r["dZ"], bw1)
+    if with_bias:
+        r["db2"] = bias_grad(G16, bias_scale(T))
+        r["db1"] = bias_grad(r["dZ"], bias_scale(T))
     return r
 
 

@@ -215,11 +215,17 @@ static double* decode_all(const void* src, int dt, size_t n) {
   return d;
 }
 
-int uso_linear_fwd(const void* X, int x_dt, const void* W, int w_dt, void* Y, int y_dt,
-                   long b, long m, long n, float alpha) {
+/* Forward product with an optional bias row c[n] (FP16 storage; NULL = none): the FFN of App. J.1 is
+ * W2 act(W1 z + b1) + b2.  Reading (the paper gives the bias no scale of its own): biases start at zero
+ * ("non-bias parameters" are the ones drawn with unit variance, Sec. 5.2 recipe), so adding them leaves the
+ * unit-variance output as it is and the forward pass needs no factor; the bias joins the scaled sum before the
+ * single rounding:  Y[i,j] = round_out( alpha * sum_k X[i,k] W[k,j] + c[j] ). */
+static int linear_fwd_impl(const void* X, int x_dt, const void* W, int w_dt, const void* c, void* Y, int y_dt,
+                           long b, long m, long n, float alpha) {
   double* Xd = decode_all(X, x_dt, (size_t)b * m);
   double* Wd = decode_all(W, w_dt, (size_t)m * n);
-  if (!Xd || !Wd) { free(Xd); free(Wd); return 1; }
+  double* cd = c ? decode_all(c, ODT_F16, (size_t)n) : NULL;
+  if (!Xd || !Wd || (c && !cd)) { free(Xd); free(Wd); free(cd); return 1; }
 #pragma omp parallel
   {
     double* acc = (double*)malloc((size_t)n * sizeof(double)); /* one output row of running sums */
@@ -231,12 +237,33 @@ int uso_linear_fwd(const void* X, int x_dt, const void* W, int w_dt, void* Y, in
         for (long j = 0; j < n; ++j) acc[j] += x * Wd[k * n + j];
       }
       for (long j = 0; j < n; ++j)
-        store_bits(Y, y_dt, (size_t)(i * n + j), round_out((double)alpha * acc[j], y_dt));
+        store_bits(Y, y_dt, (size_t)(i * n + j), round_out((double)alpha * acc[j] + (cd ? cd[j] : 0.0), y_dt));
     }
     free(acc);
   }
-  free(Xd); free(Wd);
+  free(Xd); free(Wd); free(cd);
   return 0;
+}
+
+int uso_linear_fwd(const void* X, int x_dt, const void* W, int w_dt, void* Y, int y_dt,
+                   long b, long m, long n, float alpha) {
+  return linear_fwd_impl(X, x_dt, W, w_dt, NULL, Y, y_dt, b, m, n, alpha);
+}
+
+int uso_linear_bias_fwd(const void* X, int x_dt, const void* W, int w_dt, const void* c, void* Y, int y_dt,
+                        long b, long m, long n, float alpha) {
+  return linear_fwd_impl(X, x_dt, W, w_dt, c, Y, y_dt, b, m, n, alpha);
+}
+
+/* Gradient of a bias row: dc[j] = round_out( beta_c * sum_{i<b} G[i,j] ), rows in index order, double sum.
+ * Reading: the sum runs over the b rows (tokens) like the one in grad_W, and like the bias c of the scaled
+ * layer norm (Table A.2 "Other": beta_c = b^-1/2) it gets b^-1/2; the factor is an argument. */
+void uso_bias_grad(const void* G, int g_dt, void* dc, int o_dt, long b, long n, float beta_c) {
+  double* acc = (double*)calloc((size_t)n, sizeof(double));
+  for (long i = 0; i < b; ++i)
+    for (long j = 0; j < n; ++j) acc[j] += uso_decode_bits(load_bits(G, g_dt, (size_t)(i * n + j)), g_dt);
+  for (long j = 0; j < n; ++j) store_bits(dc, o_dt, (size_t)j, round_out((double)beta_c * acc[j], o_dt));
+  free(acc);
 }
 
 int uso_linear_bwd_dx(const void* G, int g_dt, const void* W, int w_dt, void* dX, int o_dt,
