@@ -52,7 +52,7 @@ class Ffn:
         # (they are all the layer-1 backward matmuls read)
         self.dZ16 = None if fp8 else e((T, f))
         self.dZ8 = e((T, f), u8) if fp8 else None
-        self.wsb = us.ffn_workspace_bytes(T, d, f)
+        self.wsb = max(us.ffn_workspace_bytes(T, d, f), us.ffn_bias_workspace_bytes(T, d, f))
         self.ws = torch.empty(max(self.wsb, 16), dtype=u8, device=dev)
         # the GELU tables depend on the two scale factors only: built once here, like the workspace itself
         us.gelu_tables(self.ws.data_ptr(), self.wsb, 0.0, 0.0, torch.cuda.current_stream().cuda_stream)
@@ -124,6 +124,28 @@ class Ffn:
         us.ffn_res_fwd(p(self.X), p(X), p(W1), p(W2), p(self.Z), p(self.H), p(self.Y), T, d, f, tau, self.mode, p(self.ws), self.wsb, st)
         us.ffn_res_bwd(p(X), p(W1), p(W2), p(self.Z), p(self.H), p(self.G), p(G), p(self.dZ16), p(self.dZ8), p(self.dX), p(self.dW1),
                        p(self.dW2), T, d, f, tau, self.mode, p(self.ws), self.wsb, st)
+
+
+    def step_bias(self):
+        """The same step for the FFN with bias rows, W2 gelu(W1 x + b1) + b2: biases fused into the two forward epilogues,
+        their gradients as column sums of G and of the FP16 dZ (which the FP8 step then has to store): a side measurement."""
+        us, p, st, torch = self.us, self.p, self.torch.cuda.current_stream().cuda_stream, self.torch
+        T, d, f = self.T, self.d, self.f
+        if not hasattr(self, "b1"):
+            self.b1, self.b2 = torch.zeros(f, dtype=torch.float16, device="cuda:0"), torch.zeros(d, dtype=torch.float16, device="cuda:0")
+            self.db1, self.db2 = torch.empty_like(self.b1), torch.empty_like(self.b2)
+            self.dZ16b = self.dZ16 if self.dZ16 is not None else torch.empty((T, f), dtype=torch.float16, device="cuda:0")
+        if self.fp8:
+            us.cast_fp8_batch([p(self.X), p(self.W1), p(self.W2), p(self.G)], [p(self.X8), p(self.W1_8), p(self.W2_8), p(self.G8)],
+                              [self.X.numel(), self.W1.numel(), self.W2.numel(), self.G.numel()],
+                              [us.E4M3, us.E4M3, us.E4M3, us.E5M2], st)
+            X, W1, W2, G = self.X8, self.W1_8, self.W2_8, self.G8
+        else:
+            X, W1, W2, G = self.X, self.W1, self.W2, self.G
+        us.ffn_bias_fwd(p(X), p(W1), p(self.b1), p(W2), p(self.b2), p(self.Z), p(self.H), p(self.Y), T, d, f, self.mode, p(self.ws),
+                        self.wsb, st)
+        us.ffn_bias_bwd(p(X), p(W1), p(W2), p(self.Z), p(self.H), p(G), p(self.G), p(self.dZ16b), p(self.dZ8), p(self.dX), p(self.dW1),
+                        p(self.dW2), p(self.db1), p(self.db2), T, d, f, self.mode, p(self.ws), self.wsb, st)
 
 
 def ramp_up(torch, fn, seconds=0.15):
@@ -300,6 +322,10 @@ def main():
         out["residual_layer"] = {"what": "same workload with the fixed(tau=0.5) residual interpolation fused into the step "
                                          "(forward output and grad_X read one more FP16 [tokens, d_model] tensor each)",
                                  "ms_per_step": ms_res, "TFLOPs": ffn.flop / (ms_res * 1e-3) * 1e-12}
+        ms_b = time_steps(torch, ffn.step_bias, args.steps, args.warmup)
+        out["ffn_with_biases"] = {"what": "same workload with bias rows b1, b2 (added in the forward epilogues) and their gradients "
+                                          "(column sums of G and of the FP16 dZ, which is then stored as well)",
+                                  "ms_per_step": ms_b, "TFLOPs": ffn.flop / (ms_b * 1e-3) * 1e-12}
     if not args.no_secondary:
         # stand-alone elementwise kernels (HBM bound): 32 Mi FP16 elements, algorithmic bytes 4 B (forward) / 6 B (backward) / 6 B (add)
         n = 32 << 20
@@ -323,6 +349,10 @@ def main():
         ms = time_steps(torch, lambda: us.layer_norm_bwd(za.data_ptr(), lw.data_ptr(), zb.data_ptr(), zo.data_ptr(), ldw.data_ptr(),
                                                          ldc.data_ptr(), lb, ln, 1e-5, 0.0, lws.data_ptr(), lwsb, st), 50, 5)
         ew["layer_norm_bwd_GBps"] = round(6.0 * n / (ms * 1e-3) * 1e-9, 1)
+        bwsb = us.bias_grad_workspace_bytes(lb, ln)
+        bws = torch.empty(bwsb, dtype=torch.uint8, device="cuda:0")
+        ms = time_steps(torch, lambda: us.bias_grad(za.data_ptr(), us.F16, ldc.data_ptr(), lb, ln, 0.0, bws.data_ptr(), bwsb, st), 50, 5)
+        ew["bias_grad_GBps"] = round(2.0 * n / (ms * 1e-3) * 1e-9, 1)
         # diagnostics: read-only, 2 B / element
         hist = torch.zeros(us.HIST_BINS, dtype=torch.int64, device="cuda:0")
         sums = torch.zeros(2, dtype=torch.float64, device="cuda:0")

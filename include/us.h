@@ -294,6 +294,41 @@ us_status us_ffn_res_bwd(const void* X, const void* W1, const void* W2, const vo
                          void* dW2, long T, long d, long f, float tau, int mode, void* workspace,
                          size_t workspace_bytes, void* stream);
 
+/*
+ * Bias rows (App. J.1: ffn(z) = W2 act(W1 z + b1) + b2).  The paper gives the bias no factor of its own: biases
+ * start at zero (only non-bias parameters are drawn with unit variance, Sec. 5.2), so the forward pass adds them
+ * unscaled, inside the single rounding of the output, and the gradient, a sum over the b rows, gets b^-1/2 like
+ * the bias of the scaled layer norm (Table A.2 "Other").
+ *
+ * us_linear_bias_fwd: us_linear_fwd with  Y = round( alpha * X W + bias ), the epilogue (GELU, residual) then acts on
+ *   that Y.  bias: device, FP16 [n], 16-byte aligned, or NULL (then exactly us_linear_fwd).  y_dt must be US_F16
+ *   when a bias is given (US_ERR_DTYPE otherwise).
+ * us_bias_grad:  dc[j] = fp16( beta_c * sum_i G[i,j] ),  G [b,n] of g_dt = US_F16, US_E4M3 or US_E5M2; dc FP16 [n];
+ *   n a multiple of 16 (b is free); beta_c <= 0 selects b^-1/2.  FP32 sums in a fixed order (reproducible).
+ *   workspace: us_bias_grad_workspace_bytes(b, n) bytes of scratch, 16-byte aligned (US_ERR_WORKSPACE if smaller).
+ * us_ffn_bias_fwd / us_ffn_bias_bwd: us_ffn_fwd / us_ffn_bwd with b1 [f], b2 [d] (either may be NULL) and their
+ *   gradients db1 [f], db2 [d] (FP16 out, either may be NULL).  The bias gradients are sums of the FP16 gradients
+ *   (FP8 copies exist for the matmuls only, App. J.2): db2 reads G16, the FP16 incoming gradient [T,d] (G is
+ *   the matmul operand: the same tensor without US_FFN_FP8, its E5M2 cast with it), and db1 reads dZ16, which
+ *   must then be stored (US_ERR_NULL if db1 is asked for without dZ16, or db2 without G16).
+ *   workspace: us_ffn_bias_workspace_bytes(T, d, f).
+ */
+us_status us_linear_bias_fwd(const void* X, const void* W, const void* bias, void* Y, long b, long m, long n,
+                             us_dtype x_dt, us_dtype w_dt, us_dtype y_dt, float alpha, us_epilogue epi,
+                             float epi_scale, void* aux16, void* aux8, void* workspace, size_t workspace_bytes,
+                             void* stream);
+us_status us_bias_grad(const void* G, us_dtype g_dt, void* dc, long b, long n, float beta_c, void* workspace,
+                       size_t workspace_bytes, void* stream);
+size_t us_bias_grad_workspace_bytes(long b, long n);
+us_status us_ffn_bias_fwd(const void* X, const void* W1, const void* b1, const void* W2, const void* b2, void* Z,
+                          void* H, void* Y, long T, long d, long f, int mode, void* workspace,
+                          size_t workspace_bytes, void* stream);
+us_status us_ffn_bias_bwd(const void* X, const void* W1, const void* W2, const void* Z, const void* H,
+                          const void* G, const void* G16, void* dZ16, void* dZ8, void* dX, void* dW1, void* dW2,
+                          void* db1, void* db2, long T, long d, long f, int mode, void* workspace,
+                          size_t workspace_bytes, void* stream);
+size_t us_ffn_bias_workspace_bytes(long T, long d, long f);
+
 #ifdef __cplusplus
 }
 #endif

@@ -72,8 +72,17 @@ def lib() -> ctypes.CDLL:
     L.us_ffn_bwd.argtypes = [vp] * 11 + [l, l, l, i, vp, sz, vp]
     L.us_ffn_workspace_bytes.argtypes = [l, l, l]
     L.us_ffn_workspace_bytes.restype = sz
+    L.us_linear_bias_fwd.argtypes = [vp, vp, vp, vp, l, l, l, i, i, i, f, i, f, vp, vp, vp, sz, vp]
+    L.us_bias_grad.argtypes = [vp, i, vp, l, l, f, vp, sz, vp]
+    L.us_bias_grad_workspace_bytes.argtypes = [l, l]
+    L.us_bias_grad_workspace_bytes.restype = sz
+    L.us_ffn_bias_fwd.argtypes = [vp] * 8 + [l, l, l, i, vp, sz, vp]
+    L.us_ffn_bias_bwd.argtypes = [vp] * 14 + [l, l, l, i, vp, sz, vp]
+    L.us_ffn_bias_workspace_bytes.argtypes = [l, l, l]
+    L.us_ffn_bias_workspace_bytes.restype = sz
     for name in ("us_linear_scales", "us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd",
-                 "us_gelu_tables", "us_ffn_fwd", "us_ffn_bwd", "us_weighted_add", "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd", "us_layer_norm_fwd", "us_layer_norm_bwd", "us_exponent_histogram", "us_cast_snr"):
+                 "us_gelu_tables", "us_ffn_fwd", "us_ffn_bwd", "us_weighted_add", "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd", "us_layer_norm_fwd", "us_layer_norm_bwd", "us_exponent_histogram", "us_cast_snr",
+                 "us_linear_bias_fwd", "us_bias_grad", "us_ffn_bias_fwd", "us_ffn_bias_bwd"):
         getattr(L, name).restype = i
     _lib = L
     return L
@@ -161,6 +170,35 @@ def ffn_res_bwd(X, W1, W2, Z, H, Gskip, G, dZ16, dZ8, dXin, dW1, dW2, T, d, f, t
                 stream=None):
     _check(lib().us_ffn_res_bwd(X, W1, W2, Z, H, Gskip, G, dZ16, dZ8, dXin, dW1, dW2, T, d, f, tau, int(mode), workspace,
                                 workspace_bytes, stream), "us_ffn_res_bwd")
+
+
+def linear_bias_fwd(X, W, bias, Y, b, m, n, x_dt, w_dt, y_dt=F16, alpha=0.0, epi=EPI_NONE, epi_scale=0.0, aux16=None, aux8=None,
+                    workspace=None, workspace_bytes=0, stream=None):
+    _check(lib().us_linear_bias_fwd(X, W, bias, Y, b, m, n, x_dt, w_dt, y_dt, alpha, epi, epi_scale, aux16, aux8, workspace,
+                                    workspace_bytes, stream), "us_linear_bias_fwd")
+
+
+def bias_grad(G, g_dt, dc, b, n, beta_c=0.0, workspace=None, workspace_bytes=0, stream=None):
+    _check(lib().us_bias_grad(G, g_dt, dc, b, n, beta_c, workspace, workspace_bytes, stream), "us_bias_grad")
+
+
+def bias_grad_workspace_bytes(b: int, n: int) -> int:
+    return int(lib().us_bias_grad_workspace_bytes(b, n))
+
+
+def ffn_bias_fwd(X, W1, b1, W2, b2, Z, H, Y, T, d, f, mode, workspace=None, workspace_bytes=0, stream=None):
+    _check(lib().us_ffn_bias_fwd(X, W1, b1, W2, b2, Z, H, Y, T, d, f, int(mode), workspace, workspace_bytes, stream),
+           "us_ffn_bias_fwd")
+
+
+def ffn_bias_bwd(X, W1, W2, Z, H, G, G16, dZ16, dZ8, dX, dW1, dW2, db1, db2, T, d, f, mode, workspace=None, workspace_bytes=0,
+                 stream=None):
+    _check(lib().us_ffn_bias_bwd(X, W1, W2, Z, H, G, G16, dZ16, dZ8, dX, dW1, dW2, db1, db2, T, d, f, int(mode), workspace,
+                                 workspace_bytes, stream), "us_ffn_bias_bwd")
+
+
+def ffn_bias_workspace_bytes(T: int, d: int, f: int) -> int:
+    return int(lib().us_ffn_bias_workspace_bytes(T, d, f))
 
 
 def act_fwd(z, h, n, dt=F16, kind=ACT_GELU, s1=0.0, scale=0.0, stream=None):

@@ -112,6 +112,13 @@ size_t us_workspace_bytes(long b, long m, long n) {
 us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, long n, us_dtype x_dt, us_dtype w_dt,
                         us_dtype y_dt, float alpha, us_epilogue epi, float epi_scale, void* aux16, void* aux8,
                         void* workspace, size_t workspace_bytes, void* stream) {
+  return us_linear_bias_fwd(X, W, nullptr, Y, b, m, n, x_dt, w_dt, y_dt, alpha, epi, epi_scale, aux16, aux8, workspace,
+                            workspace_bytes, stream);
+}
+
+us_status us_linear_bias_fwd(const void* X, const void* W, const void* bias, void* Y, long b, long m, long n, us_dtype x_dt,
+                             us_dtype w_dt, us_dtype y_dt, float alpha, us_epilogue epi, float epi_scale, void* aux16,
+                             void* aux8, void* workspace, size_t workspace_bytes, void* stream) {
   const bool tables_ready = ((int)epi & US_EPI_TABLES_READY) != 0;
   const int act = ((int)epi >> 4) & 0xf;
   epi = (us_epilogue)((int)epi & 0xf);
@@ -122,15 +129,18 @@ us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, l
   if (y_dt != US_F16 && y_dt != US_F32) return US_ERR_DTYPE;
   if (epi != US_EPI_NONE && epi != US_EPI_GELU && epi != US_EPI_RESIDUAL) return US_ERR_DTYPE;
   if (epi != US_EPI_NONE && y_dt != US_F16) return US_ERR_DTYPE;
+  if (bias && y_dt != US_F16) return US_ERR_DTYPE;       // the bias joins the sum before the rounding to FP16
   if (epi == US_EPI_RESIDUAL && !residual_weight_ok(epi_scale)) return US_ERR_VALUE;
   if (b < 0 || m < 0 || n < 0 || !mult16(b) || !mult16(m) || !mult16(n)) return US_ERR_SHAPE;
   if (b == 0 || n == 0) return US_OK;
   if (!Y || (m > 0 && (!X || !W))) return US_ERR_NULL;
   if (epi == US_EPI_GELU && !aux16 && !aux8) return US_ERR_NULL;
   if (epi == US_EPI_RESIDUAL && !aux16) return US_ERR_NULL;
-  if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || !aligned16(aux16) || !aligned16(aux8) || !aligned16(workspace))
+  if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || !aligned16(aux16) || !aligned16(aux8) || !aligned16(workspace) ||
+      !aligned16(bias))
     return US_ERR_ALIGN;
   GemmProblem p{};
+  p.bias = bias;
   p.A = X; p.B = W; p.C = Y;
   p.M = b; p.N = n; p.K = m;
   p.lda = m; p.ldb = n; p.ldc = n;
@@ -331,15 +341,20 @@ size_t us_ffn_workspace_bytes(long T, long d, long f) {
 
 us_status us_ffn_fwd(const void* X, const void* W1, const void* W2, void* Z, void* H, void* Y, long T, long d, long f,
                      int mode, void* workspace, size_t workspace_bytes, void* stream) {
+  return us_ffn_bias_fwd(X, W1, nullptr, W2, nullptr, Z, H, Y, T, d, f, mode, workspace, workspace_bytes, stream);
+}
+
+us_status us_ffn_bias_fwd(const void* X, const void* W1, const void* b1, const void* W2, const void* b2, void* Z, void* H,
+                          void* Y, long T, long d, long f, int mode, void* workspace, size_t workspace_bytes, void* stream) {
   const bool fp8 = (mode & US_FFN_FP8) != 0;
   const int ready = (mode & US_FFN_TABLES_READY) ? US_EPI_TABLES_READY : 0;
   const us_dtype op = fp8 ? US_E4M3 : US_F16;
   // layer 1 with the GELU fused: Z = d^-1/2 X W1 (FP16), H = 1.7009 gelu(Z) as FP16 or as E4M3 codes
-  us_status s = us_linear_fwd(X, W1, Z, T, d, f, op, op, US_F16, 0.0f, (us_epilogue)(US_EPI_GELU | ready), 0.0f, fp8 ? nullptr : H,
-                              fp8 ? H : nullptr, workspace, workspace_bytes, stream);
+  us_status s = us_linear_bias_fwd(X, W1, b1, Z, T, d, f, op, op, US_F16, 0.0f, (us_epilogue)(US_EPI_GELU | ready), 0.0f,
+                                   fp8 ? nullptr : H, fp8 ? H : nullptr, workspace, workspace_bytes, stream);
   if (s != US_OK) return s;
-  // layer 2: Y = f^-1/2 H W2
-  return us_linear_fwd(H, W2, Y, T, f, d, op, op, US_F16, 0.0f, US_EPI_NONE, 0.0f, nullptr, nullptr, nullptr, 0, stream);
+  // layer 2: Y = f^-1/2 H W2 (+ b2)
+  return us_linear_bias_fwd(H, W2, b2, Y, T, f, d, op, op, US_F16, 0.0f, US_EPI_NONE, 0.0f, nullptr, nullptr, nullptr, 0, stream);
 }
 
 us_status us_ffn_bwd(const void* X, const void* W1, const void* W2, const void* Z, const void* H, const void* G,
@@ -359,6 +374,48 @@ us_status us_ffn_bwd(const void* X, const void* W1, const void* W2, const void* 
   const void* dZ = fp8 ? dZ8 : dZ16;
   return us_linear_bwd(X, W1, dZ, dX, dW1, T, d, f, op, op, gr, US_F16, 0.0f, 0.0f, US_EPI_NONE, 0.0f, nullptr, nullptr,
                        workspace, workspace_bytes, stream);
+}
+
+us_status us_bias_grad(const void* G, us_dtype g_dt, void* dc, long b, long n, float beta_c, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  if (g_dt != US_F16 && g_dt != US_E4M3 && g_dt != US_E5M2) return US_ERR_DTYPE;
+  if (b < 0 || n < 0 || !mult16(n)) return US_ERR_SHAPE;
+  if (n == 0) return US_OK;
+  if (!dc || (b > 0 && !G)) return US_ERR_NULL;
+  if (!aligned16(G) || !aligned16(dc) || !aligned16(workspace)) return US_ERR_ALIGN;
+  if (b > 0 && (!workspace || workspace_bytes < bias_grad_workspace_bytes(b, n))) return US_ERR_WORKSPACE;
+  const float beta = (beta_c > 0.0f) ? beta_c : (float)(1.0 / sqrt((double)(b > 0 ? b : 1)));
+  return from_hip(launch_bias_grad(G, g_dt, dc, b, n, beta, workspace, as_stream(stream)));
+}
+
+size_t us_bias_grad_workspace_bytes(long b, long n) { return bias_grad_workspace_bytes(b, n); }
+
+us_status us_ffn_bias_bwd(const void* X, const void* W1, const void* W2, const void* Z, const void* H, const void* G,
+                          const void* G16, void* dZ16, void* dZ8, void* dX, void* dW1, void* dW2, void* db1, void* db2,
+                          long T, long d, long f, int mode, void* workspace, size_t workspace_bytes, void* stream) {
+  // the bias gradients are sums of the FP16 gradients (the FP8 copies feed the matmuls only): db1 needs dZ16 stored
+  if ((db1 && !dZ16) || (db2 && !G16)) return US_ERR_NULL;
+  if (db1 || db2) {
+    const size_t need = (size_t)kTableAreaBytes + bias_grad_workspace_bytes(T, f > d ? f : d);
+    if (!workspace || workspace_bytes < need) return US_ERR_WORKSPACE;
+  }
+  us_status s = us_ffn_bwd(X, W1, W2, Z, H, G, dZ16, dZ8, dX, dW1, dW2, T, d, f, mode, workspace, workspace_bytes, stream);
+  if (s != US_OK) return s;
+  // the column sums run after the matmuls on the same stream and reuse the area behind the tables
+  char* scratch = (char*)workspace + kTableAreaBytes;
+  const size_t scratch_bytes = workspace_bytes - (size_t)kTableAreaBytes;
+  if (db2) {
+    s = us_bias_grad(G16, US_F16, db2, T, d, 0.0f, scratch, scratch_bytes, stream);
+    if (s != US_OK) return s;
+  }
+  if (db1) s = us_bias_grad(dZ16, US_F16, db1, T, f, 0.0f, scratch, scratch_bytes, stream);
+  return s;
+}
+
+size_t us_ffn_bias_workspace_bytes(long T, long d, long f) {
+  const size_t a = us_ffn_workspace_bytes(T, d, f);
+  const size_t b = (size_t)kTableAreaBytes + bias_grad_workspace_bytes(T, f > d ? f : d);
+  return a > b ? a : b;
 }
 
 }  // extern "C"

@@ -34,6 +34,7 @@ struct GemmArgs {
   uint8_t* aux8;         // optional FP8 copy of the epilogue's FP16 result
   float* partial;        // EPI_PARTIAL: [splits][M][N] FP32
   const uint8_t* table;  // EPI_*_TAB: the table in global memory (us_device.h)
+  const _Float16* bias;  // forward product only: optional row [N] added to scale * acc before the rounding, or NULL
   int xcd_gm, xcd_gn;    // XCD rectangle split of the tile grid (0,0 = one rectangle)
   int grp_w;             // width of the column bands the rectangle is walked in
 };
@@ -241,7 +242,15 @@ struct EpiStrip {
 // Must be entered after a workgroup barrier (the strips overlay the operand tiles).  A wave works on
 // the 32-row blocks I0 .. I1-1 of its accumulators (all of them unless two wave groups share a tile:
 // then each group finishes one half of the rows, see the wave-split reduction of the direct kernel).
-template <class Cfg, int EPI, bool WIDE, int I0 = 0, int I1 = Cfg::FM>
+// BIAS: the kernel is a forward product with an FP16 result and may be given a bias row (GemmArgs::bias); the
+// other kernels do not carry the code.
+template <bool A_KC, bool B_KC, int EPI, bool WIDE>
+constexpr bool epilogue_takes_bias() {
+  return A_KC && !B_KC && !WIDE &&
+         (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_GELU_TAB || EPI == EPI_GELU_TAB16 || EPI == EPI_RESIDUAL);
+}
+
+template <class Cfg, int EPI, bool WIDE, int I0 = 0, int I1 = Cfg::FM, bool BIAS = false>
 __device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&acc)[Cfg::FM][Cfg::FN], uint8_t* lds,
                                                      long m0, long n0, long split) {
   static_assert(WIDE ? (EPI == EPI_STORE || EPI == EPI_PARTIAL) : (EPI != EPI_PARTIAL), "");
@@ -249,6 +258,24 @@ __device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&a
   constexpr int AUX_FMT = (EPI == EPI_GELU_GRAD || EPI == EPI_GELU_GRAD_TAB) ? US_E5M2 : US_E4M3;
   const uint8_t* lut = lds + S::STRIP_BYTES;
   static_assert(S::TABLE_BYTES == 0 || Cfg::WAVES_K == 1, "the table copy below meets all waves at a barrier");
+  // Bias row: register 4q+e of accumulator block j belongs to column j*32 + 8q + 4(lane/32) + e of the wave's
+  // tile, so a lane needs four consecutive bias values per (j, q).  Requested first, so that the table copy
+  // below (where there is one) is in flight at the same time.
+  [[maybe_unused]] v4h bias4[BIAS ? Cfg::FN : 1][4] = {};
+  [[maybe_unused]] bool has_bias = false;
+  if constexpr (BIAS) {
+    has_bias = g.bias != nullptr;
+    if (has_bias) {
+      const long nb0 = n0 + ((threadIdx.x >> 6) % Cfg::WAVES_MN / Cfg::WAVES_M) * Cfg::WN + 4 * ((threadIdx.x & 63) >> 5);
+#pragma unroll
+      for (int j = 0; j < Cfg::FN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const long n = nb0 + j * 32 + 8 * q;
+          if (n < g.N) bias4[j][q] = *reinterpret_cast<const v4h*>(g.bias + n);
+        }
+    }
+  }
   if constexpr (S::TABLE_BYTES > 0) {
     // copy the table into LDS: whole 1 KB wave loads, 16 bytes per lane, spread over the waves
     for (int c = threadIdx.x >> 6; c < S::TABLE_BYTES / 1024; c += Cfg::WAVES)
@@ -296,22 +323,36 @@ __device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&a
   fetch_group(0);
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
+    auto to_strip = [&](auto with_bias) {
 #pragma unroll
-    for (int j = 0; j < Cfg::FN; ++j) {
+      for (int j = 0; j < Cfg::FN; ++j) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int col = j * 32 + 8 * q + 4 * (lane >> 5);
-        const float v0 = acc[I0 + i][j][4 * q] * scale, v1 = acc[I0 + i][j][4 * q + 1] * scale;
-        const float v2 = acc[I0 + i][j][4 * q + 2] * scale, v3 = acc[I0 + i][j][4 * q + 3] * scale;
-        uint8_t* p = strip + (lane & 31) * EP + col * S::ES;
-        if (WIDE) {
-          v4f o = {v0, v1, v2, v3};
-          *US_LDS_PTR(v4f, p) = o;
-        } else {
-          v4h o = {to_half(v0), to_half(v1), to_half(v2), to_half(v3)};
-          *US_LDS_PTR(v4h, p) = o;
+        for (int q = 0; q < 4; ++q) {
+          const int col = j * 32 + 8 * q + 4 * (lane >> 5);
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            if constexpr (decltype(with_bias)::value)
+              v[e] = __builtin_fmaf(acc[I0 + i][j][4 * q + e], scale, (float)bias4[j][q][e]);   // one rounding of the sum
+            else
+              v[e] = acc[I0 + i][j][4 * q + e] * scale;
+          }
+          uint8_t* p = strip + (lane & 31) * EP + col * S::ES;
+          if (WIDE) {
+            v4f o = {v[0], v[1], v[2], v[3]};
+            *US_LDS_PTR(v4f, p) = o;
+          } else {
+            v4h o = {to_half(v[0]), to_half(v[1]), to_half(v[2]), to_half(v[3])};
+            *US_LDS_PTR(v4h, p) = o;
+          }
         }
       }
+    };
+    if constexpr (BIAS) {
+      if (has_bias) to_strip(std::true_type{});
+      else to_strip(std::false_type{});
+    } else {
+      to_strip(std::false_type{});
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();

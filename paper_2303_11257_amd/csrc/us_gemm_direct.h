@@ -385,11 +385,11 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs& g, int bid, lon
     if (wk == 0) receive(std::integral_constant<int, 0>{});
     else receive(std::integral_constant<int, HALF>{});
     __syncthreads();     // everything exchanged: the strips may overlay the exchange area
-    if (wk == 0) store_block_epilogue<Cfg, EPI, WIDE, 0, HALF>(g, acc, lds, m0, n0, split);
-    else store_block_epilogue<Cfg, EPI, WIDE, HALF, FM>(g, acc, lds, m0, n0, split);
+    if (wk == 0) store_block_epilogue<Cfg, EPI, WIDE, 0, HALF, epilogue_takes_bias<A_KC, B_KC, EPI, WIDE>()>(g, acc, lds, m0, n0, split);
+    else store_block_epilogue<Cfg, EPI, WIDE, HALF, FM, epilogue_takes_bias<A_KC, B_KC, EPI, WIDE>()>(g, acc, lds, m0, n0, split);
     return;
   }
-  store_block_epilogue<Cfg, EPI, WIDE>(g, acc, lds, m0, n0, split);
+  store_block_epilogue<Cfg, EPI, WIDE, 0, Cfg::FM, epilogue_takes_bias<A_KC, B_KC, EPI, WIDE>()>(g, acc, lds, m0, n0, split);
 }
 
 template <class Cfg, bool FP8, int FA, int FB, bool A_KC, bool B_KC, int EPI, bool WIDE>

@@ -56,6 +56,7 @@ inline GemmArgs make_args(const GemmProblem& p, long k_per_split, int BM, int BN
   g.aux8 = (uint8_t*)p.aux8;
   g.partial = (float*)p.workspace;
   g.table = (const uint8_t*)p.table;
+  g.bias = (const _Float16*)p.bias;
   choose_xcd_grid(ceil_div(p.M, BM), ceil_div(p.N, BN), g.xcd_gm, g.xcd_gn);
   g.grp_w = (BM >= 256) ? 4 : 8;   // 32 (one per CU) resp. 64 (two per CU) concurrent tiles per XCD: 8 x 4 / 8 x 8
   return g;

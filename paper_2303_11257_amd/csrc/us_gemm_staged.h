@@ -199,7 +199,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_staged_kernel(Ge
     __syncthreads();
   }
   // the loop's last barrier has retired every read of the operand tiles
-  store_block_epilogue<Cfg, EPI, WIDE>(g, acc, lds, m0, n0, split);
+  store_block_epilogue<Cfg, EPI, WIDE, 0, Cfg::FM, epilogue_takes_bias<A_KC, B_KC, EPI, WIDE>()>(g, acc, lds, m0, n0, split);
 }
 
 }  // namespace us

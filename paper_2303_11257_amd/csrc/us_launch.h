@@ -28,6 +28,9 @@ hipError_t launch_layer_norm_fwd(const void* X, const void* w, const void* c, vo
 hipError_t launch_layer_norm_bwd(const void* X, const void* w, const void* G, void* dX, void* dw, void* dc, long b, long n, float eps,
                                  float beta_wc, void* workspace, hipStream_t stream);
 
+size_t bias_grad_workspace_bytes(long b, long n);
+hipError_t launch_bias_grad(const void* G, us_dtype g_dt, void* dc, long b, long n, float beta, void* workspace, hipStream_t stream);
+
 // One GEMM problem  C[M,N] = epilogue( scale * sum_k A(m,k) B(n,k) ).
 //   a_kc / b_kc: operand is K-contiguous (element (r,k) at base[r*ld + k]) or K-strided
 //   (element (r,k) at base[k*ld + r]).  The three layer-level products map to
@@ -52,6 +55,7 @@ struct GemmProblem {
   void* aux16;             // GELU: FP16 [M,N] or NULL
   void* aux8;              // GELU: E4M3 [M,N]; GELU_GRAD: E5M2 [M,N]; or NULL
   void* workspace;         // split-K partial sums (FP32), or NULL
+  const void* bias;        // forward product with FP16 result: optional FP16 row [N] added before the rounding, or NULL
   void* table;             // table area of the workspace (us_device.h), or NULL: arithmetic epilogue
   bool tables_ready;       // the table area is already filled for this epi_scale
   size_t workspace_bytes;

@@ -22,7 +22,8 @@ def test_every_declared_symbol_is_exported():
     assert {"us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd", "us_linear_scales",
             "us_workspace_bytes", "us_status_string", "us_ffn_fwd", "us_ffn_bwd", "us_gelu_tables", "us_weighted_add",
             "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd", "us_layer_norm_fwd", "us_layer_norm_bwd",
-            "us_layer_norm_workspace_bytes", "us_exponent_histogram", "us_cast_snr"} <= set(names)
+            "us_layer_norm_workspace_bytes", "us_exponent_histogram", "us_cast_snr", "us_linear_bias_fwd", "us_bias_grad",
+            "us_bias_grad_workspace_bytes", "us_ffn_bias_fwd", "us_ffn_bias_bwd", "us_ffn_bias_workspace_bytes"} <= set(names)
     L = ctypes.CDLL(us.library_path())
     for n in names:
         assert hasattr(L, n), n
@@ -49,6 +50,9 @@ def test_workspace_rule():
     assert wb > 0 and wb % (768 * 3072 * 4) == 0                    # whole FP32 slices of the output
     assert us.ffn_workspace_bytes(4096, 768, 3072) >= wb + table_area
     assert us.workspace_bytes(0, 16, 16) == 0
+    assert us.bias_grad_workspace_bytes(8192, 4096) == 256 * 4096 * 4 and us.bias_grad_workspace_bytes(33, 16) == 2 * 16 * 4
+    assert us.ffn_bias_workspace_bytes(8192, 1024, 4096) == table_area + 256 * 4096 * 4
+    assert us.ffn_bias_workspace_bytes(4096, 768, 3072) == us.ffn_workspace_bytes(4096, 768, 3072)   # the dW slices are larger
     assert us.layer_norm_workspace_bytes(8192, 1024) == 256 * 2 * 1024 * 4 and us.layer_norm_workspace_bytes(33, 16) == 2 * 2 * 16 * 4
 
 
@@ -93,6 +97,15 @@ def test_argument_errors_are_detected_on_the_host():
         (lambda: us.weighted_add(16, 16, 32, 8, E4), 4),
         (lambda: us.ffn_res_fwd(16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 0.0, 0), 7),                          # tau must be in (0, 1]
         (lambda: us.ffn_res_bwd(16, 16, 16, 16, 16, 16, 16, 16, None, 16, 16, 16, 16, 16, 16, 1.5, 0), 7),
+        (lambda: us.linear_bias_fwd(16, 16, 16, 16, 16, 16, 16, F16, F16, F32), 4),                          # bias needs an FP16 result
+        (lambda: us.linear_bias_fwd(16, 16, 8, 16, 16, 16, 16, F16, F16), 3),
+        (lambda: us.bias_grad(16, F32, 16, 32, 32, 0.0, 16, 1 << 20), 4),
+        (lambda: us.bias_grad(16, F16, 16, 32, 24, 0.0, 16, 1 << 20), 2),
+        (lambda: us.bias_grad(16, F16, None, 32, 32, 0.0, 16, 1 << 20), 1),
+        (lambda: us.bias_grad(16, F16, 16, 32, 32, 0.0, 16, 100), 5),
+        (lambda: us.ffn_bias_bwd(16, 16, 16, 16, 16, 16, 16, None, 16, 16, 16, 16, 16, 16, 16, 16, 16, us.FFN_FP8, 16, 1 << 20), 1),  # db1 without dZ16
+        (lambda: us.ffn_bias_bwd(16, 16, 16, 16, 16, 16, None, 16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 0, 16, 1 << 20), 1),          # db2 without G16
+        (lambda: us.ffn_bias_bwd(16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 64, 16, 16, 0, 16, 1000), 5),
         (lambda: us.gelu_tables(None, 1 << 20), 1),
         (lambda: us.gelu_tables(16, 1000), 5),                       # smaller than the table area
         (lambda: us.gelu_tables(24, 1 << 20), 3),
@@ -117,3 +130,4 @@ def test_argument_errors_are_detected_on_the_host():
     us.gelu_fwd(None, None, 0)
     us.linear_fwd(None, None, None, 0, 16, 16, F16, F16)
     us.linear_bwd(None, None, None, None, None, 0, 0, 0, F16, F16, F16)
+    us.bias_grad(None, F16, None, 0, 0)
