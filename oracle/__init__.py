@@ -59,6 +59,12 @@ def _load():
     lib.uso_linear_bias_fwd.restype = i
     lib.uso_bias_grad.argtypes = [vp, i, vp, i, l, l, f]
     lib.uso_bias_grad.restype = None
+    lib.uso_softmax_fwd.argtypes = [vp, vp, l, l, f, f]
+    lib.uso_softmax_fwd.restype = None
+    lib.uso_softmax_bwd.argtypes = [vp, vp, vp, l, l, f, f]
+    lib.uso_softmax_bwd.restype = None
+    lib.uso_softmax_xent.argtypes = [vp, vp, vp, vp, l, l, f, f]
+    lib.uso_softmax_xent.restype = None
     lib.uso_gelu_fwd.argtypes = [vp, vp, sz, i, f]
     lib.uso_gelu_fwd.restype = None
     lib.uso_gelu_bwd.argtypes = [vp, vp, vp, sz, i, f]
@@ -458,3 +464,54 @@ def cast_snr(a: np.ndarray, dst_dt: int, scale: float = 1.0):
     sums = np.zeros(2, np.float64)
     _load().uso_cast_snr(_p(a), _dt_of(a, None), a.size, dst_dt, float(np.float32(scale)), _p(sums))
     return float(sums[0]), float(sums[1])
+
+
+# ---- scaled softmax and softmax cross-entropy (Table A.2 "Other", App. G) ---------------------------------
+def softmax_scales(s: int):
+    """(alpha, beta) = (s, s): the output of a softmax over s unit-normal values is about 1/s everywhere, so s times
+    it is about a vector of ones for the matmul that follows (App. G "Softmax (followed by matmul)")."""
+    return np.float32(s), np.float32(s)
+
+
+def softmax_xent_scale(s: int):
+    """beta = s / sqrt(s - 1) (App. G "Softmax cross-entropy"; alpha = 1)."""
+    return np.float32(s / math.sqrt(s - 1.0))
+
+
+def softmax_fwd(x, alpha=None, s1=1.0):
+    """y = round(alpha * softmax(s1 * x)) over the last dimension of an FP16 [rows, s] array."""
+    x = _c(x)
+    assert x.dtype == np.float16 and x.ndim == 2
+    rows, s = x.shape
+    if alpha is None:
+        alpha = softmax_scales(s)[0]
+    y = np.empty_like(x)
+    _load().uso_softmax_fwd(_p(x), _p(y), rows, s, float(np.float32(s1)), float(np.float32(alpha)))
+    return y
+
+
+def softmax_bwd(x, g, beta=None, s1=1.0):
+    """dx = round(beta * s1 * p * (g - sum(p * g))), p = softmax(s1 * x)."""
+    x, g = _c(x), _c(g)
+    assert x.dtype == np.float16 and g.dtype == np.float16 and x.shape == g.shape and x.ndim == 2
+    rows, s = x.shape
+    if beta is None:
+        beta = softmax_scales(s)[1]
+    dx = np.empty_like(x)
+    _load().uso_softmax_bwd(_p(x), _p(g), _p(dx), rows, s, float(np.float32(s1)), float(np.float32(beta)))
+    return dx
+
+
+def softmax_xent(x, target, beta=None, s1=1.0):
+    """(loss[rows] float64, dx[rows, s] FP16): loss = -log softmax(s1 x)_target, dx = round(beta * s1 * (p - onehot));
+    rows whose target lies outside 0 .. s-1 carry no label: loss 0, gradient 0."""
+    x = _c(x)
+    target = np.ascontiguousarray(target, dtype=np.int32)
+    assert x.dtype == np.float16 and x.ndim == 2 and target.shape == (x.shape[0],)
+    rows, s = x.shape
+    if beta is None:
+        beta = softmax_xent_scale(s)
+    loss = np.empty(rows, np.float64)
+    dx = np.empty_like(x)
+    _load().uso_softmax_xent(_p(x), _p(target), _p(loss), _p(dx), rows, s, float(np.float32(s1)), float(np.float32(beta)))
+    return loss, dx

@@ -502,6 +502,98 @@ void uso_weighted_add2(const void* a, const void* b, void* out, size_t n, int dt
 }
 
 /*
+ * ---- scaled softmax and softmax cross-entropy (Table A.2 "Other"; App. G "Softmax (followed by matmul)",
+ *      "Softmax cross-entropy"; App. H "Softmax functions" for the input factor s1) --------------------
+ * Rows of s values, FP16 storage, double arithmetic, one rounding per output.
+ *   softmax fwd   y_j  = round( alpha * p_j ),  p = softmax(s1 * x) computed with the row maximum subtracted
+ *                 (Table A.2: alpha = s, so that the output is about a vector of ones for the matmul that follows)
+ *   softmax bwd   dx_j = round( beta * s1 * p_j * (g_j - sum_k p_k g_k) )      (Table A.2: beta = s)
+ *                 f_grad of the unscaled softmax times beta (Sec. 5.1), p recomputed from x, not taken from
+ *                 the rounded output
+ *   xent          loss = -(t_c - log sum_k exp(t_k)),  t = s1 * x, c the target class      (alpha = 1)
+ *                 dx_j = round( beta * s1 * (p_j - [j == c]) )   (App. G: beta = s / sqrt(s - 1); the op ends
+ *                 the model, so the incoming gradient is 1)
+ *                 Reading: a target outside 0 .. s-1 marks a row without a label (positions that are not
+ *                 predicted): loss 0, gradient row 0.
+ * s1 * x is not rounded before the exponential.
+ */
+static void softmax_row(const void* x, long row, long s, double s1, double* p, double* logsum, double* maxv) {
+  double m = -INFINITY;
+  int has_nan = 0;
+  for (long j = 0; j < s; ++j) {
+    double t = s1 * uso_decode_bits(load_bits(x, ODT_F16, (size_t)(row * s + j)), ODT_F16);
+    p[j] = t;
+    if (isnan(t)) has_nan = 1;
+    if (t > m) m = t;
+  }
+  if (has_nan) m = NAN;
+  double sum = 0.0;
+  for (long j = 0; j < s; ++j) { p[j] = exp(p[j] - m); sum += p[j]; }
+  for (long j = 0; j < s; ++j) p[j] /= sum;
+  if (logsum) *logsum = log(sum);
+  if (maxv) *maxv = m;
+}
+
+void uso_softmax_fwd(const void* x, void* y, long rows, long s, float s1, float alpha) {
+#pragma omp parallel
+  {
+    double* p = (double*)malloc((size_t)s * sizeof(double));
+#pragma omp for schedule(static)
+    for (long i = 0; i < rows; ++i) {
+      softmax_row(x, i, s, (double)s1, p, NULL, NULL);
+      for (long j = 0; j < s; ++j) store_bits(y, ODT_F16, (size_t)(i * s + j), round_out((double)alpha * p[j], ODT_F16));
+    }
+    free(p);
+  }
+}
+
+void uso_softmax_bwd(const void* x, const void* g, void* dx, long rows, long s, float s1, float beta) {
+#pragma omp parallel
+  {
+    double* p = (double*)malloc((size_t)s * sizeof(double));
+#pragma omp for schedule(static)
+    for (long i = 0; i < rows; ++i) {
+      softmax_row(x, i, s, (double)s1, p, NULL, NULL);
+      double dot = 0.0;
+      for (long j = 0; j < s; ++j) dot += p[j] * uso_decode_bits(load_bits(g, ODT_F16, (size_t)(i * s + j)), ODT_F16);
+      for (long j = 0; j < s; ++j) {
+        double gj = uso_decode_bits(load_bits(g, ODT_F16, (size_t)(i * s + j)), ODT_F16);
+        store_bits(dx, ODT_F16, (size_t)(i * s + j), round_out((double)beta * (double)s1 * p[j] * (gj - dot), ODT_F16));
+      }
+    }
+    free(p);
+  }
+}
+
+void uso_softmax_xent(const void* x, const int* target, double* loss, void* dx, long rows, long s, float s1, float beta) {
+#pragma omp parallel
+  {
+    double* p = (double*)malloc((size_t)s * sizeof(double));
+#pragma omp for schedule(static)
+    for (long i = 0; i < rows; ++i) {
+      const long c = target[i];
+      if (c < 0 || c >= s) {
+        if (loss) loss[i] = 0.0;
+        if (dx) for (long j = 0; j < s; ++j) store_bits(dx, ODT_F16, (size_t)(i * s + j), 0);
+        continue;
+      }
+      double logsum, m;
+      softmax_row(x, i, s, (double)s1, p, &logsum, &m);
+      if (loss) {
+        double tc = (double)s1 * uso_decode_bits(load_bits(x, ODT_F16, (size_t)(i * s + c)), ODT_F16);
+        loss[i] = -(tc - m - logsum);
+      }
+      if (dx)
+        for (long j = 0; j < s; ++j)
+          store_bits(dx, ODT_F16, (size_t)(i * s + j),
+                     round_out((double)beta * (double)s1 * (p[j] - (j == c ? 1.0 : 0.0)), ODT_F16));
+    }
+    free(p);
+  }
+}
+
+
+/*
  * ---- scale selection (Sec. 5.5; Table A.2; Sec. 5.2 for the geometric-mean rule) --------------
  * mode 0: unconstrained  alpha = m^-1/2, beta_x = n^-1/2, beta_w = b^-1/2
  * mode 1: X is not a cut-edge, so alpha = beta_x = (m*n)^-1/4; beta_w unchanged
