@@ -353,6 +353,18 @@ def main():
         bws = torch.empty(bwsb, dtype=torch.uint8, device="cuda:0")
         ms = time_steps(torch, lambda: us.bias_grad(za.data_ptr(), us.F16, ldc.data_ptr(), lb, ln, 0.0, bws.data_ptr(), bwsb, st), 50, 5)
         ew["bias_grad_GBps"] = round(2.0 * n / (ms * 1e-3) * 1e-9, 1)
+        # scaled softmax on [65536, 512] (attention rows): 4 B / element forward, 6 B backward; cross-entropy on
+        # [1024, 30528] (a BERT vocabulary, padded to a multiple of 8): loss and gradient, 4 B / element
+        sb, ss = n // 512, 512
+        ms = time_steps(torch, lambda: us.softmax_fwd(za.data_ptr(), zo.data_ptr(), sb, ss, 0.0, 0.0, st), 50, 5)
+        ew["softmax_fwd_GBps"] = round(4.0 * n / (ms * 1e-3) * 1e-9, 1)
+        ms = time_steps(torch, lambda: us.softmax_bwd(za.data_ptr(), zb.data_ptr(), zo.data_ptr(), sb, ss, 0.0, 0.0, st), 50, 5)
+        ew["softmax_bwd_GBps"] = round(6.0 * n / (ms * 1e-3) * 1e-9, 1)
+        xr, xs = 1024, 30528
+        xt = torch.randint(0, xs, (xr,), dtype=torch.int32, device="cuda:0")
+        xl = torch.empty(xr, dtype=torch.float32, device="cuda:0")
+        ms = time_steps(torch, lambda: us.softmax_xent(za.data_ptr(), xt.data_ptr(), xl.data_ptr(), zo.data_ptr(), xr, xs, 0.0, 0.0, st), 50, 5)
+        ew["softmax_xent_GBps"] = round(4.0 * xr * xs / (ms * 1e-3) * 1e-9, 1)
         # diagnostics: read-only, 2 B / element
         hist = torch.zeros(us.HIST_BINS, dtype=torch.int64, device="cuda:0")
         sums = torch.zeros(2, dtype=torch.float64, device="cuda:0")

@@ -329,6 +329,29 @@ us_status us_ffn_bias_bwd(const void* X, const void* W1, const void* W2, const v
                           size_t workspace_bytes, void* stream);
 size_t us_ffn_bias_workspace_bytes(long T, long d, long f);
 
+/*
+ * Scaled softmax over the last dimension (Table A.2 "Other"; App. G "Softmax (followed by matmul)"), and its
+ * aligned form with an input factor s1 = 1 / temperature (App. H "Softmax functions").  X, Y, G, dX: device, FP16
+ * [rows, s], 16-byte aligned, s a multiple of 8 and at most US_SOFTMAX_MAX (US_ERR_SHAPE otherwise); rows is free.
+ *   fwd:  Y[i,j]  = fp16( alpha * p_ij ),  p_i = softmax(s1 * X[i,:])           alpha <= 0 selects s
+ *   bwd:  dX[i,j] = fp16( beta * s1 * p_ij * (G[i,j] - sum_k p_ik G[i,k]) )     beta  <= 0 selects s
+ * s1 = 0 selects 1; a negative s1 is US_ERR_VALUE.  s1 * x is not rounded before the exponential; the backward pass
+ * recomputes p from X (not from the rounded Y).  A NaN or a +inf in a row makes the whole row NaN.  No masks.
+ *
+ * Softmax cross-entropy at the end of a model (App. G "Softmax cross-entropy": alpha = 1, beta = s / sqrt(s - 1)):
+ *   loss[i] = -log softmax(s1 * X[i,:])_target[i]                (FP32 [rows], device; may be NULL)
+ *   dX[i,j] = fp16( beta * s1 * (p_ij - [j == target[i]]) )      (FP16 [rows, s]; may be NULL; not both NULL)
+ * target: device, int32 [rows]; a value outside 0 .. s-1 marks a row without a label: loss 0, gradient row 0.
+ * s a multiple of 8 and at most US_XENT_MAX.  beta <= 0 selects s / sqrt(s - 1).
+ */
+#define US_SOFTMAX_MAX 4096
+#define US_XENT_MAX 65536
+us_status us_softmax_fwd(const void* X, void* Y, long rows, long s, float s1, float alpha, void* stream);
+us_status us_softmax_bwd(const void* X, const void* G, void* dX, long rows, long s, float s1, float beta,
+                         void* stream);
+us_status us_softmax_xent(const void* X, const int* target, float* loss, void* dX, long rows, long s, float s1,
+                          float beta, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -72,6 +72,9 @@ def lib() -> ctypes.CDLL:
     L.us_ffn_bwd.argtypes = [vp] * 11 + [l, l, l, i, vp, sz, vp]
     L.us_ffn_workspace_bytes.argtypes = [l, l, l]
     L.us_ffn_workspace_bytes.restype = sz
+    L.us_softmax_fwd.argtypes = [vp, vp, l, l, f, f, vp]
+    L.us_softmax_bwd.argtypes = [vp, vp, vp, l, l, f, f, vp]
+    L.us_softmax_xent.argtypes = [vp, vp, vp, vp, l, l, f, f, vp]
     L.us_linear_bias_fwd.argtypes = [vp, vp, vp, vp, l, l, l, i, i, i, f, i, f, vp, vp, vp, sz, vp]
     L.us_bias_grad.argtypes = [vp, i, vp, l, l, f, vp, sz, vp]
     L.us_bias_grad_workspace_bytes.argtypes = [l, l]
@@ -82,7 +85,8 @@ def lib() -> ctypes.CDLL:
     L.us_ffn_bias_workspace_bytes.restype = sz
     for name in ("us_linear_scales", "us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd",
                  "us_gelu_tables", "us_ffn_fwd", "us_ffn_bwd", "us_weighted_add", "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd", "us_layer_norm_fwd", "us_layer_norm_bwd", "us_exponent_histogram", "us_cast_snr",
-                 "us_linear_bias_fwd", "us_bias_grad", "us_ffn_bias_fwd", "us_ffn_bias_bwd"):
+                 "us_linear_bias_fwd", "us_bias_grad", "us_ffn_bias_fwd", "us_ffn_bias_bwd", "us_softmax_fwd", "us_softmax_bwd",
+                 "us_softmax_xent"):
         getattr(L, name).restype = i
     _lib = L
     return L
@@ -199,6 +203,18 @@ def ffn_bias_bwd(X, W1, W2, Z, H, G, G16, dZ16, dZ8, dX, dW1, dW2, db1, db2, T, 
 
 def ffn_bias_workspace_bytes(T: int, d: int, f: int) -> int:
     return int(lib().us_ffn_bias_workspace_bytes(T, d, f))
+
+
+def softmax_fwd(X, Y, rows, s, s1=0.0, alpha=0.0, stream=None):
+    _check(lib().us_softmax_fwd(X, Y, rows, s, s1, alpha, stream), "us_softmax_fwd")
+
+
+def softmax_bwd(X, G, dX, rows, s, s1=0.0, beta=0.0, stream=None):
+    _check(lib().us_softmax_bwd(X, G, dX, rows, s, s1, beta, stream), "us_softmax_bwd")
+
+
+def softmax_xent(X, target, loss, dX, rows, s, s1=0.0, beta=0.0, stream=None):
+    _check(lib().us_softmax_xent(X, target, loss, dX, rows, s, s1, beta, stream), "us_softmax_xent")
 
 
 def act_fwd(z, h, n, dt=F16, kind=ACT_GELU, s1=0.0, scale=0.0, stream=None):

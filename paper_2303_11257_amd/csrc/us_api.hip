@@ -418,4 +418,33 @@ size_t us_ffn_bias_workspace_bytes(long T, long d, long f) {
   return a > b ? a : b;
 }
 
+us_status us_softmax_fwd(const void* X, void* Y, long rows, long s, float s1, float alpha, void* stream) {
+  if (rows < 0 || s < 0 || s % 8 != 0 || s > US_SOFTMAX_MAX) return US_ERR_SHAPE;
+  if (rows == 0 || s == 0) return US_OK;
+  if (!X || !Y) return US_ERR_NULL;
+  if (!aligned16(X) || !aligned16(Y)) return US_ERR_ALIGN;
+  if (s1 < 0.0f) return US_ERR_VALUE;
+  return from_hip(launch_softmax_fwd(X, Y, rows, s, s1 > 0.0f ? s1 : 1.0f, alpha > 0.0f ? alpha : (float)s, as_stream(stream)));
+}
+
+us_status us_softmax_bwd(const void* X, const void* G, void* dX, long rows, long s, float s1, float beta, void* stream) {
+  if (rows < 0 || s < 0 || s % 8 != 0 || s > US_SOFTMAX_MAX) return US_ERR_SHAPE;
+  if (rows == 0 || s == 0) return US_OK;
+  if (!X || !G || !dX) return US_ERR_NULL;
+  if (!aligned16(X) || !aligned16(G) || !aligned16(dX)) return US_ERR_ALIGN;
+  if (s1 < 0.0f) return US_ERR_VALUE;
+  return from_hip(launch_softmax_bwd(X, G, dX, rows, s, s1 > 0.0f ? s1 : 1.0f, beta > 0.0f ? beta : (float)s, as_stream(stream)));
+}
+
+us_status us_softmax_xent(const void* X, const int* target, float* loss, void* dX, long rows, long s, float s1, float beta,
+                          void* stream) {
+  if (rows < 0 || s < 0 || s % 8 != 0 || s > US_XENT_MAX) return US_ERR_SHAPE;
+  if (rows == 0 || s == 0) return US_OK;
+  if (!X || !target || (!loss && !dX)) return US_ERR_NULL;
+  if (!aligned16(X) || !aligned16(dX) || ((uintptr_t)target & 3) || ((uintptr_t)loss & 3)) return US_ERR_ALIGN;
+  if (s1 < 0.0f) return US_ERR_VALUE;
+  const float b = beta > 0.0f ? beta : (float)((double)s / sqrt((double)(s > 1 ? s - 1 : 1)));
+  return from_hip(launch_softmax_xent(X, target, loss, dX, rows, s, s1 > 0.0f ? s1 : 1.0f, b, as_stream(stream)));
+}
+
 }  // extern "C"

@@ -4,8 +4,8 @@
 //   forward   reads X, writes Y                                   4 B / element
 //   backward  reads X and G, writes dX, and leaves per-row-block column sums of G*xhat and G in a
 //             workspace; a second small kernel adds the blocks in order (deterministic)      6 B / element
-#include "us_device.h"
 #include "us_launch.h"
+#include "us_rows.h"
 
 namespace us {
 
@@ -13,26 +13,6 @@ namespace {
 
 constexpr int kLnThreads = 256;       // four waves, one row each at a time
 constexpr int kLnRowsPerBlock = 32;   // rows whose column sums one workgroup accumulates (backward)
-
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
-}
-
-// A row of n FP16 values as NCH chunks of 8 per lane: chunk k of lane l covers columns (k*64 + l)*8 .. +7.
-template <int NCH>
-struct RowRegs {
-  v8h v[NCH];
-  __device__ __forceinline__ void load(const _Float16* row, int n, int lane) {
-#pragma unroll
-    for (int k = 0; k < NCH; ++k) {
-      const int col = (k * 64 + lane) * 8;
-      if (col < n) v[k] = *reinterpret_cast<const v8h*>(row + col);
-      else v[k] = v8h{0, 0, 0, 0, 0, 0, 0, 0};
-    }
-  }
-};
 
 // mean and 1/sqrt(variance + eps) of the row held in x (two passes over the registers)
 template <int NCH>

@@ -23,7 +23,7 @@ def test_every_declared_symbol_is_exported():
             "us_workspace_bytes", "us_status_string", "us_ffn_fwd", "us_ffn_bwd", "us_gelu_tables", "us_weighted_add",
             "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd", "us_layer_norm_fwd", "us_layer_norm_bwd",
             "us_layer_norm_workspace_bytes", "us_exponent_histogram", "us_cast_snr", "us_linear_bias_fwd", "us_bias_grad",
-            "us_bias_grad_workspace_bytes", "us_ffn_bias_fwd", "us_ffn_bias_bwd", "us_ffn_bias_workspace_bytes"} <= set(names)
+            "us_bias_grad_workspace_bytes", "us_ffn_bias_fwd", "us_ffn_bias_bwd", "us_ffn_bias_workspace_bytes", "us_softmax_fwd", "us_softmax_bwd", "us_softmax_xent"} <= set(names)
     L = ctypes.CDLL(us.library_path())
     for n in names:
         assert hasattr(L, n), n
@@ -106,6 +106,14 @@ def test_argument_errors_are_detected_on_the_host():
         (lambda: us.ffn_bias_bwd(16, 16, 16, 16, 16, 16, 16, None, 16, 16, 16, 16, 16, 16, 16, 16, 16, us.FFN_FP8, 16, 1 << 20), 1),  # db1 without dZ16
         (lambda: us.ffn_bias_bwd(16, 16, 16, 16, 16, 16, None, 16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 0, 16, 1 << 20), 1),          # db2 without G16
         (lambda: us.ffn_bias_bwd(16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 64, 16, 16, 0, 16, 1000), 5),
+        (lambda: us.softmax_fwd(16, 16, 4, 12), 2),                                                        # s not a multiple of 8
+        (lambda: us.softmax_fwd(16, 16, 4, 8192), 2),                                                      # row too long
+        (lambda: us.softmax_fwd(16, None, 4, 64), 1),
+        (lambda: us.softmax_fwd(16, 16, 4, 64, -1.0), 7),
+        (lambda: us.softmax_bwd(16, 16, 24, 4, 64), 3),
+        (lambda: us.softmax_xent(16, 16, None, None, 4, 64), 1),                                           # neither output
+        (lambda: us.softmax_xent(16, 18, 16, 16, 4, 64), 3),                                               # targets not 4-byte aligned
+        (lambda: us.softmax_xent(16, 16, 16, 16, 4, 65544), 2),
         (lambda: us.gelu_tables(None, 1 << 20), 1),
         (lambda: us.gelu_tables(16, 1000), 5),                       # smaller than the table area
         (lambda: us.gelu_tables(24, 1 << 20), 3),
@@ -131,3 +139,5 @@ def test_argument_errors_are_detected_on_the_host():
     us.linear_fwd(None, None, None, 0, 16, 16, F16, F16)
     us.linear_bwd(None, None, None, None, None, 0, 0, 0, F16, F16, F16)
     us.bias_grad(None, F16, None, 0, 0)
+    us.softmax_fwd(None, None, 0, 64)
+    us.softmax_xent(None, None, None, None, 0, 64)
