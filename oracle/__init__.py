@@ -515,3 +515,53 @@ def softmax_xent(x, target, beta=None, s1=1.0):
     dx = np.empty_like(x)
     _load().uso_softmax_xent(_p(x), _p(target), _p(loss), _p(dx), rows, s, float(np.float32(s1)), float(np.float32(beta)))
     return loss, dx
+
+
+# ---- batched scaled matmuls and unit-scaled dot-product attention (App. F "Scaled dot product self attention",
+#      Table A.2 "Linear" for the factors of each product, App. G for the softmax between them) -------------------
+def matmul_batched(A, B, scale, trans_a=False, trans_b=False, a_dt=None, b_dt=None, out_dt=F16):
+    """C[i] = round(scale * op(A[i]) op(B[i])) for every i of the leading (batch) dimension; op transposes the last
+    two dimensions where asked.  Each slice is the plain matmul of this module (double sums in index order)."""
+    assert not (trans_a and trans_b)
+    outs = []
+    for a, b in zip(A, B):
+        if not trans_a and not trans_b:
+            outs.append(linear_fwd(a, b, scale, a_dt, b_dt, out_dt))            # [M,K] [K,N]
+        elif trans_b:
+            outs.append(linear_bwd_dx(a, b, scale, a_dt, b_dt, out_dt))         # [M,K] [N,K]^T
+        else:
+            outs.append(linear_bwd_dw(a, b, scale, a_dt, b_dt, out_dt))         # [K,M]^T [K,N]
+    return np.stack(outs)
+
+
+def attention_scales(s: int, d: int):
+    """Factors of the three ops of one attention head with s keys and head size d, by Table A.2's matmul rule
+    (alpha = fan_in^-1/2, beta_X = fan_out^-1/2, beta_W = rows^-1/2) and its softmax row:
+      scores  A = Q K^T : reduces over d, its two gradients over s;  probabilities: alpha = beta = s;
+      output  O = P V   : reduces over s, grad_P over d, grad_V over the s queries."""
+    r = lambda v: np.float32(1.0 / math.sqrt(v))
+    return dict(a_scores=r(d), b_q=r(s), b_k=r(s), a_soft=np.float32(s), b_soft=np.float32(s), a_out=r(s), b_p=r(d), b_v=r(s))
+
+
+def attention_fwd(Q, K, V):
+    """Unit-scaled dot-product attention for FP16 Q, K, V of shape [heads, s, d] (no mask): every stored tensor kept."""
+    h, s, d = Q.shape
+    c = attention_scales(s, d)
+    r = {}
+    r["A"] = matmul_batched(Q, K, c["a_scores"], trans_b=True)                   # [h, s, s]
+    r["P"] = softmax_fwd(r["A"].reshape(h * s, s), c["a_soft"]).reshape(h, s, s)
+    r["O"] = matmul_batched(r["P"], V, c["a_out"])                               # [h, s, d]
+    return r
+
+
+def attention_bwd(Q, K, V, dO, fwd: dict):
+    """Backward of attention_fwd from its stored A and P."""
+    h, s, d = Q.shape
+    c = attention_scales(s, d)
+    r = {}
+    r["dV"] = matmul_batched(fwd["P"], dO, c["b_v"], trans_a=True)               # P^T dO   [h, s, d]
+    r["dP"] = matmul_batched(dO, V, c["b_p"], trans_b=True)                      # dO V^T   [h, s, s]
+    r["dA"] = softmax_bwd(fwd["A"].reshape(h * s, s), r["dP"].reshape(h * s, s), c["b_soft"]).reshape(h, s, s)
+    r["dQ"] = matmul_batched(r["dA"], K, c["b_q"])                               # dA K     [h, s, d]
+    r["dK"] = matmul_batched(r["dA"], Q, c["b_k"], trans_a=True)                 # dA^T Q   [h, s, d]
+    return r
