@@ -376,6 +376,28 @@ def main():
         ew["peak_GBps"] = PEAK_HBM_GBS
         out["elementwise"] = ew
         del za, zb, zo
+    if not args.no_secondary:
+        # unit-scaled attention (unfused: batched matmuls + scaled softmax), 16 sequences x 16 heads, 512 tokens, head size 64
+        ah, as_, ad = 256, 512, 64
+        e16 = lambda *shape: torch.randn(shape, dtype=torch.float16, device="cuda:0")
+        aq, ak, av, ado = (e16(ah, as_, ad) for _ in range(4))
+        aA, aP, adP, adA = (torch.empty((ah, as_, as_), dtype=torch.float16, device="cuda:0") for _ in range(4))
+        aO, adQ, adK, adV = (torch.empty((ah, as_, ad), dtype=torch.float16, device="cuda:0") for _ in range(4))
+        st = torch.cuda.current_stream().cuda_stream
+        dp = lambda t: t.data_ptr()
+
+        def attn_step():
+            us.attention_fwd(dp(aq), dp(ak), dp(av), dp(aA), dp(aP), dp(aO), ah, as_, ad, st)
+            us.attention_bwd(dp(aq), dp(ak), dp(av), dp(aA), dp(aP), dp(ado), dp(adP), dp(adA), dp(adQ), dp(adK), dp(adV), ah, as_, ad, st)
+        ms_a = time_steps(torch, attn_step, 50, 5)
+        a_flop = 12.0 * as_ * as_ * ad * ah
+        # [heads, s, s] tensors: A written + read twice, P written + read twice, dP written + read, dA written + read twice
+        a_bytes = 11.0 * ah * as_ * as_ * 2
+        out["attention"] = {"what": "unit-scaled attention fwd+bwd, FP16, 256 heads x 512 tokens x 64, unfused (6 batched matmuls, "
+                                    "scaled softmax fwd and bwd; scores and probabilities stored)",
+                            "ms_per_step": ms_a, "TFLOPs": a_flop / (ms_a * 1e-3) * 1e-12,
+                            "score_tensor_GBps": a_bytes / (ms_a * 1e-3) * 1e-9}
+        del aq, ak, av, ado, aA, aP, adP, adA, aO, adQ, adK, adV
     if not args.no_secondary and args.workload != "C2":
         w2 = WORKLOADS["C2"]
         f2 = Ffn(torch, us, synth, w2["T"], w2["d"], w2["f"], False, synth.BASE_SEED + 1)

@@ -352,6 +352,31 @@ us_status us_softmax_bwd(const void* X, const void* G, void* dX, long rows, long
 us_status us_softmax_xent(const void* X, const int* target, float* loss, void* dX, long rows, long s, float s1,
                           float beta, void* stream);
 
+/*
+ * A batch of equally shaped, independent scaled matmuls in one launch (the per-head products of attention):
+ *   C[i] = round( scale * op(A[i]) op(B[i]) ),  i = 0 .. batch-1,  C[i] is [M,N] row-major, matrices packed one after
+ *   the other.  trans_a = 0: A[i] is [M,K]; 1: A[i] is [K,M].  trans_b = 0: B[i] is [K,N]; 1: B[i] is [N,K].  Both 1 is
+ *   not supported (US_ERR_SHAPE).  Operand types: F16 x F16, or the FP8 pairs of the layer products: E4M3 x E4M3
+ *   (no transposition), E5M2 x E4M3 (trans_b), E4M3 x E5M2 (trans_a).  c_dt F16 or F32.  M, N, K multiples of 16,
+ *   batch <= 65535, scale > 0 (US_ERR_VALUE otherwise).  FP32 accumulation over all of K in one workgroup: no workspace.
+ *
+ * Unit-scaled dot-product attention without mask for `heads` independent heads (batch x heads of a layer), built from
+ * the call above and the scaled softmax, with the factors Table A.2 gives each op (App. F notes that the familiar
+ * 1/sqrt(d) is the forward factor of the scores):
+ *   fwd:  A = fp16(d^-1/2 Q K^T)   P = fp16(s * softmax(A))   O = fp16(s^-1/2 P V)
+ *   bwd:  dV = fp16(s^-1/2 P^T dO)  dP = fp16(d^-1/2 dO V^T)  dA = fp16(s * p (dP - sum p dP))
+ *         dQ = fp16(s^-1/2 dA K)    dK = fp16(s^-1/2 dA^T Q)
+ * Q, K, V, O, dO, dQ, dK, dV: FP16 [heads, s, d]; A, P, dP, dA: FP16 [heads, s, s]; all device, 16-byte aligned; s and d
+ * multiples of 16, s <= US_SOFTMAX_MAX.  A and P are stored by the forward call and read by the backward call.
+ */
+us_status us_matmul_batched(const void* A, const void* B, void* C, long batch, long M, long N, long K, int trans_a,
+                            int trans_b, us_dtype a_dt, us_dtype b_dt, us_dtype c_dt, float scale, void* stream);
+us_status us_attention_fwd(const void* Q, const void* K, const void* V, void* A, void* P, void* O, long heads, long s,
+                           long d, void* stream);
+us_status us_attention_bwd(const void* Q, const void* K, const void* V, const void* A, const void* P, const void* dO,
+                           void* dP, void* dA, void* dQ, void* dK, void* dV, long heads, long s, long d,
+                           void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -72,6 +72,9 @@ def lib() -> ctypes.CDLL:
     L.us_ffn_bwd.argtypes = [vp] * 11 + [l, l, l, i, vp, sz, vp]
     L.us_ffn_workspace_bytes.argtypes = [l, l, l]
     L.us_ffn_workspace_bytes.restype = sz
+    L.us_matmul_batched.argtypes = [vp, vp, vp, l, l, l, l, i, i, i, i, i, f, vp]
+    L.us_attention_fwd.argtypes = [vp] * 6 + [l, l, l, vp]
+    L.us_attention_bwd.argtypes = [vp] * 11 + [l, l, l, vp]
     L.us_softmax_fwd.argtypes = [vp, vp, l, l, f, f, vp]
     L.us_softmax_bwd.argtypes = [vp, vp, vp, l, l, f, f, vp]
     L.us_softmax_xent.argtypes = [vp, vp, vp, vp, l, l, f, f, vp]
@@ -86,7 +89,7 @@ def lib() -> ctypes.CDLL:
     for name in ("us_linear_scales", "us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd",
                  "us_gelu_tables", "us_ffn_fwd", "us_ffn_bwd", "us_weighted_add", "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd", "us_layer_norm_fwd", "us_layer_norm_bwd", "us_exponent_histogram", "us_cast_snr",
                  "us_linear_bias_fwd", "us_bias_grad", "us_ffn_bias_fwd", "us_ffn_bias_bwd", "us_softmax_fwd", "us_softmax_bwd",
-                 "us_softmax_xent"):
+                 "us_softmax_xent", "us_matmul_batched", "us_attention_fwd", "us_attention_bwd"):
         getattr(L, name).restype = i
     _lib = L
     return L
@@ -203,6 +206,19 @@ def ffn_bias_bwd(X, W1, W2, Z, H, G, G16, dZ16, dZ8, dX, dW1, dW2, db1, db2, T, 
 
 def ffn_bias_workspace_bytes(T: int, d: int, f: int) -> int:
     return int(lib().us_ffn_bias_workspace_bytes(T, d, f))
+
+
+def matmul_batched(A, B, C, batch, M, N, K, trans_a, trans_b, a_dt, b_dt, c_dt, scale, stream=None):
+    _check(lib().us_matmul_batched(A, B, C, batch, M, N, K, int(trans_a), int(trans_b), a_dt, b_dt, c_dt, scale, stream),
+           "us_matmul_batched")
+
+
+def attention_fwd(Q, K, V, A, P, O, heads, s, d, stream=None):
+    _check(lib().us_attention_fwd(Q, K, V, A, P, O, heads, s, d, stream), "us_attention_fwd")
+
+
+def attention_bwd(Q, K, V, A, P, dO, dP, dA, dQ, dK, dV, heads, s, d, stream=None):
+    _check(lib().us_attention_bwd(Q, K, V, A, P, dO, dP, dA, dQ, dK, dV, heads, s, d, stream), "us_attention_bwd")
 
 
 def softmax_fwd(X, Y, rows, s, s1=0.0, alpha=0.0, stream=None):

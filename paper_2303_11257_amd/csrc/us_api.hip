@@ -447,4 +447,67 @@ us_status us_softmax_xent(const void* X, const int* target, float* loss, void* d
   return from_hip(launch_softmax_xent(X, target, loss, dX, rows, s, s1 > 0.0f ? s1 : 1.0f, b, as_stream(stream)));
 }
 
+us_status us_matmul_batched(const void* A, const void* B, void* C, long batch, long M, long N, long K, int trans_a, int trans_b,
+                            us_dtype a_dt, us_dtype b_dt, us_dtype c_dt, float scale, void* stream) {
+  if ((trans_a != 0 && trans_a != 1) || (trans_b != 0 && trans_b != 1) || (trans_a && trans_b)) return US_ERR_SHAPE;
+  const bool f16 = (a_dt == US_F16 && b_dt == US_F16);
+  // the FP8 pairs are those of the three layer products: forward E4M3 x E4M3, grad_X E5M2 x E4M3, grad_W E4M3 x E5M2
+  const bool fp8 = !trans_a && !trans_b ? (a_dt == US_E4M3 && b_dt == US_E4M3)
+                   : trans_b            ? (a_dt == US_E5M2 && b_dt == US_E4M3)
+                                        : (a_dt == US_E4M3 && b_dt == US_E5M2);
+  if (!f16 && !fp8) return US_ERR_DTYPE;
+  if (c_dt != US_F16 && c_dt != US_F32) return US_ERR_DTYPE;
+  if (batch < 0 || batch > 65535 || M < 0 || N < 0 || K < 0 || !mult16(M) || !mult16(N) || !mult16(K)) return US_ERR_SHAPE;
+  if (batch == 0 || M == 0 || N == 0) return US_OK;
+  if (!C || (K > 0 && (!A || !B))) return US_ERR_NULL;
+  if (!aligned16(A) || !aligned16(B) || !aligned16(C)) return US_ERR_ALIGN;
+  if (!(scale > 0.0f)) return US_ERR_VALUE;
+  GemmProblem p{};
+  p.A = A; p.B = B; p.C = C;
+  p.M = M; p.N = N; p.K = K;
+  p.a_kc = !trans_a;                 // A [M,K] as stored, or [K,M]
+  p.b_kc = trans_b != 0;             // B [N,K] when transposed, else [K,N]
+  p.lda = p.a_kc ? K : M;
+  p.ldb = p.b_kc ? K : N;
+  p.ldc = N;
+  p.a_dt = a_dt; p.b_dt = b_dt; p.c_dt = c_dt;
+  p.scale = scale;
+  p.epi = US_EPI_NONE;
+  p.batch = batch;
+  p.batch_a = M * K; p.batch_b = N * K; p.batch_c = M * N;
+  return from_hip(launch_gemm(p, as_stream(stream)));
+}
+
+us_status us_attention_fwd(const void* Q, const void* K, const void* V, void* A, void* P, void* O, long heads, long s, long d,
+                           void* stream) {
+  if (heads < 0 || s < 0 || d < 0 || !mult16(s) || !mult16(d) || s > US_SOFTMAX_MAX) return US_ERR_SHAPE;
+  if (heads == 0 || s == 0 || d == 0) return US_OK;
+  if (!Q || !K || !V || !A || !P || !O) return US_ERR_NULL;
+  const float rs = (float)(1.0 / sqrt((double)s)), rd = (float)(1.0 / sqrt((double)d));
+  // scores A = d^-1/2 Q K^T, probabilities P = s softmax(A), output O = s^-1/2 P V
+  us_status st = us_matmul_batched(Q, K, A, heads, s, s, d, 0, 1, US_F16, US_F16, US_F16, rd, stream);
+  if (st != US_OK) return st;
+  st = us_softmax_fwd(A, P, heads * s, s, 0.0f, 0.0f, stream);
+  if (st != US_OK) return st;
+  return us_matmul_batched(P, V, O, heads, s, d, s, 0, 0, US_F16, US_F16, US_F16, rs, stream);
+}
+
+us_status us_attention_bwd(const void* Q, const void* K, const void* V, const void* A, const void* P, const void* dO, void* dP,
+                           void* dA, void* dQ, void* dK, void* dV, long heads, long s, long d, void* stream) {
+  if (heads < 0 || s < 0 || d < 0 || !mult16(s) || !mult16(d) || s > US_SOFTMAX_MAX) return US_ERR_SHAPE;
+  if (heads == 0 || s == 0 || d == 0) return US_OK;
+  if (!Q || !K || !V || !A || !P || !dO || !dP || !dA || !dQ || !dK || !dV) return US_ERR_NULL;
+  const float rs = (float)(1.0 / sqrt((double)s)), rd = (float)(1.0 / sqrt((double)d));
+  // dV = s^-1/2 P^T dO;  dP = d^-1/2 dO V^T;  dA = s * softmax'(A)(dP);  dQ = s^-1/2 dA K;  dK = s^-1/2 dA^T Q
+  us_status st = us_matmul_batched(P, dO, dV, heads, s, d, s, 1, 0, US_F16, US_F16, US_F16, rs, stream);
+  if (st != US_OK) return st;
+  st = us_matmul_batched(dO, V, dP, heads, s, s, d, 0, 1, US_F16, US_F16, US_F16, rd, stream);
+  if (st != US_OK) return st;
+  st = us_softmax_bwd(A, dP, dA, heads * s, s, 0.0f, 0.0f, stream);
+  if (st != US_OK) return st;
+  st = us_matmul_batched(dA, K, dQ, heads, s, d, s, 0, 0, US_F16, US_F16, US_F16, rs, stream);
+  if (st != US_OK) return st;
+  return us_matmul_batched(dA, Q, dK, heads, s, d, s, 1, 0, US_F16, US_F16, US_F16, rs, stream);
+}
+
 }  // extern "C"

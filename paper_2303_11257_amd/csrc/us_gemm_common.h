@@ -34,10 +34,19 @@ struct GemmArgs {
   uint8_t* aux8;         // optional FP8 copy of the epilogue's FP16 result
   float* partial;        // EPI_PARTIAL: [splits][M][N] FP32
   const uint8_t* table;  // EPI_*_TAB: the table in global memory (us_device.h)
+  long batch_a, batch_b, batch_c;   // bytes between consecutive problems of a batch (blockIdx.z), 0 for a single one
   const _Float16* bias;  // forward product only: optional row [N] added to scale * acc before the rounding, or NULL
   int xcd_gm, xcd_gn;    // XCD rectangle split of the tile grid (0,0 = one rectangle)
   int grp_w;             // width of the column bands the rectangle is walked in
 };
+
+// Problem number blockIdx.z of a batch of equally shaped, independent products (plain-store epilogue only).
+__device__ __forceinline__ void select_batch_item(GemmArgs& g) {
+  const long z = blockIdx.z;
+  g.A += z * g.batch_a;
+  g.B += z * g.batch_b;
+  g.C = (uint8_t*)g.C + z * g.batch_c;
+}
 
 // Tile configuration.  BKB = bytes of K per row and pipeline stage; NST = LDS stage buffers;
 // MINB = workgroups per CU the register allocation should allow.  WAVES_K > 1: that many groups of

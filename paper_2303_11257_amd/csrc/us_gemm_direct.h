@@ -395,6 +395,7 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs& g, int bid, lon
 template <class Cfg, bool FP8, int FA, int FB, bool A_KC, bool B_KC, int EPI, bool WIDE>
 __global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_direct_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  if constexpr (EPI == EPI_STORE) select_batch_item(g);
   gemm_direct_tile<Cfg, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(g, (int)blockIdx.x, (long)blockIdx.y, lds);
 }
 

@@ -57,6 +57,12 @@ inline GemmArgs make_args(const GemmProblem& p, long k_per_split, int BM, int BN
   g.partial = (float*)p.workspace;
   g.table = (const uint8_t*)p.table;
   g.bias = (const _Float16*)p.bias;
+  if (p.batch > 1) {
+    const long es = (p.a_dt == US_F16) ? 2 : 1;
+    g.batch_a = p.batch_a * es;
+    g.batch_b = p.batch_b * es;
+    g.batch_c = p.batch_c * (p.c_dt == US_F32 ? 4 : 2);
+  }
   choose_xcd_grid(ceil_div(p.M, BM), ceil_div(p.N, BN), g.xcd_gm, g.xcd_gn);
   g.grp_w = (BM >= 256) ? 4 : 8;   // 32 (one per CU) resp. 64 (two per CU) concurrent tiles per XCD: 8 x 4 / 8 x 8
   return g;
@@ -78,7 +84,7 @@ hipError_t launch_one(const GemmProblem& p, int splits, long k_per_split, hipStr
   }
   const GemmArgs g = make_args(p, k_per_split, Cfg::BM, Cfg::BN);
   const long tiles = ceil_div(p.M, Cfg::BM) * ceil_div(p.N, Cfg::BN);
-  dim3 grid((unsigned)tiles, (unsigned)splits, 1);
+  dim3 grid((unsigned)tiles, (unsigned)splits, (unsigned)(p.batch > 1 ? p.batch : 1));
   kern<<<grid, Cfg::THREADS, LDS, st>>>(g);
   return hipGetLastError();
 }
@@ -88,8 +94,10 @@ hipError_t launch_sized(const GemmProblem& p, int splits, long k_per_split, hipS
   const long bk = FP8 ? 128 : 64;                       // elements of K per stage of the direct kernels
   const bool direct_ok = p.K > 0 && p.K % bk == 0;      // slice lengths are multiples of 128 already
   if (!direct_ok) return launch_one<false, CfgS128, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
-  if (use_big_tile(p.M, p.N, splits))
+  const bool batched = p.batch > 1;      // the tile count that decides is the whole batch's
+  if (use_big_tile(p.M, p.N, splits * (int)(batched ? p.batch : 1)) && (!batched || (p.M >= 256 && p.N >= 256)))
     return launch_one<true, CfgD256, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
+  if (batched) return launch_one<true, CfgD128, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
   if constexpr ((A_KC || B_KC) && (EPI == EPI_STORE || EPI == EPI_RESIDUAL) && !WIDE) {
     if (splits == 1 && ceil_div(p.M, 128) * ceil_div(p.N, 128) <= 256 && p.K >= 1024)
       return launch_one<true, CfgW128, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);

@@ -124,6 +124,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_staged_kernel(Ge
   constexpr int PB = B_KC ? T::PITCH_KC : T::PITCH_B_KS;
 
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  if constexpr (EPI == EPI_STORE) select_batch_item(g);
 
   const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
   int tm, tn;

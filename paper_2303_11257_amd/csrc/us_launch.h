@@ -59,6 +59,8 @@ struct GemmProblem {
   void* aux16;             // GELU: FP16 [M,N] or NULL
   void* aux8;              // GELU: E4M3 [M,N]; GELU_GRAD: E5M2 [M,N]; or NULL
   void* workspace;         // split-K partial sums (FP32), or NULL
+  long batch;              // number of equally shaped, independent products (0 or 1: a single one); plain store only
+  long batch_a, batch_b, batch_c;   // elements between consecutive problems
   const void* bias;        // forward product with FP16 result: optional FP16 row [N] added before the rounding, or NULL
   void* table;             // table area of the workspace (us_device.h), or NULL: arithmetic epilogue
   bool tables_ready;       // the table area is already filled for this epi_scale

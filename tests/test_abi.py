@@ -23,7 +23,8 @@ def test_every_declared_symbol_is_exported():
             "us_workspace_bytes", "us_status_string", "us_ffn_fwd", "us_ffn_bwd", "us_gelu_tables", "us_weighted_add",
             "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd", "us_layer_norm_fwd", "us_layer_norm_bwd",
             "us_layer_norm_workspace_bytes", "us_exponent_histogram", "us_cast_snr", "us_linear_bias_fwd", "us_bias_grad",
-            "us_bias_grad_workspace_bytes", "us_ffn_bias_fwd", "us_ffn_bias_bwd", "us_ffn_bias_workspace_bytes", "us_softmax_fwd", "us_softmax_bwd", "us_softmax_xent"} <= set(names)
+            "us_bias_grad_workspace_bytes", "us_ffn_bias_fwd", "us_ffn_bias_bwd", "us_ffn_bias_workspace_bytes", "us_softmax_fwd", "us_softmax_bwd", "us_softmax_xent", "us_matmul_batched",
+            "us_attention_fwd", "us_attention_bwd"} <= set(names)
     L = ctypes.CDLL(us.library_path())
     for n in names:
         assert hasattr(L, n), n
@@ -114,6 +115,14 @@ def test_argument_errors_are_detected_on_the_host():
         (lambda: us.softmax_xent(16, 16, None, None, 4, 64), 1),                                           # neither output
         (lambda: us.softmax_xent(16, 18, 16, 16, 4, 64), 3),                                               # targets not 4-byte aligned
         (lambda: us.softmax_xent(16, 16, 16, 16, 4, 65544), 2),
+        (lambda: us.matmul_batched(16, 16, 16, 2, 16, 16, 16, 1, 1, F16, F16, F16, 1.0), 2),               # both transposed
+        (lambda: us.matmul_batched(16, 16, 16, 2, 16, 16, 16, 0, 1, E4, E4, F16, 1.0), 4),                 # not one of the FP8 pairs
+        (lambda: us.matmul_batched(16, 16, 16, 70000, 16, 16, 16, 0, 0, F16, F16, F16, 1.0), 2),
+        (lambda: us.matmul_batched(16, 16, 16, 2, 16, 16, 16, 0, 0, F16, F16, F16, 0.0), 7),
+        (lambda: us.matmul_batched(16, None, 16, 2, 16, 16, 16, 0, 0, F16, F16, F16, 1.0), 1),
+        (lambda: us.attention_fwd(16, 16, 16, 16, 16, 16, 2, 8192, 64), 2),                                # rows longer than the softmax takes
+        (lambda: us.attention_fwd(16, 16, 16, 16, None, 16, 2, 64, 64), 1),
+        (lambda: us.attention_bwd(16, 16, 16, 16, 16, 16, 16, 16, 16, 16, None, 2, 64, 64), 1),
         (lambda: us.gelu_tables(None, 1 << 20), 1),
         (lambda: us.gelu_tables(16, 1000), 5),                       # smaller than the table area
         (lambda: us.gelu_tables(24, 1 << 20), 3),
