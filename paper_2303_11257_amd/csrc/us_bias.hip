@@ -121,11 +121,13 @@ hipError_t launch_bias_grad(const void* G, us_dtype g_dt, void* dc, long b, long
   dim3 grid((unsigned)nblocks, (unsigned)((cpr + 255) / 256), 1);
   float* partial = (float*)workspace;
   const uint8_t* g = (const uint8_t*)G;
-  if (g_dt == US_F16) colsum_kernel<US_F16><<<grid, kThreads, 0, st>>>(g, partial, b, n, cpr, cw, rs);
-  else if (g_dt == US_E4M3) colsum_kernel<US_E4M3><<<grid, kThreads, 0, st>>>(g, partial, b, n, cpr, cw, rs);
-  else colsum_kernel<US_E5M2><<<grid, kThreads, 0, st>>>(g, partial, b, n, cpr, cw, rs);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (nblocks > 0) {                       // no rows: the sums are empty and the second kernel writes zeros
+    if (g_dt == US_F16) colsum_kernel<US_F16><<<grid, kThreads, 0, st>>>(g, partial, b, n, cpr, cw, rs);
+    else if (g_dt == US_E4M3) colsum_kernel<US_E4M3><<<grid, kThreads, 0, st>>>(g, partial, b, n, cpr, cw, rs);
+    else colsum_kernel<US_E5M2><<<grid, kThreads, 0, st>>>(g, partial, b, n, cpr, cw, rs);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   colsum_reduce_kernel<<<(unsigned)(n / 16), 256, 0, st>>>(partial, (_Float16*)dc, nblocks, n, beta);
   return hipGetLastError();
 }

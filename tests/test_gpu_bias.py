@@ -153,6 +153,12 @@ def test_bias_grad_against_the_oracle(shape, fmt):
     assert np.array_equal(_bits(dc), _bits(_bias_grad(Gop, gdt)))                            # fixed order of additions
 
 
+def test_bias_grad_of_no_rows_is_zero():
+    dc = torch.full((48,), 7.0, dtype=torch.float16, device=DEV)
+    us.bias_grad(None, us.F16, ptr(dc), 0, 48, 0.0, None, 0, stream())
+    assert not to_np(dc).any()
+
+
 def test_bias_grad_exact_integers():
     b, n = 1000, 304
     G = synth.small_ints(76, synth.T_G, (b, n))
