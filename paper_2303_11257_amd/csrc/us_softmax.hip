@@ -137,11 +137,24 @@ __global__ void __launch_bounds__(kThreads) xent_kernel(const _Float16* X, const
       continue;
     }
     float m = -__builtin_inff();
-    for (int i = threadIdx.x; i < nchunks; i += kThreads) {
-      const v8h v = *reinterpret_cast<const v8h*>(X + r * s + i * 8);
-      *reinterpret_cast<v8h*>(row + i * 8) = v;
+    // eight 16-byte loads per thread are requested before the first is used: with two workgroups per CU (the rows
+    // fill the LDS) the bytes in flight have to come from each thread
+    for (int i0 = threadIdx.x; i0 < nchunks; i0 += 8 * kThreads) {
+      v8h v[8];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) m = __builtin_fmaxf(m, s1 * (float)v[q]);
+      for (int u = 0; u < 8; ++u) {
+        const int i = i0 + u * kThreads;
+        if (i < nchunks) v[u] = *reinterpret_cast<const v8h*>(X + r * s + i * 8);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = i0 + u * kThreads;
+        if (i < nchunks) {
+          *reinterpret_cast<v8h*>(row + i * 8) = v[u];
+#pragma unroll
+          for (int q = 0; q < 8; ++q) m = __builtin_fmaxf(m, s1 * (float)v[u][q]);
+        }
+      }
     }
     m = block_max(m, scratch);                          // (its barriers also publish the row in LDS)
     float sum = 0.0f;
