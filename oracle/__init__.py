@@ -59,6 +59,10 @@ def _load():
     lib.uso_linear_bias_fwd.restype = i
     lib.uso_bias_grad.argtypes = [vp, i, vp, i, l, l, f]
     lib.uso_bias_grad.restype = None
+    lib.uso_sum_fwd.argtypes = [vp, vp, l, l, f]
+    lib.uso_sum_fwd.restype = None
+    lib.uso_sum_bwd.argtypes = [vp, vp, l, l, f]
+    lib.uso_sum_bwd.restype = None
     lib.uso_softmax_fwd.argtypes = [vp, vp, l, l, f, f]
     lib.uso_softmax_fwd.restype = None
     lib.uso_softmax_bwd.argtypes = [vp, vp, vp, l, l, f, f]
@@ -464,6 +468,33 @@ def cast_snr(a: np.ndarray, dst_dt: int, scale: float = 1.0):
     sums = np.zeros(2, np.float64)
     _load().uso_cast_snr(_p(a), _dt_of(a, None), a.size, dst_dt, float(np.float32(scale)), _p(sums))
     return float(sums[0]), float(sums[1])
+
+
+# ---- scaled sum over the last dimension (Table A.2 "Linear") -------------------------------------------------------
+def sum_scales(n: int):
+    """(alpha, beta) = (n^-1/2, 1)."""
+    return np.float32(1.0 / math.sqrt(n)), np.float32(1.0)
+
+
+def sum_fwd(x, alpha=None):
+    """y[rows] = round(alpha * sum over the last dimension of FP16 x[rows, n])."""
+    x = _c(x)
+    assert x.dtype == np.float16 and x.ndim == 2
+    rows, n = x.shape
+    if alpha is None:
+        alpha = sum_scales(n)[0]
+    y = np.empty(rows, np.float16)
+    _load().uso_sum_fwd(_p(x), _p(y), rows, n, float(np.float32(alpha)))
+    return y
+
+
+def sum_bwd(g, n: int, beta=1.0):
+    """dx[rows, n] = round(beta * g[rows]) in every column."""
+    g = _c(g)
+    assert g.dtype == np.float16 and g.ndim == 1
+    dx = np.empty((g.shape[0], n), np.float16)
+    _load().uso_sum_bwd(_p(g), _p(dx), g.shape[0], n, float(np.float32(beta)))
+    return dx
 
 
 # ---- scaled softmax and softmax cross-entropy (Table A.2 "Other", App. G) ---------------------------------

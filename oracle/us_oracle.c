@@ -502,6 +502,26 @@ void uso_weighted_add2(const void* a, const void* b, void* out, size_t n, int dt
 }
 
 /*
+ * ---- scaled sum over the last dimension (Table A.2 "Linear": sum(x) = sum_i x_i, alpha = n^-1/2, beta = 1) -----
+ *   fwd  y_i   = round( alpha * sum_{j<n} x_ij )      double sum in index order
+ *   bwd  dx_ij = round( beta * g_i )                  the gradient of a sum is its incoming gradient in every place
+ */
+void uso_sum_fwd(const void* x, void* y, long rows, long n, float alpha) {
+  for (long i = 0; i < rows; ++i) {
+    double acc = 0.0;
+    for (long j = 0; j < n; ++j) acc += uso_decode_bits(load_bits(x, ODT_F16, (size_t)(i * n + j)), ODT_F16);
+    store_bits(y, ODT_F16, (size_t)i, round_out((double)alpha * acc, ODT_F16));
+  }
+}
+
+void uso_sum_bwd(const void* g, void* dx, long rows, long n, float beta) {
+  for (long i = 0; i < rows; ++i) {
+    const uint32_t b = round_out((double)beta * uso_decode_bits(load_bits(g, ODT_F16, (size_t)i), ODT_F16), ODT_F16);
+    for (long j = 0; j < n; ++j) store_bits(dx, ODT_F16, (size_t)(i * n + j), b);
+  }
+}
+
+/*
  * ---- scaled softmax and softmax cross-entropy (Table A.2 "Other"; App. G "Softmax (followed by matmul)",
  *      "Softmax cross-entropy"; App. H "Softmax functions" for the input factor s1) --------------------
  * Rows of s values, FP16 storage, double arithmetic, one rounding per output.
