@@ -365,6 +365,8 @@ def main():
         xl = torch.empty(xr, dtype=torch.float32, device="cuda:0")
         ms = time_steps(torch, lambda: us.softmax_xent(za.data_ptr(), xt.data_ptr(), xl.data_ptr(), zo.data_ptr(), xr, xs, 0.0, 0.0, st), 50, 5)
         ew["softmax_xent_GBps"] = round(4.0 * xr * xs / (ms * 1e-3) * 1e-9, 1)
+        ms = time_steps(torch, lambda: us.sum_fwd(za.data_ptr(), zo.data_ptr(), sb, ss, 0.0, st), 50, 5)
+        ew["sum_fwd_GBps"] = round(2.0 * n / (ms * 1e-3) * 1e-9, 1)
         # diagnostics: read-only, 2 B / element
         hist = torch.zeros(us.HIST_BINS, dtype=torch.int64, device="cuda:0")
         sums = torch.zeros(2, dtype=torch.float64, device="cuda:0")

@@ -377,6 +377,15 @@ us_status us_attention_bwd(const void* Q, const void* K, const void* V, const vo
                            void* dP, void* dA, void* dQ, void* dK, void* dV, long heads, long s, long d,
                            void* stream);
 
+/*
+ * Scaled sum over the last dimension (Table A.2 "Linear": sum(x), alpha = n^-1/2, beta = 1).
+ *   fwd:  Y[i]    = fp16( alpha * sum_j X[i,j] )     X FP16 [rows, n] (16-byte aligned), Y FP16 [rows]; alpha <= 0: n^-1/2
+ *   bwd:  dX[i,j] = fp16( beta * G[i] )              G FP16 [rows], dX FP16 [rows, n] (16-byte aligned); beta <= 0: 1
+ * n a multiple of 8 (US_ERR_SHAPE otherwise); n = 0 gives Y = 0.  FP32 sum in a fixed order.
+ */
+us_status us_sum_fwd(const void* X, void* Y, long rows, long n, float alpha, void* stream);
+us_status us_sum_bwd(const void* G, void* dX, long rows, long n, float beta, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
     L.us_matmul_batched.argtypes = [vp, vp, vp, l, l, l, l, i, i, i, i, i, f, vp]
     L.us_attention_fwd.argtypes = [vp] * 6 + [l, l, l, vp]
     L.us_attention_bwd.argtypes = [vp] * 11 + [l, l, l, vp]
+    L.us_sum_fwd.argtypes = [vp, vp, l, l, f, vp]
+    L.us_sum_bwd.argtypes = [vp, vp, l, l, f, vp]
     L.us_softmax_fwd.argtypes = [vp, vp, l, l, f, f, vp]
     L.us_softmax_bwd.argtypes = [vp, vp, vp, l, l, f, f, vp]
     L.us_softmax_xent.argtypes = [vp, vp, vp, vp, l, l, f, f, vp]
@@ -89,7 +91,7 @@ def lib() -> ctypes.CDLL:
     for name in ("us_linear_scales", "us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd",
                  "us_gelu_tables", "us_ffn_fwd", "us_ffn_bwd", "us_weighted_add", "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd", "us_layer_norm_fwd", "us_layer_norm_bwd", "us_exponent_histogram", "us_cast_snr",
                  "us_linear_bias_fwd", "us_bias_grad", "us_ffn_bias_fwd", "us_ffn_bias_bwd", "us_softmax_fwd", "us_softmax_bwd",
-                 "us_softmax_xent", "us_matmul_batched", "us_attention_fwd", "us_attention_bwd"):
+                 "us_softmax_xent", "us_matmul_batched", "us_attention_fwd", "us_attention_bwd", "us_sum_fwd", "us_sum_bwd"):
         getattr(L, name).restype = i
     _lib = L
     return L
@@ -219,6 +221,14 @@ def attention_fwd(Q, K, V, A, P, O, heads, s, d, stream=None):
 
 def attention_bwd(Q, K, V, A, P, dO, dP, dA, dQ, dK, dV, heads, s, d, stream=None):
     _check(lib().us_attention_bwd(Q, K, V, A, P, dO, dP, dA, dQ, dK, dV, heads, s, d, stream), "us_attention_bwd")
+
+
+def sum_fwd(X, Y, rows, n, alpha=0.0, stream=None):
+    _check(lib().us_sum_fwd(X, Y, rows, n, alpha, stream), "us_sum_fwd")
+
+
+def sum_bwd(G, dX, rows, n, beta=0.0, stream=None):
+    _check(lib().us_sum_bwd(G, dX, rows, n, beta, stream), "us_sum_bwd")
 
 
 def softmax_fwd(X, Y, rows, s, s1=0.0, alpha=0.0, stream=None):

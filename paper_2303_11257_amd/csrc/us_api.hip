@@ -510,4 +510,21 @@ us_status us_attention_bwd(const void* Q, const void* K, const void* V, const vo
   return us_matmul_batched(dA, Q, dK, heads, s, d, s, 1, 0, US_F16, US_F16, US_F16, rs, stream);
 }
 
+us_status us_sum_fwd(const void* X, void* Y, long rows, long n, float alpha, void* stream) {
+  if (rows < 0 || n < 0 || n % 8 != 0 || n > (1L << 30)) return US_ERR_SHAPE;
+  if (rows == 0) return US_OK;
+  if (!Y || (n > 0 && !X)) return US_ERR_NULL;
+  if (!aligned16(X) || ((uintptr_t)Y & 1)) return US_ERR_ALIGN;
+  const float a = alpha > 0.0f ? alpha : (float)(1.0 / sqrt((double)(n > 0 ? n : 1)));
+  return from_hip(launch_sum_fwd(X, Y, rows, n, a, as_stream(stream)));
+}
+
+us_status us_sum_bwd(const void* G, void* dX, long rows, long n, float beta, void* stream) {
+  if (rows < 0 || n < 0 || n % 8 != 0 || n > (1L << 30)) return US_ERR_SHAPE;
+  if (rows == 0 || n == 0) return US_OK;
+  if (!G || !dX) return US_ERR_NULL;
+  if (!aligned16(dX) || ((uintptr_t)G & 1)) return US_ERR_ALIGN;
+  return from_hip(launch_sum_bwd(G, dX, rows, n, beta > 0.0f ? beta : 1.0f, as_stream(stream)));
+}
+
 }  // extern "C"

@@ -28,6 +28,8 @@ hipError_t launch_layer_norm_fwd(const void* X, const void* w, const void* c, vo
 hipError_t launch_layer_norm_bwd(const void* X, const void* w, const void* G, void* dX, void* dw, void* dc, long b, long n, float eps,
                                  float beta_wc, void* workspace, hipStream_t stream);
 
+hipError_t launch_sum_fwd(const void* X, void* Y, long rows, long n, float alpha, hipStream_t stream);
+hipError_t launch_sum_bwd(const void* G, void* dX, long rows, long n, float beta, hipStream_t stream);
 hipError_t launch_softmax_fwd(const void* X, void* Y, long rows, long s, float s1, float alpha, hipStream_t stream);
 hipError_t launch_softmax_bwd(const void* X, const void* G, void* dX, long rows, long s, float s1, float beta, hipStream_t stream);
 hipError_t launch_softmax_xent(const void* X, const int* target, float* loss, void* dX, long rows, long s, float s1, float beta,

@@ -1,4 +1,4 @@
-// Scaled softmax over the last dimension and softmax cross-entropy (Table A.2 "Other"; App. G "Softmax (followed
+// Scaled softmax over the last dimension, softmax cross-entropy and the scaled sum (Table A.2 "Other"; App. G "Softmax (followed
 // by matmul)", "Softmax cross-entropy").  HBM-bound row kernels, FP16 storage, FP32 arithmetic, every tensor read
 // or written once:
 //   softmax forward   y = alpha * softmax(s1 x)                          4 B / element   (alpha = s by default)
@@ -182,6 +182,39 @@ __global__ void __launch_bounds__(kThreads) xent_kernel(const _Float16* X, const
   }
 }
 
+// Scaled sum over the last dimension (Table A.2 "Linear": alpha = n^-1/2, beta = 1).  One wave per row; a lane adds every
+// 64th 16-byte chunk, then the lanes are added by the butterfly: a fixed order, 2 B / element read.
+__global__ void __launch_bounds__(kThreads) sum_fwd_kernel(const _Float16* X, _Float16* Y, long rows, int n, float alpha) {
+  const int lane = threadIdx.x & 63;
+  const long wave0 = (long)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+  const long nwaves = (long)gridDim.x * (kThreads / 64);
+  const int nchunks = n / 8;
+  for (long row = wave0; row < rows; row += nwaves) {
+    const _Float16* x = X + row * n;
+    float acc = 0.0f;
+    for (int i = lane; i < nchunks; i += 64) {
+      const v8h v = *reinterpret_cast<const v8h*>(x + i * 8);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) acc += (float)v[q];
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) Y[row] = to_half(alpha * acc);
+  }
+}
+
+// Its backward pass: dx_ij = beta * g_i in every column (write-only, 2 B / element).
+__global__ void __launch_bounds__(kThreads) sum_bwd_kernel(const _Float16* G, _Float16* dX, long rows, int n, float beta) {
+  const int lane = threadIdx.x & 63;
+  const long wave0 = (long)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+  const long nwaves = (long)gridDim.x * (kThreads / 64);
+  const int nchunks = n / 8;
+  for (long row = wave0; row < rows; row += nwaves) {
+    const _Float16 b = to_half(beta * (float)G[row]);
+    const v8h o = {b, b, b, b, b, b, b, b};
+    for (int i = lane; i < nchunks; i += 64) *reinterpret_cast<v8h*>(dX + row * n + i * 8) = o;
+  }
+}
+
 int grid_rows(long rows) {
   long g = (rows + kThreads / 64 - 1) / (kThreads / 64);
   if (g > 256 * 16) g = 256 * 16;
@@ -189,6 +222,16 @@ int grid_rows(long rows) {
 }
 
 }  // namespace
+
+hipError_t launch_sum_fwd(const void* X, void* Y, long rows, long n, float alpha, hipStream_t st) {
+  sum_fwd_kernel<<<grid_rows(rows), kThreads, 0, st>>>((const _Float16*)X, (_Float16*)Y, rows, (int)n, alpha);
+  return hipGetLastError();
+}
+
+hipError_t launch_sum_bwd(const void* G, void* dX, long rows, long n, float beta, hipStream_t st) {
+  sum_bwd_kernel<<<grid_rows(rows), kThreads, 0, st>>>((const _Float16*)G, (_Float16*)dX, rows, (int)n, beta);
+  return hipGetLastError();
+}
 
 hipError_t launch_softmax_fwd(const void* X, void* Y, long rows, long s, float s1, float alpha, hipStream_t st) {
   const _Float16* x = (const _Float16*)X;

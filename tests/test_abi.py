@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported():
             "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd", "us_layer_norm_fwd", "us_layer_norm_bwd",
             "us_layer_norm_workspace_bytes", "us_exponent_histogram", "us_cast_snr", "us_linear_bias_fwd", "us_bias_grad",
             "us_bias_grad_workspace_bytes", "us_ffn_bias_fwd", "us_ffn_bias_bwd", "us_ffn_bias_workspace_bytes", "us_softmax_fwd", "us_softmax_bwd", "us_softmax_xent", "us_matmul_batched",
-            "us_attention_fwd", "us_attention_bwd"} <= set(names)
+            "us_attention_fwd", "us_attention_bwd", "us_sum_fwd", "us_sum_bwd"} <= set(names)
     L = ctypes.CDLL(us.library_path())
     for n in names:
         assert hasattr(L, n), n
@@ -123,6 +123,9 @@ def test_argument_errors_are_detected_on_the_host():
         (lambda: us.attention_fwd(16, 16, 16, 16, 16, 16, 2, 8192, 64), 2),                                # rows longer than the softmax takes
         (lambda: us.attention_fwd(16, 16, 16, 16, None, 16, 2, 64, 64), 1),
         (lambda: us.attention_bwd(16, 16, 16, 16, 16, 16, 16, 16, 16, 16, None, 2, 64, 64), 1),
+        (lambda: us.sum_fwd(16, 16, 4, 12), 2),
+        (lambda: us.sum_fwd(16, None, 4, 16), 1),
+        (lambda: us.sum_bwd(16, 24, 4, 16), 3),
         (lambda: us.gelu_tables(None, 1 << 20), 1),
         (lambda: us.gelu_tables(16, 1000), 5),                       # smaller than the table area
         (lambda: us.gelu_tables(24, 1 << 20), 3),
