@@ -367,7 +367,8 @@ us_status us_softmax_xent(const void* X, const int* target, float* loss, void* d
  *   bwd:  dV = fp16(s^-1/2 P^T dO)  dP = fp16(d^-1/2 dO V^T)  dA = fp16(s * p (dP - sum p dP))
  *         dQ = fp16(s^-1/2 dA K)    dK = fp16(s^-1/2 dA^T Q)
  * Q, K, V, O, dO, dQ, dK, dV: FP16 [heads, s, d]; A, P, dP, dA: FP16 [heads, s, s]; all device, 16-byte aligned; s and d
- * multiples of 16, s <= US_SOFTMAX_MAX.  A and P are stored by the forward call and read by the backward call.
+ * multiples of 16, s <= US_SOFTMAX_MAX, heads <= 65535.  A and P are stored by the forward call and read by the
+ * backward call.
  */
 us_status us_matmul_batched(const void* A, const void* B, void* C, long batch, long M, long N, long K, int trans_a,
                             int trans_b, us_dtype a_dt, us_dtype b_dt, us_dtype c_dt, float scale, void* stream);
