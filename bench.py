@@ -354,16 +354,19 @@ def main():
         ms = time_steps(torch, lambda: us.bias_grad(za.data_ptr(), us.F16, ldc.data_ptr(), lb, ln, 0.0, bws.data_ptr(), bwsb, st), 50, 5)
         ew["bias_grad_GBps"] = round(2.0 * n / (ms * 1e-3) * 1e-9, 1)
         # scaled softmax on [65536, 512] (attention rows): 4 B / element forward, 6 B backward; cross-entropy on
-        # [1024, 30528] (a BERT vocabulary, padded to a multiple of 8): loss and gradient, 4 B / element
+        # [8192, 30528] (a BERT vocabulary, padded to a multiple of 8): loss and gradient, 4 B / element
         sb, ss = n // 512, 512
         ms = time_steps(torch, lambda: us.softmax_fwd(za.data_ptr(), zo.data_ptr(), sb, ss, 0.0, 0.0, st), 50, 5)
         ew["softmax_fwd_GBps"] = round(4.0 * n / (ms * 1e-3) * 1e-9, 1)
         ms = time_steps(torch, lambda: us.softmax_bwd(za.data_ptr(), zb.data_ptr(), zo.data_ptr(), sb, ss, 0.0, 0.0, st), 50, 5)
         ew["softmax_bwd_GBps"] = round(6.0 * n / (ms * 1e-3) * 1e-9, 1)
-        xr, xs = 1024, 30528
+        xr, xs = 8192, 30528                      # the tokens of the C3 batch against a BERT vocabulary
+        xa = torch.randn((xr, xs), dtype=torch.float16, device="cuda:0")
+        xo = torch.empty_like(xa)
         xt = torch.randint(0, xs, (xr,), dtype=torch.int32, device="cuda:0")
         xl = torch.empty(xr, dtype=torch.float32, device="cuda:0")
-        ms = time_steps(torch, lambda: us.softmax_xent(za.data_ptr(), xt.data_ptr(), xl.data_ptr(), zo.data_ptr(), xr, xs, 0.0, 0.0, st), 50, 5)
+        ms = time_steps(torch, lambda: us.softmax_xent(xa.data_ptr(), xt.data_ptr(), xl.data_ptr(), xo.data_ptr(), xr, xs, 0.0, 0.0, st), 20, 3)
+        del xa, xo
         ew["softmax_xent_GBps"] = round(4.0 * xr * xs / (ms * 1e-3) * 1e-9, 1)
         ms = time_steps(torch, lambda: us.sum_fwd(za.data_ptr(), zo.data_ptr(), sb, ss, 0.0, st), 50, 5)
         ew["sum_fwd_GBps"] = round(2.0 * n / (ms * 1e-3) * 1e-9, 1)
