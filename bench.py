@@ -327,38 +327,39 @@ def main():
                                           "(column sums of G and of the FP16 dZ, which is then stored as well)",
                                   "ms_per_step": ms_b, "TFLOPs": ffn.flop / (ms_b * 1e-3) * 1e-12}
     if not args.no_secondary:
-        # stand-alone elementwise kernels (HBM bound): 32 Mi FP16 elements, algorithmic bytes 4 B (forward) / 6 B (backward) / 6 B (add)
-        n = 32 << 20
+        # stand-alone elementwise kernels (HBM bound): 256 Mi FP16 elements (512 MB per tensor: twice the 256 MB last-level
+        # cache, so the rates are HBM's), algorithmic bytes 4 B (forward) / 6 B (backward) / 6 B (add)
+        n = 256 << 20
         za, zb, zo = (torch.randn(n, dtype=torch.float16, device="cuda:0") for _ in range(3))
         st = torch.cuda.current_stream().cuda_stream
         ew = {}
         for name, kind in (("gelu", us.ACT_GELU), ("relu", us.ACT_RELU), ("tanh", us.ACT_TANH), ("sigmoid", us.ACT_SIGMOID)):
-            ms = time_steps(torch, lambda: us.act_fwd(za.data_ptr(), zo.data_ptr(), n, us.F16, kind, 0.0, 0.0, st), 50, 5)
+            ms = time_steps(torch, lambda: us.act_fwd(za.data_ptr(), zo.data_ptr(), n, us.F16, kind, 0.0, 0.0, st), 20, 3)
             ew[name + "_fwd_GBps"] = round(4.0 * n / (ms * 1e-3) * 1e-9, 1)
-            ms = time_steps(torch, lambda: us.act_bwd(za.data_ptr(), zb.data_ptr(), zo.data_ptr(), n, us.F16, kind, 0.0, 0.0, st), 50, 5)
+            ms = time_steps(torch, lambda: us.act_bwd(za.data_ptr(), zb.data_ptr(), zo.data_ptr(), n, us.F16, kind, 0.0, 0.0, st), 20, 3)
             ew[name + "_bwd_GBps"] = round(6.0 * n / (ms * 1e-3) * 1e-9, 1)
-        ms = time_steps(torch, lambda: us.weighted_add(za.data_ptr(), zb.data_ptr(), zo.data_ptr(), n, us.F16, 0.8, 0.6, st), 50, 5)
+        ms = time_steps(torch, lambda: us.weighted_add(za.data_ptr(), zb.data_ptr(), zo.data_ptr(), n, us.F16, 0.8, 0.6, st), 20, 3)
         ew["weighted_add_GBps"] = round(6.0 * n / (ms * 1e-3) * 1e-9, 1)
-        # scaled layer norm on [32768, 1024] FP16 (the BERT-large hidden size): 4 B / element forward, 6 B backward
+        # scaled layer norm on [262144, 1024] FP16 (the BERT-large hidden size): 4 B / element forward, 6 B backward
         lb, ln = n // 1024, 1024
         lw, lc, ldw, ldc = (torch.ones(ln, dtype=torch.float16, device="cuda:0") for _ in range(4))
         lwsb = us.layer_norm_workspace_bytes(lb, ln)
         lws = torch.empty(lwsb, dtype=torch.uint8, device="cuda:0")
-        ms = time_steps(torch, lambda: us.layer_norm_fwd(za.data_ptr(), lw.data_ptr(), lc.data_ptr(), zo.data_ptr(), lb, ln, 1e-5, st), 50, 5)
+        ms = time_steps(torch, lambda: us.layer_norm_fwd(za.data_ptr(), lw.data_ptr(), lc.data_ptr(), zo.data_ptr(), lb, ln, 1e-5, st), 20, 3)
         ew["layer_norm_fwd_GBps"] = round(4.0 * n / (ms * 1e-3) * 1e-9, 1)
         ms = time_steps(torch, lambda: us.layer_norm_bwd(za.data_ptr(), lw.data_ptr(), zb.data_ptr(), zo.data_ptr(), ldw.data_ptr(),
-                                                         ldc.data_ptr(), lb, ln, 1e-5, 0.0, lws.data_ptr(), lwsb, st), 50, 5)
+                                                         ldc.data_ptr(), lb, ln, 1e-5, 0.0, lws.data_ptr(), lwsb, st), 20, 3)
         ew["layer_norm_bwd_GBps"] = round(6.0 * n / (ms * 1e-3) * 1e-9, 1)
         bwsb = us.bias_grad_workspace_bytes(lb, ln)
         bws = torch.empty(bwsb, dtype=torch.uint8, device="cuda:0")
-        ms = time_steps(torch, lambda: us.bias_grad(za.data_ptr(), us.F16, ldc.data_ptr(), lb, ln, 0.0, bws.data_ptr(), bwsb, st), 50, 5)
+        ms = time_steps(torch, lambda: us.bias_grad(za.data_ptr(), us.F16, ldc.data_ptr(), lb, ln, 0.0, bws.data_ptr(), bwsb, st), 20, 3)
         ew["bias_grad_GBps"] = round(2.0 * n / (ms * 1e-3) * 1e-9, 1)
-        # scaled softmax on [65536, 512] (attention rows): 4 B / element forward, 6 B backward; cross-entropy on
+        # scaled softmax on [524288, 512] (attention rows): 4 B / element forward, 6 B backward; cross-entropy on
         # [8192, 30528] (a BERT vocabulary, padded to a multiple of 8): loss and gradient, 4 B / element
         sb, ss = n // 512, 512
-        ms = time_steps(torch, lambda: us.softmax_fwd(za.data_ptr(), zo.data_ptr(), sb, ss, 0.0, 0.0, st), 50, 5)
+        ms = time_steps(torch, lambda: us.softmax_fwd(za.data_ptr(), zo.data_ptr(), sb, ss, 0.0, 0.0, st), 20, 3)
         ew["softmax_fwd_GBps"] = round(4.0 * n / (ms * 1e-3) * 1e-9, 1)
-        ms = time_steps(torch, lambda: us.softmax_bwd(za.data_ptr(), zb.data_ptr(), zo.data_ptr(), sb, ss, 0.0, 0.0, st), 50, 5)
+        ms = time_steps(torch, lambda: us.softmax_bwd(za.data_ptr(), zb.data_ptr(), zo.data_ptr(), sb, ss, 0.0, 0.0, st), 20, 3)
         ew["softmax_bwd_GBps"] = round(6.0 * n / (ms * 1e-3) * 1e-9, 1)
         xr, xs = 8192, 30528                      # the tokens of the C3 batch against a BERT vocabulary
         xa = torch.randn((xr, xs), dtype=torch.float16, device="cuda:0")
@@ -368,16 +369,20 @@ def main():
         ms = time_steps(torch, lambda: us.softmax_xent(xa.data_ptr(), xt.data_ptr(), xl.data_ptr(), xo.data_ptr(), xr, xs, 0.0, 0.0, st), 20, 3)
         del xa, xo
         ew["softmax_xent_GBps"] = round(4.0 * xr * xs / (ms * 1e-3) * 1e-9, 1)
-        ms = time_steps(torch, lambda: us.sum_fwd(za.data_ptr(), zo.data_ptr(), sb, ss, 0.0, st), 50, 5)
+        ms = time_steps(torch, lambda: us.sum_fwd(za.data_ptr(), zo.data_ptr(), sb, ss, 0.0, st), 20, 3)
         ew["sum_fwd_GBps"] = round(2.0 * n / (ms * 1e-3) * 1e-9, 1)
         # diagnostics: read-only, 2 B / element
         hist = torch.zeros(us.HIST_BINS, dtype=torch.int64, device="cuda:0")
         sums = torch.zeros(2, dtype=torch.float64, device="cuda:0")
-        ms = time_steps(torch, lambda: us.exponent_histogram(za.data_ptr(), us.F16, n, hist.data_ptr(), st), 50, 5)
+        ms = time_steps(torch, lambda: us.exponent_histogram(za.data_ptr(), us.F16, n, hist.data_ptr(), st), 20, 3)
         ew["exponent_histogram_GBps"] = round(2.0 * n / (ms * 1e-3) * 1e-9, 1)
-        ms = time_steps(torch, lambda: us.cast_snr(za.data_ptr(), us.F16, n, us.E4M3, 1.0, sums.data_ptr(), st), 50, 5)
+        ms = time_steps(torch, lambda: us.cast_snr(za.data_ptr(), us.F16, n, us.E4M3, 1.0, sums.data_ptr(), st), 20, 3)
         ew["cast_snr_GBps"] = round(2.0 * n / (ms * 1e-3) * 1e-9, 1)
         ew["snr_e4m3_unit_normal"] = round(float(sums[0] / sums[1]), 1)
+        # the same two on a tensor that fits the last-level cache (32 Mi elements): fixed costs show
+        ns = 32 << 20
+        ms = time_steps(torch, lambda: us.exponent_histogram(za.data_ptr(), us.F16, ns, hist.data_ptr(), st), 20, 3)
+        ew["exponent_histogram_64MB_GBps"] = round(2.0 * ns / (ms * 1e-3) * 1e-9, 1)
         ew["peak_GBps"] = PEAK_HBM_GBS
         out["elementwise"] = ew
         del za, zb, zo
@@ -394,7 +399,7 @@ def main():
         def attn_step():
             us.attention_fwd(dp(aq), dp(ak), dp(av), dp(aA), dp(aP), dp(aO), ah, as_, ad, st)
             us.attention_bwd(dp(aq), dp(ak), dp(av), dp(aA), dp(aP), dp(ado), dp(adP), dp(adA), dp(adQ), dp(adK), dp(adV), ah, as_, ad, st)
-        ms_a = time_steps(torch, attn_step, 50, 5)
+        ms_a = time_steps(torch, attn_step, 20, 3)
         a_flop = 12.0 * as_ * as_ * ad * ah
         # [heads, s, s] tensors: A written + read twice, P written + read twice, dP written + read, dA written + read twice
         a_bytes = 11.0 * ah * as_ * as_ * 2

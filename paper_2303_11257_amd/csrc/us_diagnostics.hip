@@ -106,8 +106,13 @@ int grid_for(size_t nvec) {
 }  // namespace
 
 hipError_t launch_exponent_histogram(const void* src, us_dtype dt, size_t n, unsigned long long* hist, hipStream_t st) {
-  if (dt == US_F16) histogram_kernel<_Float16><<<grid_for(n / 8), kThreads, 0, st>>>((const _Float16*)src, n, hist);
-  else histogram_kernel<float><<<grid_for(n / 4), kThreads, 0, st>>>((const float*)src, n, hist);
+  // every workgroup ends with 35 atomics on the same 35 counters: at least 64 Ki elements per workgroup keep that
+  // tail short on small tensors
+  const size_t by_work = n / 65536 + 1;
+  int g = grid_for(dt == US_F16 ? n / 8 : n / 4);
+  if ((size_t)g > by_work) g = (int)by_work;
+  if (dt == US_F16) histogram_kernel<_Float16><<<g, kThreads, 0, st>>>((const _Float16*)src, n, hist);
+  else histogram_kernel<float><<<g, kThreads, 0, st>>>((const float*)src, n, hist);
   return hipGetLastError();
 }
 
