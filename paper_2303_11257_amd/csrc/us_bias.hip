@@ -10,7 +10,7 @@ namespace us {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kRowsPerBlock = 32;
+constexpr int kRowsPerBlock = 32;      // fewest rows a workgroup sums (sizes the scratch); more when there are many rows
 
 template <int DT, int V>
 __device__ __forceinline__ void add_chunk(float (&acc)[V], const v4i& raw) {
@@ -40,7 +40,7 @@ __device__ __forceinline__ void add_chunk(float (&acc)[V], const v4i& raw) {
 // cpr = chunks per row, CW = chunks this block covers (at most 256), RS = 256 / CW rows side by side.
 template <int DT>
 __global__ void __launch_bounds__(kThreads) colsum_kernel(const uint8_t* G, float* partial, long b, long n, int cpr, int cw_count,
-                                                          int rs) {
+                                                          int rs, int rows_per_block) {
   constexpr int V = DT == US_F16 ? 8 : 16;
   __shared__ float red[kThreads * V];
   const int cw = threadIdx.x % cw_count, rsub = threadIdx.x / cw_count;
@@ -48,8 +48,8 @@ __global__ void __launch_bounds__(kThreads) colsum_kernel(const uint8_t* G, floa
   const bool active = rsub < rs && chunk < cpr;
   float acc[V] = {};
   if (active) {
-    const long row0 = (long)blockIdx.x * kRowsPerBlock;
-    const long row1 = row0 + kRowsPerBlock < b ? row0 + kRowsPerBlock : b;
+    const long row0 = (long)blockIdx.x * rows_per_block;
+    const long row1 = row0 + rows_per_block < b ? row0 + rows_per_block : b;
     const size_t pitch = (size_t)cpr * 16;
     const uint8_t* p = G + (size_t)chunk * 16;
     long r = row0 + rsub;
@@ -117,14 +117,17 @@ hipError_t launch_bias_grad(const void* G, us_dtype g_dt, void* dc, long b, long
   const int cpr = (int)(n * es / 16);
   const int cw = cpr < 256 ? cpr : 256;
   const int rs = 256 / cw;
-  const int nblocks = (int)((b + kRowsPerBlock - 1) / kRowsPerBlock);
+  // at most 2048 workgroups: beyond that each takes more rows (a multiple of the minimum, so the scratch suffices)
+  long rpb = kRowsPerBlock;
+  while ((b + rpb - 1) / rpb > 2048) rpb *= 2;
+  const int nblocks = (int)((b + rpb - 1) / rpb);
   dim3 grid((unsigned)nblocks, (unsigned)((cpr + 255) / 256), 1);
   float* partial = (float*)workspace;
   const uint8_t* g = (const uint8_t*)G;
   if (nblocks > 0) {                       // no rows: the sums are empty and the second kernel writes zeros
-    if (g_dt == US_F16) colsum_kernel<US_F16><<<grid, kThreads, 0, st>>>(g, partial, b, n, cpr, cw, rs);
-    else if (g_dt == US_E4M3) colsum_kernel<US_E4M3><<<grid, kThreads, 0, st>>>(g, partial, b, n, cpr, cw, rs);
-    else colsum_kernel<US_E5M2><<<grid, kThreads, 0, st>>>(g, partial, b, n, cpr, cw, rs);
+    if (g_dt == US_F16) colsum_kernel<US_F16><<<grid, kThreads, 0, st>>>(g, partial, b, n, cpr, cw, rs, (int)rpb);
+    else if (g_dt == US_E4M3) colsum_kernel<US_E4M3><<<grid, kThreads, 0, st>>>(g, partial, b, n, cpr, cw, rs, (int)rpb);
+    else colsum_kernel<US_E5M2><<<grid, kThreads, 0, st>>>(g, partial, b, n, cpr, cw, rs, (int)rpb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
