@@ -12,7 +12,7 @@ namespace us {
 namespace {
 
 constexpr int kLnThreads = 256;       // four waves, one row each at a time
-constexpr int kLnRowsPerBlock = 32;   // rows whose column sums one workgroup accumulates (backward)
+constexpr int kLnRowsPerBlock = 32;   // fewest rows whose column sums one workgroup accumulates (backward; sizes the scratch)
 
 // mean and 1/sqrt(variance + eps) of the row held in x (two passes over the registers)
 template <int NCH>
@@ -68,10 +68,10 @@ __global__ void __launch_bounds__(kLnThreads) ln_fwd_kernel(const _Float16* X, c
 // into partial[block][2][n] (FP32).  LDS: the four waves' sums before they are added in wave order.
 template <int NCH>
 __global__ void __launch_bounds__(kLnThreads) ln_bwd_kernel(const _Float16* X, const _Float16* w, const _Float16* G, _Float16* dX,
-                                                           float* partial, long b, int n, float eps) {
+                                                           float* partial, long b, int n, float eps, int rows_per_block) {
   extern __shared__ __attribute__((aligned(16))) float red[];     // [4 waves][2][n]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const long row0 = (long)blockIdx.x * kLnRowsPerBlock;
+  const long row0 = (long)blockIdx.x * rows_per_block;
   RowRegs<NCH> wr;
   wr.load(w, n, lane);
   float aw[NCH][8], ac[NCH][8];
@@ -85,13 +85,13 @@ __global__ void __launch_bounds__(kLnThreads) ln_bwd_kernel(const _Float16* X, c
     xn.load(X + (row0 + wave) * n, n, lane);
     gn.load(G + (row0 + wave) * n, n, lane);
   }
-  for (int r = wave; r < kLnRowsPerBlock; r += kLnThreads / 64) {
+  for (int r = wave; r < rows_per_block; r += kLnThreads / 64) {
     const long row = row0 + r;
     if (row >= b) break;
     x = xn;
     g = gn;
     const long next = row + kLnThreads / 64;
-    if (r + kLnThreads / 64 < kLnRowsPerBlock && next < b) {
+    if (r + kLnThreads / 64 < rows_per_block && next < b) {
       xn.load(X + next * n, n, lane);
       gn.load(G + next * n, n, lane);
     }
@@ -207,7 +207,7 @@ hipError_t launch_layer_norm_fwd(const void* X, const void* w, const void* c, vo
 
 template <int NCH>
 static hipError_t launch_bwd(const _Float16* x, const _Float16* w, const _Float16* g, _Float16* dx, float* partial, long b, int n,
-                             float eps, int nblocks, hipStream_t st) {
+                             float eps, int nblocks, int rows_per_block, hipStream_t st) {
   const int lds = (kLnThreads / 64) * 2 * n * (int)sizeof(float);
   static bool configured = false;
   if (!configured) {
@@ -215,7 +215,7 @@ static hipError_t launch_bwd(const _Float16* x, const _Float16* w, const _Float1
     if (e != hipSuccess) return e;
     configured = true;
   }
-  ln_bwd_kernel<NCH><<<nblocks, kLnThreads, lds, st>>>(x, w, g, dx, partial, b, n, eps);
+  ln_bwd_kernel<NCH><<<nblocks, kLnThreads, lds, st>>>(x, w, g, dx, partial, b, n, eps, rows_per_block);
   return hipGetLastError();
 }
 
@@ -223,13 +223,16 @@ hipError_t launch_layer_norm_bwd(const void* X, const void* w, const void* G, vo
                                  float beta_wc, void* workspace, hipStream_t st) {
   const _Float16 *x = (const _Float16*)X, *wp = (const _Float16*)w, *g = (const _Float16*)G;
   const int nch = (int)((n / 8 + 63) / 64);
-  const int nblocks = (int)((b + kLnRowsPerBlock - 1) / kLnRowsPerBlock);
+  // at most 4096 workgroups: beyond that each takes more rows (a multiple of the minimum, so the scratch suffices)
+  long rpb = kLnRowsPerBlock;
+  while ((b + rpb - 1) / rpb > 4096) rpb *= 2;
+  const int nblocks = (int)((b + rpb - 1) / rpb);
   float* partial = (float*)workspace;
   hipError_t e;
-  if (nch <= 1) e = launch_bwd<1>(x, wp, g, (_Float16*)dX, partial, b, (int)n, eps, nblocks, st);
-  else if (nch <= 2) e = launch_bwd<2>(x, wp, g, (_Float16*)dX, partial, b, (int)n, eps, nblocks, st);
-  else if (nch <= 4) e = launch_bwd<4>(x, wp, g, (_Float16*)dX, partial, b, (int)n, eps, nblocks, st);
-  else e = launch_bwd<8>(x, wp, g, (_Float16*)dX, partial, b, (int)n, eps, nblocks, st);
+  if (nch <= 1) e = launch_bwd<1>(x, wp, g, (_Float16*)dX, partial, b, (int)n, eps, nblocks, (int)rpb, st);
+  else if (nch <= 2) e = launch_bwd<2>(x, wp, g, (_Float16*)dX, partial, b, (int)n, eps, nblocks, (int)rpb, st);
+  else if (nch <= 4) e = launch_bwd<4>(x, wp, g, (_Float16*)dX, partial, b, (int)n, eps, nblocks, (int)rpb, st);
+  else e = launch_bwd<8>(x, wp, g, (_Float16*)dX, partial, b, (int)n, eps, nblocks, (int)rpb, st);
   if (e != hipSuccess) return e;
   ln_reduce_kernel<<<(unsigned)(2 * n / 16), 256, 0, st>>>(partial, (_Float16*)dw, (_Float16*)dc, nblocks, (int)n, beta_wc);
   return hipGetLastError();

@@ -36,7 +36,7 @@ def _key(x):
     return np.where(u & 0x8000, -(u & 0x7fff), u)
 
 
-@pytest.mark.parametrize("shape", [(1, 16), (50, 48), (272, 400), (1000, 768), (512, 1024), (131, 2064), (64, 4096)])
+@pytest.mark.parametrize("shape", [(1, 16), (50, 48), (272, 400), (1000, 768), (512, 1024), (131, 2064), (64, 4096), (140001, 16)])
 @pytest.mark.parametrize("eps", [0.0, 1e-5])
 def test_forward_and_backward_against_the_oracle(shape, eps):
     """Row lengths below, at and across the 512-element wave chunk; row counts that are not multiples of the
