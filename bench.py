@@ -258,7 +258,8 @@ def main():
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (the path shards over tokens; see DESIGN.md); use --gpus 1",
+        print("bench.py: this build runs on ONE GPU only (the path would shard over tokens with one all-reduce of the weight "
+              "gradients; that is not built); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
 

@@ -50,8 +50,8 @@ struct DirectTile {
   static_assert(LDS_BYTES <= 160 * 1024, "the ring must fit the CU's 160 KB of LDS");
 };
 
-// XOR mask on the 16-byte chunk index of LDS row `row` (see the bank analysis in the file header of the
-// design notes: 64 banks x 4 B; b128 reads are served 16 lanes at a time, b64 reads 32 lanes).
+// XOR mask on the 16-byte chunk index of LDS row `row`, chosen so that the fragment reads below are free of
+// bank conflicts (64 banks x 4 B; b128 reads are served 16 lanes at a time, b64 reads 32 lanes).
 template <bool KC, bool FP8, int PITCH>
 __device__ __forceinline__ int swz(int row) {
   if constexpr (KC) {
