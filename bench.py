@@ -214,6 +214,53 @@ def time_calls(torch, calls, steps):
     return res
 
 
+
+def pytorch_reference(torch, T, d, f, steps=100, warmup=20):
+    """The same FP8 unit-scaled FFN forward + backward written with PyTorch's own ops on the same GPU (FP8 matmuls through
+    torch._scaled_mm, i.e. the vendor's GEMM library, casts / GELU / GELU' as eager elementwise kernels, the layout copies
+    that interface needs): what a framework-level implementation of the method costs here.  Context, not the target.
+    Returns None when this PyTorch build cannot run it."""
+    try:
+        dev = "cuda:0"
+        E4, E5 = torch.float8_e4m3fn, torch.float8_e5m2
+        X, W1, W2, G = (torch.randn(s, dtype=torch.float16, device=dev) for s in ((T, d), (d, f), (f, d), (T, d)))
+        sc = lambda v: torch.tensor(float(v), device=dev)
+        a1, a2, bx2, bx1, bw, one = sc(d ** -0.5), sc(f ** -0.5), sc(d ** -0.5), sc(f ** -0.5), sc(T ** -0.5), sc(1.0)
+        ag, bg = 1.7009261846542358, 1.481114387512207
+
+        def mm(a, b_nk, s):       # a [M,K] row-major; b_nk [N,K] row-major, so that b_nk.t() is the column-major [K,N] the call wants
+            return torch._scaled_mm(a, b_nk.t(), scale_a=s, scale_b=one, out_dtype=torch.float16)
+
+        def step():
+            X8, W1_8, W2_8, G8 = X.to(E4), W1.to(E4), W2.to(E4), G.to(E5)
+            Z = mm(X8, W1_8.t().contiguous(), a1)
+            H8 = (torch.nn.functional.gelu(Z) * ag).to(E4)
+            Y = mm(H8, W2_8.t().contiguous(), a2)
+            dH = mm(G8, W2_8, bx2)
+            dZ8 = (torch.ops.aten.gelu_backward(dH, Z) * bg).to(E5)
+            dW2 = mm(H8.t().contiguous(), G8.t().contiguous(), bw)
+            dX = mm(dZ8, W1_8, bx1)
+            dW1 = mm(X8.t().contiguous(), dZ8.t().contiguous(), bw)
+            return Y, dX, dW1, dW2
+
+        ms_step = time_steps(torch, step, steps, warmup)
+        # the six matmuls alone, operands prepared beforehand (a floor for anything built on that library)
+        X8, W1_8, W2_8, G8 = X.to(E4), W1.to(E4), W2.to(E4), G.to(E5)
+        H8, dZ8 = torch.randn((T, f), device=dev).to(E4), torch.randn((T, f), device=dev).to(E5)
+        W1t, W2t, H8t, G8t, X8t, dZ8t = (t.t().contiguous() for t in (W1_8, W2_8, H8, G8, X8, dZ8))
+
+        def gemms():
+            mm(X8, W1t, a1); mm(H8, W2t, a2); mm(G8, W2_8, bx2); mm(H8t, G8t, bw); mm(dZ8, W1_8, bx1); mm(X8t, dZ8t, bw)
+
+        ms_gemms = time_steps(torch, gemms, steps, warmup)
+        flop = 12.0 * T * d * f
+        return {"what": "FP8 unit-scaled FFN fwd+bwd with PyTorch ops on this GPU (torch._scaled_mm + eager elementwise kernels and "
+                        "layout copies); six_matmuls_only: the vendor library's six FP8 matmuls with operands prepared beforehand",
+                "ms_per_step": ms_step, "TFLOPs": flop / (ms_step * 1e-3) * 1e-12,
+                "six_matmuls_only_ms": ms_gemms, "six_matmuls_only_TFLOPs": flop / (ms_gemms * 1e-3) * 1e-12}
+    except Exception as e:          # an op or type this build lacks: the comparison is simply left out
+        return {"unavailable": repr(e)[:200]}
+
 def cpu_baseline(ffn, sample_tokens):
     """The oracle, as it stands, on the first `sample_tokens` tokens of the same tensors (all of d and f)."""
     import numpy as np
@@ -409,6 +456,8 @@ def main():
                             "ms_per_step": ms_a, "TFLOPs": a_flop / (ms_a * 1e-3) * 1e-12,
                             "score_tensor_GBps": a_bytes / (ms_a * 1e-3) * 1e-9}
         del aq, ak, av, ado, aA, aP, adP, adA, aO, adQ, adK, adV
+    if not args.no_secondary and w["fp8"]:
+        out["pytorch_reference"] = pytorch_reference(torch, w["T"], w["d"], w["f"])
     if not args.no_secondary and args.workload != "C2":
         w2 = WORKLOADS["C2"]
         f2 = Ffn(torch, us, synth, w2["T"], w2["d"], w2["f"], False, synth.BASE_SEED + 1)
