@@ -467,6 +467,15 @@ def main():
         out["fp16_bert_base"] = {"workload": "C2: " + w2["desc"], "ms_per_step": ms2, "TFLOPs": t2,
                                  "frac_of_mfma_peak": t2 / PEAK_TFLOPS["f16"]}
         del f2
+    if not args.no_secondary and args.workload == "C3":
+        # the same step at a size where the main loops dominate (reduction lengths 4096 / 16384 / 32768)
+        w5 = WORKLOADS["C5"]
+        f5 = Ffn(torch, us, synth, w5["T"], w5["d"], w5["f"], True, synth.BASE_SEED + 4)
+        ramp_up(torch, f5.step)
+        ms5 = time_steps(torch, f5.step, 10, 2)
+        t5 = f5.flop / (ms5 * 1e-3) * 1e-12
+        out["fp8_large"] = {"workload": "C5: " + w5["desc"], "ms_per_step": ms5, "TFLOPs": t5, "frac_of_mfma_peak": t5 / PEAK_TFLOPS["fp8"]}
+        del f5
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(ffn, min(args.cpu_sample_tokens, w["T"]))
     print(json.dumps(out))
