@@ -70,6 +70,26 @@ def test_matmul_batched_exact_integers_and_independent_items():
     assert np.array_equal(_bits(_batched(A[perm], B[perm], 0.125)), _bits(C[perm]))
 
 
+def test_a_batch_of_one_is_the_plain_matmul():
+    M, N, K = 272, 400, 256
+    A = synth.normal(102, 1, (1, M, K)); B = synth.normal(102, 2, (1, K, N))
+    C = _batched(A, B, 1 / 16)
+    tA, tB, tY = to_dev(A[0]), to_dev(B[0]), empty((M, N), np.float16)
+    us.linear_fwd(ptr(tA), ptr(tB), ptr(tY), M, K, N, us.F16, us.F16, us.F16, 1 / 16, us.EPI_NONE, 0.0, None, None, None, 0, stream())
+    assert np.array_equal(_bits(C[0]), _bits(to_np(tY)))
+
+
+def test_zero_reduction_length_and_special_values():
+    C = _batched(np.zeros((3, 32, 0), np.float16), np.zeros((3, 0, 48), np.float16), 1.0)
+    assert C.shape == (3, 32, 48) and not C.any()
+    A = synth.normal(103, 1, (2, 48, 64)); B = synth.normal(103, 2, (2, 64, 32))
+    A[1, 5, 7] = np.nan
+    A[0, 3, :] = 0; A[0, 3, 0] = np.inf; B[0, 0, :] = 1.0
+    C = _batched(A, B, 1.0)
+    assert np.all(np.isnan(C[1, 5])) and np.isfinite(C[1, 4]).all()
+    assert np.all(np.isinf(C[0, 3])) and np.isfinite(C[0, 2]).all()
+
+
 class Attn:
     def __init__(self, heads, s, d, seed, on_device=False):
         self.heads, self.s, self.d = heads, s, d
@@ -111,7 +131,7 @@ def check_heads(run, heads):
         assert_close(g["dK"], O.matmul_batched(g["dA"], g["Q"], c["b_k"], trans_a=True), "dK")
 
 
-@pytest.mark.parametrize("shape", [(3, 80, 48), (2, 272, 64), (5, 128, 128)])
+@pytest.mark.parametrize("shape", [(1, 16, 16), (3, 80, 48), (2, 272, 64), (5, 128, 128)])
 def test_attention_small_shapes_every_head(shape):
     heads, s, d = shape
     check_heads(Attn(heads, s, d, 101), range(heads))

@@ -240,3 +240,17 @@ def test_ffn_with_biases_at_the_bert_large_shape_sampled():
     # unit variance of the bias gradients (b^-1/2 on a sum of T unit-scale rows); dZ has variance ~1 only where gelu' does
     assert abs(float(dev["db2"].float().std()) - 1.0) < 0.05
     assert 0.8 < float(dev["db1"].float().std()) < 1.2
+
+
+def test_bias_and_its_gradient_propagate_nan():
+    b, m, n = 64, 64, 96
+    X, W, dt = _operands(b, m, n, 78, False)
+    bias = synth.normal(78, 9, (n,))
+    bias[5] = np.nan
+    bias[7] = np.inf
+    Y, _, _ = _fwd(X, W, dt, bias)
+    assert np.all(np.isnan(Y[:, 5])) and np.all(np.isposinf(Y[:, 7])) and np.isfinite(np.delete(Y, [5, 7], axis=1)).all()
+    G = synth.normal(78, synth.T_G, (b, n))
+    G[3, 11] = np.nan
+    dc = _bias_grad(G, us.F16)
+    assert np.isnan(dc[11]) and np.isfinite(np.delete(dc, 11)).all()

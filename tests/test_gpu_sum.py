@@ -41,3 +41,16 @@ def test_sum_exact_integers_and_empty_rows():
     ty = torch.full((5,), 3.0, dtype=torch.float16, device=DEV)
     us.sum_fwd(None, ptr(ty), 5, 0, 0.0, stream())
     assert not to_np(ty).any()
+
+
+def test_sum_propagates_nan_and_infinity():
+    x = synth.normal(123, 1, (4, 64))
+    x[1, 9] = np.nan
+    x[2, 3] = np.inf
+    x[3, 3] = np.inf; x[3, 40] = -np.inf
+    tx, ty = to_dev(x), empty((4,), np.float16)
+    us.sum_fwd(ptr(tx), ptr(ty), 4, 64, 0.0, stream())
+    y = to_np(ty)
+    assert np.isfinite(y[0]) and np.isnan(y[1]) and np.isposinf(y[2]) and np.isnan(y[3])
+    ref = O.sum_fwd(x)
+    assert np.array_equal(np.isnan(y), np.isnan(ref)) and np.array_equal(np.isinf(y), np.isinf(ref))
