@@ -136,6 +136,29 @@ def test_fp8_ffn_without_fp16_dz_small():
     _same_without_fp16_dz(FfnRun(X, W1, W2, G, fp8=True), X, W1, W2, G)
 
 
+
+@pytest.mark.parametrize("fp8", [False, True])
+def test_end_to_end_drift_against_the_oracle_chain(fp8, record_property):
+    """The stage-wise comparisons above feed every oracle stage with the GPU's own stored inputs.  Here the oracle runs
+    its whole chain by itself and the final tensors are compared: intermediate rounding flips (FP16 steps, FP8 codes at
+    a boundary) now propagate, so this drift is reported (RMS and maximum, relative to the unit scale of the tensors)
+    and only loosely gated."""
+    T, d, f = 1024, 256, 1040
+    X, W1, W2, G = synth.ffn_inputs(T, d, f, seed=131)
+    run = FfnRun(X, W1, W2, G, fp8)
+    fw = O.ffn_fwd(X, W1, W2, fp8)
+    bw = O.ffn_bwd(X, W1, W2, G, fw, fp8)
+    ref = dict(Z=fw["Z"], Y=fw["Y"], dZ16=bw["dZ"], dX=bw["dX"], dW1=bw["dW1"], dW2=bw["dW2"])
+    for name, r in ref.items():
+        g = run.full(name).astype(np.float64)
+        e = g - r.astype(np.float64)
+        rms, mx = float(np.sqrt(np.mean(e * e))), float(np.abs(e).max())
+        record_property(f"drift_{name}_rms", rms)
+        record_property(f"drift_{name}_max", mx)
+        print(f"end-to-end drift {'fp8' if fp8 else 'fp16'} {name}: rms {rms:.2e} max {mx:.2e}")
+        # FP16 chain: a few FP16 steps; FP8 chain: a flipped E4M3 / E5M2 code moves one product by up to 12 % of an element
+        assert rms < (2e-2 if fp8 else 2e-3) and mx < (0.5 if fp8 else 2e-2), (name, rms, mx)
+
 def _sample(n, k, seed):
     rng = np.random.default_rng(seed)
     return np.sort(rng.choice(n, size=min(k, n), replace=False))
