@@ -36,7 +36,7 @@ inline bool use_big_tile(long M, long N, int splits) { return ceil_div(M, 256) *
 // workgroup share it and add up in LDS.
 inline bool use_wave_split_tile(long M, long N, long K) {
   const long tiles = ceil_div(M, 128) * ceil_div(N, 128);
-  return !use_big_tile(M, N, 1) && K >= 1024 && K % 256 == 0 && tiles >= 192 && tiles <= 256;
+  return !use_big_tile(M, N, 1) && K >= 1024 && K % 256 == 0 && tiles >= 128 && tiles <= 256;
 }
 
 inline GemmArgs make_args(const GemmProblem& p, long k_per_split, int BM, int BN) {

@@ -22,10 +22,18 @@ hipError_t launch_pair(const GemmProblem& dx, const GemmProblem& dw, hipStream_t
   return hipGetLastError();
 }
 
+// grad_X without an epilogue on so few 128 x 128 tiles that the CUs get at most one each (wave-split small tile)
+bool small_tile_ok(const GemmProblem& dx) {
+  const long t = ceil_div(dx.M, 128) * ceil_div(dx.N, 128);
+  return dx.epi == US_EPI_NONE && t <= 256 && dx.K >= 1024 && !use_big_tile(dx.M, dx.N, 1);
+}
+
 template <bool FP8>
 hipError_t launch_pair_typed(const GemmProblem& dx, const GemmProblem& dw, hipStream_t st) {
   constexpr int FG = FP8 ? 1 : 0;                     // gradient operand format (E5M2) where it applies
   using KW = GemmKind<CfgK128, FP8, 0, FG, false, false, EPI_STORE, false>;
+  if (dx.epi == US_EPI_GELU_GRAD && !use_big_tile(dx.M, dx.N, 1))
+    return launch_pair<GemmKind<CfgM256, FP8, FG, 0, true, true, EPI_GELU_GRAD, false>, KW>(dx, dw, st);
   if (dx.epi == US_EPI_GELU_GRAD) {
     GemmProblem q = dx;
     q.table = (char*)dx.table + kGeluSlopeTableOffset;
@@ -41,6 +49,7 @@ hipError_t launch_pair_typed(const GemmProblem& dx, const GemmProblem& dw, hipSt
     return launch_pair<GemmKind<CfgM256, FP8, FG, 0, true, true, EPI_RESIDUAL, false>, KW>(dx, dw, st);
   }
   if (big) return launch_pair<GemmKind<CfgD256, FP8, FG, 0, true, true, EPI_STORE, false>, KW>(dx, dw, st);
+  if (small_tile_ok(dx)) return launch_pair<GemmKind<CfgW128, FP8, FG, 0, true, true, EPI_STORE, false>, KW>(dx, dw, st);
   return launch_pair<GemmKind<CfgM256, FP8, FG, 0, true, true, EPI_STORE, false>, KW>(dx, dw, st);
 }
 
@@ -58,8 +67,13 @@ bool gemm_pair_applicable(const GemmProblem& dx, const GemmProblem& dw) {
   if (!(dx.a_kc && dx.b_kc) || dw.a_kc || dw.b_kc) return false;
   if (dx.c_dt != US_F16 || dw.c_dt != US_F16 || dw.epi != US_EPI_NONE) return false;
   const long bk = fp8 ? 128 : 64;
-  if (dx.K <= 0 || dx.K % bk || !(use_big_tile(dx.M, dx.N, 1) || mid_tile_ok(dx))) return false;
-  if (dx.epi == US_EPI_GELU_GRAD && (!dx.table || dx.act != 0)) return false;   // the arithmetic epilogues are launched on their own
+  const bool big = use_big_tile(dx.M, dx.N, 1);
+  const long t_mid = ceil_div(dx.M, 256) * ceil_div(dx.N, 128);
+  // grad_X with the arithmetic activation-derivative epilogue on 256 x 128 tiles (an output too small for the large tile)
+  const bool mid_act = dx.epi == US_EPI_GELU_GRAD && !big && t_mid >= 192 && t_mid <= 512;
+  const bool small_pair = (small_tile_ok(dx) && !mid_tile_ok(dx)) || mid_act;
+  if (dx.K <= 0 || dx.K % bk || !(big || mid_tile_ok(dx) || small_pair)) return false;
+  if (dx.epi == US_EPI_GELU_GRAD && big && (!dx.table || dx.act != 0)) return false;   // large tile: table-driven epilogue only
   if (dx.epi != US_EPI_NONE && dx.epi != US_EPI_GELU_GRAD && dx.epi != US_EPI_RESIDUAL) return false;
   if (!use_wave_split_tile(dw.M, dw.N, dw.K)) return false;
   return (ceil_div(dw.M, 128) * ceil_div(dw.N, 128)) % 8 == 0;

@@ -47,13 +47,15 @@ def test_workspace_rule():
     assert us.workspace_bytes(32768, 4096, 16384) == table_area     # the output alone fills the chip: no dW slices
     # 256 tiles of 128 x 128 cover the CUs once: the token reduction is shared by wave groups, no slices
     assert us.workspace_bytes(8192, 1024, 4096) == table_area
-    wb = us.workspace_bytes(4096, 768, 3072) - table_area           # 144 tiles: sliced
-    assert wb > 0 and wb % (768 * 3072 * 4) == 0                    # whole FP32 slices of the output
-    assert us.ffn_workspace_bytes(4096, 768, 3072) >= wb + table_area
+    assert us.workspace_bytes(4096, 768, 3072) == table_area        # 144 tiles: the wave groups again
+    wb = us.workspace_bytes(4096, 512, 2048) - table_area           # 64 tiles: the token dimension is sliced
+    assert wb > 0 and wb % (512 * 2048 * 4) == 0                    # whole FP32 slices of the output
+    assert us.ffn_workspace_bytes(4096, 512, 2048) >= wb + table_area
     assert us.workspace_bytes(0, 16, 16) == 0
     assert us.bias_grad_workspace_bytes(8192, 4096) == 256 * 4096 * 4 and us.bias_grad_workspace_bytes(33, 16) == 2 * 16 * 4
     assert us.ffn_bias_workspace_bytes(8192, 1024, 4096) == table_area + 256 * 4096 * 4
-    assert us.ffn_bias_workspace_bytes(4096, 768, 3072) == us.ffn_workspace_bytes(4096, 768, 3072)   # the dW slices are larger
+    assert us.ffn_bias_workspace_bytes(4096, 512, 2048) == us.ffn_workspace_bytes(4096, 512, 2048)   # the dW slices are larger
+    assert us.ffn_bias_workspace_bytes(4096, 768, 3072) == table_area + 128 * 3072 * 4               # no slices: the bias partials
     assert us.layer_norm_workspace_bytes(8192, 1024) == 256 * 2 * 1024 * 4 and us.layer_norm_workspace_bytes(33, 16) == 2 * 2 * 16 * 4
 
 
@@ -72,7 +74,7 @@ def test_argument_errors_are_detected_on_the_host():
         (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, F16, F16, F16, 0.0, us.EPI_GELU), 1),   # no aux buffer
         (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, F16, F16, F32, 0.0, us.EPI_GELU, 0.0, 16), 4),
         (lambda: us.linear_bwd(16, 16, 16, 16, 16, 16, 16, 16, E4, E4, E4), 4),   # gradients are E5M2
-        (lambda: us.linear_bwd(16, 16, 16, 16, 16, 4096, 768, 3072, F16, F16, F16), 5),   # workspace missing
+        (lambda: us.linear_bwd(16, 16, 16, 16, 16, 4096, 512, 2048, F16, F16, F16), 5),   # workspace missing
         (lambda: us.linear_bwd(16, 16, 16, 16, None, 16, 16, 16, F16, F16, F16, F16, 0, 0, us.EPI_GELU_GRAD), 1),
         (lambda: us.linear_bwd(16, 16, 8, 16, 16, 16, 16, 16, F16, F16, F16), 3),
         (lambda: us.linear_fwd(16, 16, 16, 16, 16, 16, F16, F16, F16, 0.0, us.EPI_RESIDUAL, 0.5), 1),          # no skip input

@@ -267,7 +267,8 @@ def test_paired_grad_x_grad_w_launch_equals_separate_launches(fp8, shape):
     """A grad_X of large (or 256 x 128) tiles together with a grad_W of about one small tile per CU goes
     out as one launch; every output must equal, bit for bit, what the two separate launches give.
     Shapes: grad_X 8192 x 4096 (512 large tiles) with grad_W 4096 x 1024, and grad_X 8192 x 1024
-    (256 tiles of 256 x 128; no GELU' there) with grad_W 1024 x 4096."""
+    (256 tiles of 256 x 128, whose two wave groups add their k-steps in another order than the separate
+    launch: equal within the matmul tolerance there) with grad_W 1024 x 4096."""
     b, m, n = shape
     (X, W, G), gdt, odt = _operands(b, m, n, 149, fp8)
     Zpre = synth.normal(149, 7, (b, m))
@@ -276,14 +277,16 @@ def test_paired_grad_x_grad_w_launch_equals_separate_launches(fp8, shape):
         dX, dW, c8 = linear_bwd(X, W, G, *gdt, **kw)                       # paired
         dX1, _, c81 = linear_bwd(None, W, G, *gdt, do_dw=False, **kw)
         _, dW1, _ = linear_bwd(X, None, G, *gdt, do_dx=False)
-        if m >= 4096 or epi:
+        if m >= 4096:
             assert np.array_equal(dX.view(np.uint16), dX1.view(np.uint16)), epi
+            if c8 is not None:
+                assert np.array_equal(c8, c81)
         else:      # the paired grad_X adds its k-steps in two interleaved halves: same sum, another order
             assert_close(dX, dX1, "dX paired vs separate")
             assert np.mean(dX.view(np.uint16) != dX1.view(np.uint16)) < 0.2
+            if c8 is not None:     # the codes are those of this launch's own FP16 result
+                assert np.array_equal(c8, O.cast_fp8(dX, O.E5M2)[0])
         assert np.array_equal(dW.view(np.uint16), dW1.view(np.uint16)), epi
-        if c8 is not None:
-            assert np.array_equal(c8, c81)
     rows, cols = [0, 1, 4097, 8191], [0, 5, 1023]
     assert_close(dW[:, cols], O.linear_bwd_dw(X, np.ascontiguousarray(G[:, cols]), b ** -0.5, odt[0], odt[2]), "dW paired")
     dH = O.linear_bwd_dx(G[rows], W, n ** -0.5, odt[2], odt[1])
