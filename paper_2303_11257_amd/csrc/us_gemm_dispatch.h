@@ -19,7 +19,8 @@ using CfgD128 = GemmCfg<128, 128, 2, 2, 128, 2, 2>;
 using CfgS128 = GemmCfg<128, 128, 2, 2, 128, 2, 2>;
 using CfgK128 = GemmCfg<128, 128, 2, 2, 256, 2, 1, 2>;
 //   M256: 256 x 128 tile, 8 waves as two groups of 2 x 2 sharing every stage's k-steps, three stages; as
-//         fast as D128 on its own, used where a 512-thread shape is needed next to K128 in a paired launch
+//         fast as D128 on its own, used where a 512-thread shape is needed next to K128 in a paired launch, and
+//         for grad_W itself (both operands K-strided) on about 128 tiles in a paired launch
 using CfgM256 = GemmCfg<256, 128, 2, 2, 128, 3, 1, 2>;
 //   W128: forward / grad_X with so few 128 x 128 tiles that the CUs get at most one each (BERT-base: 192): 8 waves
 //         on the tile, two groups sharing the k-steps of each stage, four stages; 10-16 % faster than D128 there

@@ -1,5 +1,5 @@
-// Both products of a layer's backward pass (grad_X and grad_W) in one launch, when grad_X uses the
-// large tile and grad_W the wave-split small tile (both 512 threads): see gemm_pair_kernel.
+// Both products of a layer's backward pass (grad_X and grad_W) in one launch, for the combinations of
+// 512-thread tile shapes listed in gemm_pair_applicable: see gemm_pair_kernel.
 #include "us_gemm_dispatch.h"
 
 namespace us {
@@ -22,16 +22,32 @@ hipError_t launch_pair(const GemmProblem& dx, const GemmProblem& dw, hipStream_t
   return hipGetLastError();
 }
 
+// grad_W in a pair on 256 x 128 tiles that take about half of the CUs (BERT-large: 4096 x 1024 -> 128 tiles).  Such a
+// tile needs 36 % less CU time than two wave-split 128 x 128 tiles, but covers only half of the chip and runs twice as
+// long: on its own that is slower, in a pair the grad_X tiles take the other CUs from the start and the launch ends
+// when it would have ended with grad_W spread over all CUs, minus the CU time saved.  With fewer than 112 tiles the
+// long tiles outlast the rest of the launch (BERT-base, 72 tiles: measured slower).
+bool long_tile_ok(const GemmProblem& dw) {
+  const long t = ceil_div(dw.M, 256) * ceil_div(dw.N, 128);
+  return t >= 112 && t <= 128 && t % 8 == 0;
+}
+
+// grad_X without an activation derivative whose 256 x 256 tiles, together with grad_W's long tiles, give every CU one
+// tile of about the same length (BERT-large layer 1: 128 + 128)
+bool one_round_ok(const GemmProblem& dx, const GemmProblem& dw) {
+  const long t = ceil_div(dx.M, 256) * ceil_div(dx.N, 256) + ceil_div(dw.M, 256) * ceil_div(dw.N, 128);
+  return long_tile_ok(dw) && (dx.epi == US_EPI_NONE || dx.epi == US_EPI_RESIDUAL) && t >= 224 && t <= 256 && dx.K >= 2048;
+}
+
 // grad_X without an epilogue on so few 128 x 128 tiles that the CUs get at most one each (wave-split small tile)
 bool small_tile_ok(const GemmProblem& dx) {
   const long t = ceil_div(dx.M, 128) * ceil_div(dx.N, 128);
   return dx.epi == US_EPI_NONE && t <= 256 && dx.K >= 1024 && !use_big_tile(dx.M, dx.N, 1);
 }
 
-template <bool FP8>
-hipError_t launch_pair_typed(const GemmProblem& dx, const GemmProblem& dw, hipStream_t st) {
+template <bool FP8, class KW>
+hipError_t launch_pair_kw(const GemmProblem& dx, const GemmProblem& dw, hipStream_t st) {
   constexpr int FG = FP8 ? 1 : 0;                     // gradient operand format (E5M2) where it applies
-  using KW = GemmKind<CfgK128, FP8, 0, FG, false, false, EPI_STORE, false>;
   if (dx.epi == US_EPI_GELU_GRAD && !use_big_tile(dx.M, dx.N, 1))
     return launch_pair<GemmKind<CfgM256, FP8, FG, 0, true, true, EPI_GELU_GRAD, false>, KW>(dx, dw, st);
   if (dx.epi == US_EPI_GELU_GRAD) {
@@ -43,7 +59,8 @@ hipError_t launch_pair_typed(const GemmProblem& dx, const GemmProblem& dw, hipSt
     }
     return launch_pair<GemmKind<CfgD256, FP8, FG, 0, true, true, EPI_GELU_GRAD_TAB, false>, KW>(q, dw, st);
   }
-  const bool big = use_big_tile(dx.M, dx.N, 1);
+  // the large tile also when it and grad_W's long tiles fill the CUs exactly once
+  const bool big = use_big_tile(dx.M, dx.N, 1) || (KW::BM == 256 && one_round_ok(dx, dw));
   if (dx.epi == US_EPI_RESIDUAL) {
     if (big) return launch_pair<GemmKind<CfgD256, FP8, FG, 0, true, true, EPI_RESIDUAL, false>, KW>(dx, dw, st);
     return launch_pair<GemmKind<CfgM256, FP8, FG, 0, true, true, EPI_RESIDUAL, false>, KW>(dx, dw, st);
@@ -51,6 +68,13 @@ hipError_t launch_pair_typed(const GemmProblem& dx, const GemmProblem& dw, hipSt
   if (big) return launch_pair<GemmKind<CfgD256, FP8, FG, 0, true, true, EPI_STORE, false>, KW>(dx, dw, st);
   if (small_tile_ok(dx)) return launch_pair<GemmKind<CfgW128, FP8, FG, 0, true, true, EPI_STORE, false>, KW>(dx, dw, st);
   return launch_pair<GemmKind<CfgM256, FP8, FG, 0, true, true, EPI_STORE, false>, KW>(dx, dw, st);
+}
+
+template <bool FP8>
+hipError_t launch_pair_typed(const GemmProblem& dx, const GemmProblem& dw, hipStream_t st) {
+  constexpr int FG = FP8 ? 1 : 0;
+  if (long_tile_ok(dw)) return launch_pair_kw<FP8, GemmKind<CfgM256, FP8, 0, FG, false, false, EPI_STORE, false>>(dx, dw, st);
+  return launch_pair_kw<FP8, GemmKind<CfgK128, FP8, 0, FG, false, false, EPI_STORE, false>>(dx, dw, st);
 }
 
 // grad_X without an epilogue whose 256 x 128 tiles cover the CUs about once
@@ -72,11 +96,11 @@ bool gemm_pair_applicable(const GemmProblem& dx, const GemmProblem& dw) {
   // grad_X with the arithmetic activation-derivative epilogue on 256 x 128 tiles (an output too small for the large tile)
   const bool mid_act = dx.epi == US_EPI_GELU_GRAD && !big && t_mid >= 192 && t_mid <= 512;
   const bool small_pair = (small_tile_ok(dx) && !mid_tile_ok(dx)) || mid_act;
-  if (dx.K <= 0 || dx.K % bk || !(big || mid_tile_ok(dx) || small_pair)) return false;
+  if (dx.K <= 0 || dx.K % bk || !(big || mid_tile_ok(dx) || small_pair || one_round_ok(dx, dw))) return false;
   if (dx.epi == US_EPI_GELU_GRAD && big && (!dx.table || dx.act != 0)) return false;   // large tile: table-driven epilogue only
   if (dx.epi != US_EPI_NONE && dx.epi != US_EPI_GELU_GRAD && dx.epi != US_EPI_RESIDUAL) return false;
   if (!use_wave_split_tile(dw.M, dw.N, dw.K)) return false;
-  return (ceil_div(dw.M, 128) * ceil_div(dw.N, 128)) % 8 == 0;
+  return long_tile_ok(dw) || (ceil_div(dw.M, 128) * ceil_div(dw.N, 128)) % 8 == 0;
 }
 
 hipError_t launch_gemm_pair(const GemmProblem& dx, const GemmProblem& dw, hipStream_t st) {

@@ -77,8 +77,8 @@ size_t gemm_workspace_bytes(long M, long N, long K);
 hipError_t launch_gemm(const GemmProblem& p, hipStream_t stream);
 
 // grad_X (dx) and grad_W (dw) of one layer in a single launch with interleaved tiles; only for the
-// shape / type combinations gemm_pair_applicable accepts.  grad_W is bit-identical to its own launch; grad_X may run
-// on a tile whose wave groups add their k-steps in another order than alone: FP16 results can differ in the last place.
+// shape / type combinations gemm_pair_applicable accepts.  Either product may run on another tile shape than
+// alone, whose wave groups add their k-steps in another order: FP16 results can differ in the last place.
 bool gemm_pair_applicable(const GemmProblem& dx, const GemmProblem& dw);
 hipError_t launch_gemm_pair(const GemmProblem& dx, const GemmProblem& dw, hipStream_t stream);
 

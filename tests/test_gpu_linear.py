@@ -265,16 +265,20 @@ def test_table_driven_gelu_fp16_output_equals_the_arithmetic_one():
 @pytest.mark.parametrize("shape", [(8192, 4096, 1024), (8192, 1024, 4096)])
 def test_paired_grad_x_grad_w_launch_equals_separate_launches(fp8, shape):
     """A grad_X of large (or 256 x 128) tiles together with a grad_W of about one small tile per CU goes
-    out as one launch; every output must equal, bit for bit, what the two separate launches give.
-    Shapes: grad_X 8192 x 4096 (512 large tiles) with grad_W 4096 x 1024, and grad_X 8192 x 1024
-    (256 tiles of 256 x 128, whose two wave groups add their k-steps in another order than the separate
-    launch: equal within the matmul tolerance there) with grad_W 1024 x 4096."""
+    out as one launch.  Shapes: grad_X 8192 x 4096 (512 large tiles: the same kernel as alone, so the same
+    bits) with grad_W 4096 x 1024, and grad_X 8192 x 1024 with grad_W 1024 x 4096.  In the pair grad_W sits
+    on 128 tiles of 256 x 128 (alone: 256 of 128 x 128) and the second grad_X on the large tile; their wave
+    groups share the k-steps differently, so the sums are added in another order: equal within the matmul
+    tolerance, the same bits from call to call and whatever the epilogue of grad_X."""
     b, m, n = shape
     (X, W, G), gdt, odt = _operands(b, m, n, 149, fp8)
     Zpre = synth.normal(149, 7, (b, m))
+    dW_first = None
     for epi in (us.EPI_NONE, us.EPI_GELU_GRAD):
         kw = dict(epi=epi, Zpre=Zpre if epi else None, want8=bool(epi) and fp8)
         dX, dW, c8 = linear_bwd(X, W, G, *gdt, **kw)                       # paired
+        dW_first = dW if dW_first is None else dW_first
+        assert np.array_equal(dW.view(np.uint16), dW_first.view(np.uint16)), epi
         dX1, _, c81 = linear_bwd(None, W, G, *gdt, do_dw=False, **kw)
         _, dW1, _ = linear_bwd(X, None, G, *gdt, do_dx=False)
         if m >= 4096:
@@ -286,7 +290,8 @@ def test_paired_grad_x_grad_w_launch_equals_separate_launches(fp8, shape):
             assert np.mean(dX.view(np.uint16) != dX1.view(np.uint16)) < 0.2
             if c8 is not None:     # the codes are those of this launch's own FP16 result
                 assert np.array_equal(c8, O.cast_fp8(dX, O.E5M2)[0])
-        assert np.array_equal(dW.view(np.uint16), dW1.view(np.uint16)), epi
+        assert_close(dW, dW1, "dW paired vs separate")
+        assert np.mean(dW.view(np.uint16) != dW1.view(np.uint16)) < 0.2
     rows, cols = [0, 1, 4097, 8191], [0, 5, 1023]
     assert_close(dW[:, cols], O.linear_bwd_dw(X, np.ascontiguousarray(G[:, cols]), b ** -0.5, odt[0], odt[2]), "dW paired")
     dH = O.linear_bwd_dx(G[rows], W, n ** -0.5, odt[2], odt[1])

@@ -21,10 +21,12 @@ BASE = [
     (1024, 1024, 2000),   # forward: at most one small tile per CU and a long reduction (wave-split small tile)
     (1040, 2048, 1008),   # the same for grad_X; grad_W cut into K slices
     (1024, 2000, 1552),   # grad_W: 208 small tiles, long reduction: wave-split tile with ragged edges
-    (2048, 1792, 1536),   # grad_W: exactly 168 tiles (K slices) next to the wave-split range
+    (2048, 1792, 1536),   # grad_W: 168 tiles, in the lower part of the wave-split range
     (6000, 128, 4000),    # forward: 384 large tiles with ragged edges, one stage of reduction
     (6144, 4096, 768),    # backward of one layer in one launch (large-tile grad_X, wave-split grad_W)
     (4096, 768, 2048),    # forward and grad_X on 256 x 128 / 128 x 128 tiles, grad_W on 96 tiles (K slices)
+    (2304, 4000, 1024),   # paired backward with grad_W on 128 long (256 x 128) tiles, ragged; grad_X on 256 x 128 tiles
+    (7936, 1008, 4096),   # paired backward as one round: 124 large grad_X tiles + 128 long grad_W tiles, both ragged
 ]
 
 
@@ -107,4 +109,7 @@ def test_forward_and_backward(shape, fp8):
     widx = torch.as_tensor(wr, device=DEV)
     dWref = O.linear_bwd_dw(np.ascontiguousarray(X[:, wr]), G, bw, od[0], od[2])
     assert_close(dW[widx].cpu().numpy(), dWref, "dW")
-    assert torch.equal(dW, dW2), "grad_W must not depend on the epilogue of grad_X"
+    # grad_W has its own kernel alone and another in a paired launch (whether a pair forms depends on grad_X's epilogue
+    # too): the same sum added in another order, so nearly every FP16 result is the same and the rest a rounding apart
+    assert_close(dW2[widx].cpu().numpy(), dWref, "dW next to GELU'")
+    assert (dW != dW2).float().mean().item() < 0.2
