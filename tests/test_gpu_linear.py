@@ -103,7 +103,7 @@ def test_split_k_reduction_of_grad_w():
 
 @pytest.mark.parametrize("fp8", [False, True])
 def test_grad_w_wave_split_reduction(fp8):
-    """An output of 192-256 tiles of 128 x 128 with a long token dimension: two wave groups of one
+    """An output of 128-256 tiles of 128 x 128 with a long token dimension: two wave groups of one
     workgroup share the reduction and add up in LDS (no workspace).  Ragged in both output dimensions."""
     b, m, n = 1024, 2000, 1936                                   # 16 x 16 tiles, the last ones partial
     assert us.workspace_bytes(b, m, n) == us.TABLE_AREA_BYTES        # the table area only: no K slices
