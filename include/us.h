@@ -309,9 +309,11 @@ us_status us_ffn_res_bwd(const void* X, const void* W1, const void* W2, const vo
  * us_ffn_bias_fwd / us_ffn_bias_bwd: us_ffn_fwd / us_ffn_bwd with b1 [f], b2 [d] (either may be NULL) and their
  *   gradients db1 [f], db2 [d] (FP16 out, either may be NULL).  The bias gradients are sums of the FP16 gradients
  *   (FP8 copies exist for the matmuls only, App. J.2): db2 reads G16, the FP16 incoming gradient [T,d] (G is
- *   the matmul operand: the same tensor without US_FFN_FP8, its E5M2 cast with it), and db1 reads dZ16, which
- *   must then be stored (US_ERR_NULL if db1 is asked for without dZ16, or db2 without G16).
- *   workspace: us_ffn_bias_workspace_bytes(T, d, f).
+ *   the matmul operand: the same tensor without US_FFN_FP8, its E5M2 cast with it; US_ERR_NULL if db2 is asked for
+ *   without G16), and db1 sums the FP16 dZ inside the epilogue that produces it, so dZ16 may still be NULL with
+ *   US_FFN_FP8 (the sums are the same whether or not it is stored).
+ *   workspace: us_ffn_bias_workspace_bytes(T, d, f) = what us_ffn_bwd needs, rounded up to 256 bytes, plus
+ *   us_bias_grad_workspace_bytes(T, max(d, f)).
  */
 us_status us_linear_bias_fwd(const void* X, const void* W, const void* bias, void* Y, long b, long m, long n,
                              us_dtype x_dt, us_dtype w_dt, us_dtype y_dt, float alpha, us_epilogue epi,

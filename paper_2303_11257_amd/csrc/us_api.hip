@@ -161,10 +161,13 @@ us_status us_linear_bias_fwd(const void* X, const void* W, const void* bias, voi
   return from_hip(launch_gemm(p, as_stream(stream)));
 }
 
-us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, void* dW, long b, long m, long n,
-                        us_dtype x_dt, us_dtype w_dt, us_dtype g_dt, us_dtype out_dt, float beta_x, float beta_w,
-                        us_epilogue epi, float epi_scale, const void* Zpre, void* aux8, void* workspace,
-                        size_t workspace_bytes, void* stream) {
+// us_linear_bwd plus one internal option: colsum, FP32 [ceil(b / 32)][m], receives the column sums of the FP16 result of
+// the GELU' epilogue per 32-row block (the bias gradient of the layer, before its sum over the blocks), whether or not
+// that FP16 result is stored.
+static us_status linear_bwd_impl(const void* X, const void* W, const void* G, void* dX, void* dW, long b, long m, long n,
+                                 us_dtype x_dt, us_dtype w_dt, us_dtype g_dt, us_dtype out_dt, float beta_x, float beta_w,
+                                 us_epilogue epi, float epi_scale, const void* Zpre, void* aux8, void* workspace,
+                                 size_t workspace_bytes, void* stream, void* colsum) {
   const bool tables_ready = ((int)epi & US_EPI_TABLES_READY) != 0;
   const int act = ((int)epi >> 4) & 0xf;
   epi = (us_epilogue)((int)epi & 0xf);
@@ -178,7 +181,7 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
   if (epi == US_EPI_RESIDUAL && !residual_weight_ok(epi_scale)) return US_ERR_VALUE;
   if (b < 0 || m < 0 || n < 0 || !mult16(b) || !mult16(m) || !mult16(n)) return US_ERR_SHAPE;
   // with the GELU' epilogue the FP16 result is optional: its E5M2 copy alone may be asked for
-  const bool do_dx = (dX || (epi == US_EPI_GELU_GRAD && aux8)) && b > 0 && m > 0;
+  const bool do_dx = (dX || (epi == US_EPI_GELU_GRAD && (aux8 || colsum))) && b > 0 && m > 0;
   const bool do_dw = dW && m > 0 && n > 0;
   if (!do_dx && !do_dw) return US_OK;
   if (do_dx && n > 0 && (!G || !W)) return US_ERR_NULL;
@@ -208,6 +211,7 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
     p.Zpre = (epi != US_EPI_NONE) ? Zpre : nullptr;
     p.skip_scale = (epi == US_EPI_RESIDUAL) ? skip_weight(epi_scale) : 0.0f;
     p.aux8 = (epi == US_EPI_GELU_GRAD) ? aux8 : nullptr;
+    p.colsum = (epi == US_EPI_GELU_GRAD) ? colsum : nullptr;
     p.table = table;
     p.tables_ready = tables_ready;
   }
@@ -227,6 +231,14 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
   if (do_dx && launch_gemm(pdx, st) != hipSuccess) return US_ERR_LAUNCH;
   if (do_dw && launch_gemm(pdw, st) != hipSuccess) return US_ERR_LAUNCH;
   return US_OK;
+}
+
+us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, void* dW, long b, long m, long n,
+                        us_dtype x_dt, us_dtype w_dt, us_dtype g_dt, us_dtype out_dt, float beta_x, float beta_w,
+                        us_epilogue epi, float epi_scale, const void* Zpre, void* aux8, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  return linear_bwd_impl(X, W, G, dX, dW, b, m, n, x_dt, w_dt, g_dt, out_dt, beta_x, beta_w, epi, epi_scale, Zpre, aux8,
+                         workspace, workspace_bytes, stream, nullptr);
 }
 
 us_status us_act_fwd(const void* z, void* h, size_t n, us_dtype dt, us_activation kind, float s1, float scale, void* stream) {
@@ -357,23 +369,30 @@ us_status us_ffn_bias_fwd(const void* X, const void* W1, const void* b1, const v
   return us_linear_bias_fwd(H, W2, b2, Y, T, f, d, op, op, US_F16, 0.0f, US_EPI_NONE, 0.0f, nullptr, nullptr, nullptr, 0, stream);
 }
 
-us_status us_ffn_bwd(const void* X, const void* W1, const void* W2, const void* Z, const void* H, const void* G,
-                     void* dZ16, void* dZ8, void* dX, void* dW1, void* dW2, long T, long d, long f, int mode,
-                     void* workspace, size_t workspace_bytes, void* stream) {
+// us_ffn_bwd; dz_colsum as in linear_bwd_impl (column sums of dZ per 32-row block, FP32 [ceil(T / 32)][f]) or NULL
+static us_status ffn_bwd_impl(const void* X, const void* W1, const void* W2, const void* Z, const void* H, const void* G,
+                              void* dZ16, void* dZ8, void* dX, void* dW1, void* dW2, long T, long d, long f, int mode,
+                              void* workspace, size_t workspace_bytes, void* stream, void* dz_colsum) {
   const bool fp8 = (mode & US_FFN_FP8) != 0;
   const int ready = (mode & US_FFN_TABLES_READY) ? US_EPI_TABLES_READY : 0;
   const us_dtype op = fp8 ? US_E4M3 : US_F16;
   const us_dtype gr = fp8 ? US_E5M2 : US_F16;
   if (fp8 ? !dZ8 : !dZ16) return US_ERR_NULL;
   // layer 2 backward: dH = d^-1/2 G W2^T, fused with GELU' -> dZ (FP16 + E5M2 copy); dW2 = T^-1/2 H^T G
-  us_status s = us_linear_bwd(H, W2, G, dZ16, dW2, T, f, d, op, op, gr, US_F16, 0.0f, 0.0f,
-                              (us_epilogue)(US_EPI_GELU_GRAD | ready), 0.0f, Z,
-                              fp8 ? dZ8 : nullptr, workspace, workspace_bytes, stream);
+  us_status s = linear_bwd_impl(H, W2, G, dZ16, dW2, T, f, d, op, op, gr, US_F16, 0.0f, 0.0f,
+                                (us_epilogue)(US_EPI_GELU_GRAD | ready), 0.0f, Z,
+                                fp8 ? dZ8 : nullptr, workspace, workspace_bytes, stream, dz_colsum);
   if (s != US_OK) return s;
   // layer 1 backward: dX = f^-1/2 dZ W1^T; dW1 = T^-1/2 X^T dZ
   const void* dZ = fp8 ? dZ8 : dZ16;
   return us_linear_bwd(X, W1, dZ, dX, dW1, T, d, f, op, op, gr, US_F16, 0.0f, 0.0f, US_EPI_NONE, 0.0f, nullptr, nullptr,
                        workspace, workspace_bytes, stream);
+}
+
+us_status us_ffn_bwd(const void* X, const void* W1, const void* W2, const void* Z, const void* H, const void* G,
+                     void* dZ16, void* dZ8, void* dX, void* dW1, void* dW2, long T, long d, long f, int mode,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+  return ffn_bwd_impl(X, W1, W2, Z, H, G, dZ16, dZ8, dX, dW1, dW2, T, d, f, mode, workspace, workspace_bytes, stream, nullptr);
 }
 
 us_status us_bias_grad(const void* G, us_dtype g_dt, void* dc, long b, long n, float beta_c, void* workspace,
@@ -393,29 +412,39 @@ size_t us_bias_grad_workspace_bytes(long b, long n) { return bias_grad_workspace
 us_status us_ffn_bias_bwd(const void* X, const void* W1, const void* W2, const void* Z, const void* H, const void* G,
                           const void* G16, void* dZ16, void* dZ8, void* dX, void* dW1, void* dW2, void* db1, void* db2,
                           long T, long d, long f, int mode, void* workspace, size_t workspace_bytes, void* stream) {
-  // the bias gradients are sums of the FP16 gradients (the FP8 copies feed the matmuls only): db1 needs dZ16 stored
-  if ((db1 && !dZ16) || (db2 && !G16)) return US_ERR_NULL;
-  if (db1 || db2) {
-    const size_t need = (size_t)kTableAreaBytes + bias_grad_workspace_bytes(T, f > d ? f : d);
-    if (!workspace || workspace_bytes < need) return US_ERR_WORKSPACE;
+  // the bias gradients are sums of the FP16 gradients (the FP8 copies feed the matmuls only)
+  if (db2 && !G16) return US_ERR_NULL;
+  if ((mode & US_FFN_FP8) ? !dZ8 : !dZ16) return US_ERR_NULL;     // the operand of the layer-1 products (before any launch)
+  if (T < 0 || d < 0 || f < 0) return US_ERR_SHAPE;
+  // workspace: what us_ffn_bwd uses (tables, grad_W slices), then the area of the column sums
+  const size_t base = (us_ffn_workspace_bytes(T, d, f) + 255) & ~(size_t)255;
+  char* scratch = workspace ? (char*)workspace + base : nullptr;
+  if ((db1 || db2) && T > 0) {
+    if (!workspace || workspace_bytes < us_ffn_bias_workspace_bytes(T, d, f)) return US_ERR_WORKSPACE;
   }
-  us_status s = us_ffn_bwd(X, W1, W2, Z, H, G, dZ16, dZ8, dX, dW1, dW2, T, d, f, mode, workspace, workspace_bytes, stream);
-  if (s != US_OK) return s;
-  // the column sums run after the matmuls on the same stream and reuse the area behind the tables
-  char* scratch = (char*)workspace + kTableAreaBytes;
-  const size_t scratch_bytes = workspace_bytes - (size_t)kTableAreaBytes;
-  if (db2) {
+  const size_t scratch_bytes = workspace_bytes > base ? workspace_bytes - base : 0;
+  us_status s = US_OK;
+  if (db2) {     // first: the area is free until the matmul below fills it
     s = us_bias_grad(G16, US_F16, db2, T, d, 0.0f, scratch, scratch_bytes, stream);
     if (s != US_OK) return s;
   }
-  if (db1) s = us_bias_grad(dZ16, US_F16, db1, T, f, 0.0f, scratch, scratch_bytes, stream);
+  // db1: the epilogue that produces dZ adds up its columns per 32-row block on the way (whether or not the FP16 dZ is
+  // stored), the sum over the blocks follows the matmuls
+  const bool fused = db1 && T > 0 && f > 0;
+  s = ffn_bwd_impl(X, W1, W2, Z, H, G, dZ16, dZ8, dX, dW1, dW2, T, d, f, mode, workspace, workspace_bytes, stream,
+                   fused ? scratch : nullptr);
+  if (s != US_OK) return s;
+  if (db1 && f > 0) {
+    if (!aligned16(db1)) return US_ERR_ALIGN;
+    const float beta = (float)(1.0 / sqrt((double)(T > 0 ? T : 1)));
+    s = from_hip(launch_bias_grad_reduce(scratch, db1, T > 0 ? (T + 31) / 32 : 0, f, beta, as_stream(stream)));
+  }
   return s;
 }
 
 size_t us_ffn_bias_workspace_bytes(long T, long d, long f) {
-  const size_t a = us_ffn_workspace_bytes(T, d, f);
-  const size_t b = (size_t)kTableAreaBytes + bias_grad_workspace_bytes(T, f > d ? f : d);
-  return a > b ? a : b;
+  const size_t base = (us_ffn_workspace_bytes(T, d, f) + 255) & ~(size_t)255;
+  return base + bias_grad_workspace_bytes(T, f > d ? f : d);
 }
 
 us_status us_softmax_fwd(const void* X, void* Y, long rows, long s, float s1, float alpha, void* stream) {

@@ -135,4 +135,9 @@ hipError_t launch_bias_grad(const void* G, us_dtype g_dt, void* dc, long b, long
   return hipGetLastError();
 }
 
+hipError_t launch_bias_grad_reduce(const void* partial, void* dc, long nblocks, long n, float beta, hipStream_t st) {
+  colsum_reduce_kernel<<<(unsigned)(n / 16), 256, 0, st>>>((const float*)partial, (_Float16*)dc, (int)nblocks, n, beta);
+  return hipGetLastError();
+}
+
 }  // namespace us

@@ -36,6 +36,7 @@ struct GemmArgs {
   const uint8_t* table;  // EPI_*_TAB: the table in global memory (us_device.h)
   long batch_a, batch_b, batch_c;   // bytes between consecutive problems of a batch (blockIdx.z), 0 for a single one
   const _Float16* bias;  // forward product only: optional row [N] added to scale * acc before the rounding, or NULL
+  float* colsum;         // EPI_GELU_GRAD / _TAB: optional FP32 [ceil(M / 32)][N], column sums of the FP16 result per 32-row block
   int xcd_gm, xcd_gn;    // XCD rectangle split of the tile grid (0,0 = one rectangle)
   int grp_w;             // width of the column bands the rectangle is walked in
 };
@@ -126,7 +127,7 @@ __device__ __forceinline__ void store_grad(const GemmArgs& g, long idx, v8h r) {
 // z: the saved pre-activation at the same eight positions (GELU' epilogues only; fetched by the caller
 // well ahead of its use).
 template <int EPI, int AUX_FMT>
-__device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y, v8h z, const uint8_t* lut) {
+__device__ __forceinline__ v8h epilogue_row8(const GemmArgs& g, long idx, v8h y, v8h z, const uint8_t* lut) {
   if (EPI == EPI_GELU_TAB) {
     stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), y);   // the FP16 matmul result, kept for backward
     uint32_t c[8];
@@ -136,7 +137,7 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
     w.x = (int)(c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24));
     w.y = (int)(c[4] | (c[5] << 8) | (c[6] << 16) | (c[7] << 24));
     *reinterpret_cast<v2i*>(g.aux8 + idx) = w;
-    return;
+    return y;
   }
   if (EPI == EPI_GELU_TAB16) {
     stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), y);   // the FP16 matmul result, kept for backward
@@ -160,7 +161,7 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
       w.y = (int)(cvt_pk_fp8_from_half<AUX_FMT>(p2) | (cvt_pk_fp8_from_half<AUX_FMT>(p3) << 16));
       *reinterpret_cast<v2i*>(g.aux8 + idx) = w;
     }
-    return;
+    return r;
   }
   if (EPI == EPI_GELU_GRAD_TAB) {
     v8h r;
@@ -182,11 +183,11 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
       w.y = (int)(cvt_pk_fp8_from_half<AUX_FMT>(p2) | (cvt_pk_fp8_from_half<AUX_FMT>(p3) << 16));
       *reinterpret_cast<v2i*>(g.aux8 + idx) = w;
     }
-    return;
+    return r;
   }
   if (EPI == EPI_STORE) {
     stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), y);
-    return;
+    return y;
   }
   if (EPI == EPI_RESIDUAL) {
     // weighted addition of the skip input and the FP16-rounded matmul result (the residual layer's
@@ -195,7 +196,7 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
 #pragma unroll
     for (int k = 0; k < 8; ++k) r[k] = to_half(__builtin_fmaf(g.epi_scale, (float)y[k], g.skip_scale * (float)z[k]));
     stream_store(reinterpret_cast<v8h*>((_Float16*)g.C + idx), r);
-    return;
+    return r;
   }
   v8h r;
   if (EPI == EPI_GELU) {
@@ -230,6 +231,7 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& g, long idx, v8h y
     w.y = (int)(cvt_pk_fp8_from_half<AUX_FMT>(p2) | (cvt_pk_fp8_from_half<AUX_FMT>(p3) << 16));
     *reinterpret_cast<v2i*>(g.aux8 + idx) = w;
   }
+  return r;
 }
 
 // Strip geometry: every wave owns 32 rows x WN values of LDS (FP16, or FP32 when WIDE).
@@ -329,6 +331,14 @@ __device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&a
         }
     }
   };
+  // Column sums of the FP16 result (the bias gradient of the layer below the activation): a lane always works on
+  // the same 8 columns (CPR divides 64), so it adds its rows up in registers; the lanes of a column group are added
+  // at the end and the wave writes one FP32 row per 32-row block it finished (the sum in the first, zeros in the
+  // others), so that every row of GemmArgs::colsum is written exactly once per column, in an order that is fixed.
+  constexpr bool CAN_COLSUM = (EPI == EPI_GELU_GRAD || EPI == EPI_GELU_GRAD_TAB) && !WIDE && (64 % CPR == 0);
+  [[maybe_unused]] float cs[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+  [[maybe_unused]] bool want_colsum = false;
+  if constexpr (CAN_COLSUM) want_colsum = g.colsum != nullptr;
   fetch_group(0);
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
@@ -387,12 +397,41 @@ __device__ __forceinline__ void store_block_epilogue(const GemmArgs& g, v16f (&a
             stream_store(reinterpret_cast<v4f*>((float*)g.C + m * g.ldc + n), v);
         } else {
           v8h y = *US_LDS_PTR(const v8h, p);
-          epilogue_row8<EPI, AUX_FMT>(g, m * g.ldc + n, y, zpre[NEEDS_Z ? i % ZGROUP : 0][NEEDS_Z ? u : 0], lut);
+          const v8h r = epilogue_row8<EPI, AUX_FMT>(g, m * g.ldc + n, y, zpre[NEEDS_Z ? i % ZGROUP : 0][NEEDS_Z ? u : 0], lut);
+          if constexpr (CAN_COLSUM) {
+            if (want_colsum) {
+#pragma unroll
+              for (int k = 0; k < 8; ++k) cs[k] += (float)r[k];
+            }
+          }
         }
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     __builtin_amdgcn_wave_barrier();
+  }
+  if constexpr (CAN_COLSUM) {
+    if (want_colsum) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+#pragma unroll
+        for (int off = CPR; off < 64; off <<= 1) cs[k] += __shfl_xor(cs[k], off, 64);
+      const long n = n0 + wn0 + lane * 8;                       // lanes 0 .. CPR-1 hold the wave's WN columns
+      const long p0 = (m0 + wm0 + I0 * 32) / 32;                // first 32-row block this wave finished
+      const long prows = (g.M + 31) / 32;
+      if (lane < CPR && n < g.N) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+          if (p0 + i < prows) {
+            float* o = g.colsum + (p0 + i) * g.N + n;
+            const v4f lo = {i == 0 ? cs[0] : 0.0f, i == 0 ? cs[1] : 0.0f, i == 0 ? cs[2] : 0.0f, i == 0 ? cs[3] : 0.0f};
+            const v4f hi = {i == 0 ? cs[4] : 0.0f, i == 0 ? cs[5] : 0.0f, i == 0 ? cs[6] : 0.0f, i == 0 ? cs[7] : 0.0f};
+            *reinterpret_cast<v4f*>(o) = lo;
+            *reinterpret_cast<v4f*>(o + 4) = hi;
+          }
+        }
+      }
+    }
   }
 }
 

@@ -58,6 +58,7 @@ inline GemmArgs make_args(const GemmProblem& p, long k_per_split, int BM, int BN
   g.partial = (float*)p.workspace;
   g.table = (const uint8_t*)p.table;
   g.bias = (const _Float16*)p.bias;
+  g.colsum = (float*)p.colsum;
   if (p.batch > 1) {
     const long es = (p.a_dt == US_F16) ? 2 : 1;
     g.batch_a = p.batch_a * es;

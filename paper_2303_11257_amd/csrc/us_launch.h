@@ -36,6 +36,8 @@ hipError_t launch_softmax_xent(const void* X, const int* target, float* loss, vo
                                hipStream_t stream);
 size_t bias_grad_workspace_bytes(long b, long n);
 hipError_t launch_bias_grad(const void* G, us_dtype g_dt, void* dc, long b, long n, float beta, void* workspace, hipStream_t stream);
+// second half of launch_bias_grad alone: dc = fp16(beta * sum over the nblocks rows of partial[nblocks][n])
+hipError_t launch_bias_grad_reduce(const void* partial, void* dc, long nblocks, long n, float beta, hipStream_t stream);
 
 // One GEMM problem  C[M,N] = epilogue( scale * sum_k A(m,k) B(n,k) ).
 //   a_kc / b_kc: operand is K-contiguous (element (r,k) at base[r*ld + k]) or K-strided
@@ -64,6 +66,8 @@ struct GemmProblem {
   long batch;              // number of equally shaped, independent products (0 or 1: a single one); plain store only
   long batch_a, batch_b, batch_c;   // elements between consecutive problems
   const void* bias;        // forward product with FP16 result: optional FP16 row [N] added before the rounding, or NULL
+  void* colsum;            // GELU_GRAD: optional FP32 [ceil(M / 32)][N] that receives the column sums of the FP16 result per
+                           // 32-row block (every element written), or NULL
   void* table;             // table area of the workspace (us_device.h), or NULL: arithmetic epilogue
   bool tables_ready;       // the table area is already filled for this epi_scale
   size_t workspace_bytes;

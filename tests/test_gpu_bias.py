@@ -167,7 +167,7 @@ def test_bias_grad_exact_integers():
     assert np.array_equal(_bits(dc), _bits(exact)) and np.array_equal(_bits(dc), _bits(O.bias_grad(G, 2.0 ** -4)))
 
 
-def _ffn_bias_run(T, d, f, seed, fp8, tables=False):
+def _ffn_bias_run(T, d, f, seed, fp8, tables=False, store_dz16=True):
     X, W1, W2, G = synth.ffn_inputs(T, d, f, seed)
     b1, b2 = synth.normal(seed, 11, (f,), sigma=0.5), synth.normal(seed, 12, (d,), sigma=0.5)
     dev = {k: to_dev(v) for k, v in dict(X=X, W1=W1, W2=W2, G=G, b1=b1, b2=b2).items()}
@@ -192,7 +192,7 @@ def _ffn_bias_run(T, d, f, seed, fp8, tables=False):
     us.ffn_bias_fwd(ptr(dev["Xop"]), ptr(dev["W1op"]), ptr(dev["b1"]), ptr(dev["W2op"]), ptr(dev["b2"]), ptr(dev["Z"]), ptr(dev["H"]),
                     ptr(dev["Y"]), T, d, f, mode, ptr(ws), wsb, st)
     us.ffn_bias_bwd(ptr(dev["Xop"]), ptr(dev["W1op"]), ptr(dev["W2op"]), ptr(dev["Z"]), ptr(dev["H"]), ptr(dev["Gop"]), ptr(dev["G"]),
-                    ptr(dev["dZ16"]), ptr(dev["dZ8"]), ptr(dev["dX"]), ptr(dev["dW1"]), ptr(dev["dW2"]), ptr(dev["db1"]),
+                    ptr(dev["dZ16"]) if store_dz16 else None, ptr(dev["dZ8"]), ptr(dev["dX"]), ptr(dev["dW1"]), ptr(dev["dW2"]), ptr(dev["db1"]),
                     ptr(dev["db2"]), T, d, f, mode, ptr(ws), wsb, st)
     torch.cuda.synchronize()
     return dev, dict(X=X, W1=W1, W2=W2, G=G, b1=b1, b2=b2)
@@ -223,6 +223,21 @@ def test_ffn_with_biases_small_ragged_shape(fp8):
     assert_close(g["dX"], O.linear_bwd_dx(dZop, g["W1op"], bx1, gr, op), "dX")
     assert_close(g["dW1"], O.linear_bwd_dw(g["Xop"], dZop, bw1, op, gr), "dW1")
     assert_close(g["dW2"], O.linear_bwd_dw(g["H"], g["Gop"], bw2, op, gr), "dW2")
+
+
+@pytest.mark.parametrize("shape,tables", [((272, 144, 400), False), ((1024, 256, 2048), True), ((4096, 1024, 3072), True),
+                                          ((8192, 1024, 4096), True)])
+def test_db1_needs_no_stored_fp16_dz(shape, tables):
+    """The column sums of dZ are taken inside the epilogue that produces it: an FP8 step that stores only the E5M2 copy
+    of dZ gives the same db1, bit for bit, and the same other outputs.  Shapes: staged kernel with ragged tiles,
+    128 x 128 tiles, 256 x 128 tiles with two wave groups in a paired launch (arithmetic epilogue), the large tile with
+    the table-driven epilogue in a paired launch."""
+    T, d, f = shape
+    a, _ = _ffn_bias_run(T, d, f, 79, True, tables=tables)
+    b, _ = _ffn_bias_run(T, d, f, 79, True, tables=tables, store_dz16=False)
+    for k in ("db1", "db2", "dZ8", "dX", "dW1", "dW2"):
+        assert torch.equal(a[k].view(torch.uint8), b[k].view(torch.uint8)), k
+    assert _sum_close(b["db1"].cpu().numpy(), O.bias_grad(a["dZ16"].cpu().numpy(), O.bias_scale(T)))
 
 
 def test_ffn_with_biases_at_the_bert_large_shape_sampled():
