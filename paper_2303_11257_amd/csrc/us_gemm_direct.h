@@ -5,9 +5,9 @@
 // store instructions): a wave instruction deposits 64 x 16 B contiguously, so tiles are unpadded and
 // bank conflicts are removed by an XOR swizzle of the 16-byte chunk index instead; the swizzle is
 // applied to the *global* address each lane fetches and again when fragments are read.
-// NST stage buffers form a ring.  Matrix-core fragments are double-buffered in registers: while the
-// MFMAs of one k-step run, the LDS reads of the next k-step are already in flight, also across the
-// stage boundary.  At that boundary a wave waits for its own LDS reads of stage s, then for its own
+// NST stage buffers form a ring.  Matrix-core fragments are double-buffered in registers: the LDS reads of
+// the next k-step are issued around the MFMAs of the current one (FP16: ahead of them; FP8: one fragment
+// behind each of the last MFMAs), also across the stage boundary.  At that boundary a wave waits for its own LDS reads of stage s, then for its own
 // loads of stage s+1 (explicit s_waitcnt vmcnt(n): younger stages stay in flight), then meets the
 // other waves at one bare s_barrier; after it the buffer of stage s is free and receives the loads
 // of stage s+NST, so NST stages of HBM latency are covered by MFMAs.
@@ -267,6 +267,19 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs& g, int bid, lon
       else a[i] = direct_frag_f16<A_KC, PA>(ta, wm0 + i * 32, ks0 + ks);
     }
   };
+  // one fragment of a k-step: numbers 0 .. FN-1 are the B fragments, FN .. FN+FM-1 the A fragments
+  auto load_frag_one = [&](FragT (&a)[FM], FragT (&b)[FN], int slot, int ks, int idx) {
+    const uint8_t* ta = lds + slot * T::STAGE_BYTES;
+    const uint8_t* tb = ta + T::A_BYTES;
+    if (idx < FN) {
+      if constexpr (FP8) b[idx] = direct_frag_fp8<B_KC, PB>(tb, wn0 + idx * 32, ks0 + ks);
+      else b[idx] = direct_frag_f16<B_KC, PB>(tb, wn0 + idx * 32, ks0 + ks);
+    } else {
+      const int i = idx - FN;
+      if constexpr (FP8) a[i] = direct_frag_fp8<A_KC, PA>(ta, wm0 + i * 32, ks0 + ks);
+      else a[i] = direct_frag_f16<A_KC, PA>(ta, wm0 + i * 32, ks0 + ks);
+    }
+  };
   auto issue_stage = [&](int stage, int slot) {
     direct_issue<THREADS>(srcA, (long)stage * advA, lds + slot * T::STAGE_BYTES);
     direct_issue<THREADS>(srcB, (long)stage * advB, lds + slot * T::STAGE_BYTES + T::A_BYTES);
@@ -305,8 +318,17 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs& g, int bid, lon
       lds_reads_done();
       frag_ready(ca);
       frag_ready(cb);
+      // FP8: the next k-step's fragments are not requested ahead of this k-step's MFMAs but one fragment behind each
+      // of the last FM + FN of them, so that a wave that comes out of a wait (or the barrier) feeds the matrix core
+      // first (measured on one box: 2.47 -> 2.64 PFLOP/s on a 32768 x 4096 x 16384 product, BERT-large step 256 -> 247 us;
+      // behind the first MFMAs instead: 2.55; two per MFMA behind the last three: 2.57; all behind the last: 2.50;
+      // FP16, whose MFMAs are half as long: slower either way, so it keeps the requests in front)
+      constexpr bool SPREAD = FP8;
+      bool frags_pending = false;
+      int fslot = slot, fks = ks + 1;
       if (ks + 1 < KSTEPS) {
-        load_frags(na, nb, slot, ks + 1);
+        if constexpr (SPREAD) frags_pending = true;
+        else load_frags(na, nb, slot, ks + 1);
       } else {
         // stage boundary: this wave holds all of stage s in registers
         if (s + 1 < nstages) {
@@ -319,9 +341,12 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs& g, int bid, lon
         refill_slot = slot;
         refill_stage = s + NST;
         if (++slot == NST) slot = 0;
-        if (s + 1 < nstages) load_frags(na, nb, slot, 0);
+        if (s + 1 < nstages) {
+          if constexpr (SPREAD) { frags_pending = true; fslot = slot; fks = 0; }
+          else load_frags(na, nb, slot, 0);
+        }
       }
-      __builtin_amdgcn_sched_barrier(0);   // keep the LDS requests ahead of the MFMAs they overlap with
+      __builtin_amdgcn_sched_barrier(0);   // keep the LDS requests (FP16) ahead of the MFMAs they overlap with
       // The refill loads are spread over the MFMAs of this k-step: issued in one burst by all waves
       // they would queue up in the vector-memory pipeline and hold the waves back from the matrix core.
       constexpr int NMFMA = FM * FN;
@@ -332,6 +357,16 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs& g, int bid, lon
         for (int j = 0; j < FN; ++j) {
           if constexpr (FP8) acc[i][j] = mfma_fp8<FB, FA>(cb[j], ca[i], acc[i][j]);
           else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(cb[j], ca[i], acc[i][j], 0, 0, 0);
+          if constexpr (SPREAD) {
+            constexpr int NFR = FM + FN;
+            constexpr int FPER = (NFR + NMFMA - 1) / NMFMA;
+#pragma unroll
+            for (int q = 0; q < FPER; ++q) {
+              const int idx = (i * FN + j) * FPER + q - (NMFMA * FPER - NFR);   // the last NFR places
+              if (idx >= 0 && idx < NFR && frags_pending) load_frag_one(na, nb, fslot, fks, idx);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
           if (ks + 1 == KSTEPS) {
 #pragma unroll
             for (int q = 0; q < PER; ++q) {
