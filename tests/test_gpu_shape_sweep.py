@@ -25,6 +25,7 @@ BASE = [
     (6000, 128, 4000),    # forward: 384 large tiles with ragged edges, one stage of reduction
     (6144, 4096, 768),    # backward of one layer in one launch (large-tile grad_X, wave-split grad_W)
     (4096, 768, 2048),    # forward and grad_X on 256 x 128 / 128 x 128 tiles, grad_W on 96 tiles (K slices)
+    (6000, 2048, 1008),   # forward: 192 tiles of 256 x 128 with two wave groups, ragged in both dimensions
     (2304, 4000, 1024),   # paired backward with grad_W on 128 long (256 x 128) tiles, ragged; grad_X on 256 x 128 tiles
     (7936, 1008, 4096),   # paired backward as one round: 124 large grad_X tiles + 128 long grad_W tiles, both ragged
 ]
