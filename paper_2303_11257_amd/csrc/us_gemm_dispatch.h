@@ -28,9 +28,13 @@ using CfgW128 = GemmCfg<128, 128, 2, 2, 128, 4, 1, 2>;
 
 inline long ceil_div(long a, long b) { return (a + b - 1) / b; }
 
-// The large tile needs the output to cover the 256 CUs about one and a half times; below that the
+// The large tile needs the output to cover the 256 CUs about one and a half times, or at most once with three
+// quarters of them busy (BERT-base: 4096 x 3072 -> 192 tiles; backward of layer 2 there 67 -> 62 us); in between the
 // small tile (two workgroups per CU, four times as many tiles) keeps more of the chip busy.
-inline bool use_big_tile(long M, long N, int splits) { return ceil_div(M, 256) * ceil_div(N, 256) * splits >= 384; }
+inline bool use_big_tile(long M, long N, int splits) {
+  const long t = ceil_div(M, 256) * ceil_div(N, 256) * splits;
+  return t >= 384 || (t >= 192 && t <= 256);
+}
 
 // grad_W whose 128 x 128 tiles just about cover the CUs once (C3: 4096 x 1024 -> 256 tiles): instead of
 // cutting the long token reduction into slices that travel through HBM, two wave groups of one
