@@ -78,6 +78,15 @@ typedef struct {
 
 const char* us_status_string(us_status s);
 
+/* Diagnostics (host only).  Text describing the matmul kernels that the calling host thread's most recent matmul call
+ * (us_linear_*, us_ffn_*, us_matmul_batched, us_attention_*) enqueued, one entry per kernel joined by " + ":
+ *   kind:BMxBN:wk<wave groups>:st<stages>:<fp8|f16>:<NN|NT|TN>:<epilogue>[:f32]:s<K slices>
+ * kind is "direct" (direct-to-LDS loads), "staged" (register-staged fallback for ragged reduction lengths) or "pair"
+ * (grad_X and grad_W tiles in one launch).  The string belongs to the library and is valid until the thread's next
+ * matmul call.  For tests and tuning: it says which tile shape a problem was given (the choice of kernel is the
+ * library's; results do not depend on it beyond the order of the FP32 sums). */
+const char* us_last_launch(void);
+
 /*
  * Scale selection for matmul(X[b,m], W[m,n]) (Table A.2 "Linear"; Sec. 5.5 "Example").  Host only.
  *   mode 0: unconstrained  alpha = m^-1/2, beta_x = n^-1/2, beta_w = b^-1/2

@@ -47,6 +47,8 @@ def lib() -> ctypes.CDLL:
     fp = ctypes.POINTER(ctypes.c_float)
     L.us_status_string.argtypes = [i]
     L.us_status_string.restype = ctypes.c_char_p
+    L.us_last_launch.argtypes = []
+    L.us_last_launch.restype = ctypes.c_char_p
     L.us_linear_scales.argtypes = [l, l, l, i, fp, fp, fp]
     L.us_cast_fp8.argtypes = [vp, i, vp, i, sz, f, vp, vp]
     L.us_cast_fp8_batch.argtypes = [i, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(sz), ctypes.POINTER(i), vp]
@@ -95,6 +97,11 @@ def lib() -> ctypes.CDLL:
         getattr(L, name).restype = i
     _lib = L
     return L
+
+
+def last_launch() -> str:
+    """Which matmul kernels this thread's most recent matmul call enqueued (see us_last_launch in include/us.h)."""
+    return lib().us_last_launch().decode()
 
 
 def status_string(status: int) -> str:

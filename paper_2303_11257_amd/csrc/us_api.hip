@@ -3,6 +3,7 @@
 #include <math.h>
 #include <stdint.h>
 
+
 #include "us_device.h"
 #include "us_launch.h"
 
@@ -22,6 +23,8 @@ inline bool residual_weight_ok(float w) { return w > 0.0f && w <= 1.0f; }
 }  // namespace
 
 extern "C" {
+
+const char* us_last_launch(void) { return last_launch_record(); }
 
 const char* us_status_string(us_status s) {
   switch (s) {
@@ -109,16 +112,11 @@ size_t us_workspace_bytes(long b, long m, long n) {
   return (size_t)kTableAreaBytes + gemm_workspace_bytes(m, n, b);
 }
 
-us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, long n, us_dtype x_dt, us_dtype w_dt,
-                        us_dtype y_dt, float alpha, us_epilogue epi, float epi_scale, void* aux16, void* aux8,
-                        void* workspace, size_t workspace_bytes, void* stream) {
-  return us_linear_bias_fwd(X, W, nullptr, Y, b, m, n, x_dt, w_dt, y_dt, alpha, epi, epi_scale, aux16, aux8, workspace,
-                            workspace_bytes, stream);
-}
-
-us_status us_linear_bias_fwd(const void* X, const void* W, const void* bias, void* Y, long b, long m, long n, us_dtype x_dt,
-                             us_dtype w_dt, us_dtype y_dt, float alpha, us_epilogue epi, float epi_scale, void* aux16,
-                             void* aux8, void* workspace, size_t workspace_bytes, void* stream) {
+// us_linear_bias_fwd.  launch = false: the argument checks only (what a composite call runs for every one of its
+// products before it enqueues the first, so that a call that fails has touched no device memory).
+static us_status linear_fwd_impl(const void* X, const void* W, const void* bias, void* Y, long b, long m, long n, us_dtype x_dt,
+                                 us_dtype w_dt, us_dtype y_dt, float alpha, us_epilogue epi, float epi_scale, void* aux16,
+                                 void* aux8, void* workspace, size_t workspace_bytes, void* stream, bool launch) {
   const bool tables_ready = ((int)epi & US_EPI_TABLES_READY) != 0;
   const int act = ((int)epi >> 4) & 0xf;
   epi = (us_epilogue)((int)epi & 0xf);
@@ -158,7 +156,24 @@ us_status us_linear_bias_fwd(const void* X, const void* W, const void* bias, voi
   p.aux8 = (epi == US_EPI_GELU) ? aux8 : nullptr;
   p.table = (workspace && workspace_bytes >= (size_t)kTableAreaBytes) ? workspace : nullptr;
   p.tables_ready = tables_ready;
+  if (!launch) return US_OK;
   return from_hip(launch_gemm(p, as_stream(stream)));
+}
+
+us_status us_linear_fwd(const void* X, const void* W, void* Y, long b, long m, long n, us_dtype x_dt, us_dtype w_dt,
+                        us_dtype y_dt, float alpha, us_epilogue epi, float epi_scale, void* aux16, void* aux8,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+  begin_launch_record();
+  return linear_fwd_impl(X, W, nullptr, Y, b, m, n, x_dt, w_dt, y_dt, alpha, epi, epi_scale, aux16, aux8, workspace,
+                         workspace_bytes, stream, true);
+}
+
+us_status us_linear_bias_fwd(const void* X, const void* W, const void* bias, void* Y, long b, long m, long n, us_dtype x_dt,
+                             us_dtype w_dt, us_dtype y_dt, float alpha, us_epilogue epi, float epi_scale, void* aux16,
+                             void* aux8, void* workspace, size_t workspace_bytes, void* stream) {
+  begin_launch_record();
+  return linear_fwd_impl(X, W, bias, Y, b, m, n, x_dt, w_dt, y_dt, alpha, epi, epi_scale, aux16, aux8, workspace,
+                         workspace_bytes, stream, true);
 }
 
 // us_linear_bwd plus one internal option: colsum, FP32 [ceil(b / 32)][m], receives the column sums of the FP16 result of
@@ -167,7 +182,7 @@ us_status us_linear_bias_fwd(const void* X, const void* W, const void* bias, voi
 static us_status linear_bwd_impl(const void* X, const void* W, const void* G, void* dX, void* dW, long b, long m, long n,
                                  us_dtype x_dt, us_dtype w_dt, us_dtype g_dt, us_dtype out_dt, float beta_x, float beta_w,
                                  us_epilogue epi, float epi_scale, const void* Zpre, void* aux8, void* workspace,
-                                 size_t workspace_bytes, void* stream, void* colsum) {
+                                 size_t workspace_bytes, void* stream, void* colsum, bool launch = true) {
   const bool tables_ready = ((int)epi & US_EPI_TABLES_READY) != 0;
   const int act = ((int)epi >> 4) & 0xf;
   epi = (us_epilogue)((int)epi & 0xf);
@@ -227,6 +242,7 @@ static us_status linear_bwd_impl(const void* X, const void* W, const void* G, vo
     p.workspace = slices > 0 ? (void*)((char*)workspace + kTableAreaBytes) : nullptr;
     p.workspace_bytes = slices;
   }
+  if (!launch) return US_OK;       // (launch = false: the argument checks only, see linear_fwd_impl)
   if (do_dx && do_dw && gemm_pair_applicable(pdx, pdw)) return from_hip(launch_gemm_pair(pdx, pdw, st));
   if (do_dx && launch_gemm(pdx, st) != hipSuccess) return US_ERR_LAUNCH;
   if (do_dw && launch_gemm(pdw, st) != hipSuccess) return US_ERR_LAUNCH;
@@ -237,6 +253,7 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
                         us_dtype x_dt, us_dtype w_dt, us_dtype g_dt, us_dtype out_dt, float beta_x, float beta_w,
                         us_epilogue epi, float epi_scale, const void* Zpre, void* aux8, void* workspace,
                         size_t workspace_bytes, void* stream) {
+  begin_launch_record();
   return linear_bwd_impl(X, W, G, dX, dW, b, m, n, x_dt, w_dt, g_dt, out_dt, beta_x, beta_w, epi, epi_scale, Zpre, aux8,
                          workspace, workspace_bytes, stream, nullptr);
 }
@@ -313,36 +330,49 @@ us_status us_weighted_add(const void* a, const void* b, void* out, size_t n, us_
 
 us_status us_ffn_res_fwd(const void* Xskip, const void* X, const void* W1, const void* W2, void* Z, void* H, void* Out,
                          long T, long d, long f, float tau, int mode, void* workspace, size_t workspace_bytes, void* stream) {
+  begin_launch_record();
   if (!(tau > 0.0f && tau <= 1.0f)) return US_ERR_VALUE;
   const bool fp8 = (mode & US_FFN_FP8) != 0;
   const int ready = (mode & US_FFN_TABLES_READY) ? US_EPI_TABLES_READY : 0;
   const us_dtype op = fp8 ? US_E4M3 : US_F16;
-  us_status s = us_linear_fwd(X, W1, Z, T, d, f, op, op, US_F16, 0.0f, (us_epilogue)(US_EPI_GELU | ready), 0.0f, fp8 ? nullptr : H,
-                              fp8 ? H : nullptr, workspace, workspace_bytes, stream);
-  if (s != US_OK) return s;
-  // layer 2 with the interpolation fused: Out = sqrt(1-tau) Xskip + sqrt(tau) fp16(f^-1/2 H W2)
-  return us_linear_fwd(H, W2, Out, T, f, d, op, op, US_F16, 0.0f, US_EPI_RESIDUAL, (float)sqrt((double)tau), const_cast<void*>(Xskip),
-                       nullptr, nullptr, 0, stream);
+  // both products are checked before the first is enqueued (pass 0), then launched (pass 1)
+  for (int pass = 0; pass < 2; ++pass) {
+    const bool go = pass == 1;
+    us_status s = linear_fwd_impl(X, W1, nullptr, Z, T, d, f, op, op, US_F16, 0.0f, (us_epilogue)(US_EPI_GELU | ready), 0.0f,
+                                  fp8 ? nullptr : H, fp8 ? H : nullptr, workspace, workspace_bytes, stream, go);
+    if (s != US_OK) return s;
+    // layer 2 with the interpolation fused: Out = sqrt(1-tau) Xskip + sqrt(tau) fp16(f^-1/2 H W2)
+    s = linear_fwd_impl(H, W2, nullptr, Out, T, f, d, op, op, US_F16, 0.0f, US_EPI_RESIDUAL, (float)sqrt((double)tau),
+                        const_cast<void*>(Xskip), nullptr, nullptr, 0, stream, go);
+    if (s != US_OK) return s;
+  }
+  return US_OK;
 }
 
 us_status us_ffn_res_bwd(const void* X, const void* W1, const void* W2, const void* Z, const void* H, const void* Gskip,
                          const void* G, void* dZ16, void* dZ8, void* dXin, void* dW1, void* dW2, long T, long d, long f,
                          float tau, int mode, void* workspace, size_t workspace_bytes, void* stream) {
+  begin_launch_record();
   if (!(tau > 0.0f && tau <= 1.0f)) return US_ERR_VALUE;
   const bool fp8 = (mode & US_FFN_FP8) != 0;
   const int ready = (mode & US_FFN_TABLES_READY) ? US_EPI_TABLES_READY : 0;
   const us_dtype op = fp8 ? US_E4M3 : US_F16;
   const us_dtype gr = fp8 ? US_E5M2 : US_F16;
   if (fp8 ? !dZ8 : !dZ16) return US_ERR_NULL;
-  // the branch sees the incoming gradient unscaled: layer 2 backward exactly as in us_ffn_bwd
-  us_status s = us_linear_bwd(H, W2, G, dZ16, dW2, T, f, d, op, op, gr, US_F16, 0.0f, 0.0f,
-                              (us_epilogue)(US_EPI_GELU_GRAD | ready), 0.0f, Z, fp8 ? dZ8 : nullptr, workspace, workspace_bytes,
-                              stream);
-  if (s != US_OK) return s;
-  // layer 1 backward; grad_X leaves the branch through the interpolation with the skip path's gradient
   const void* dZ = fp8 ? dZ8 : dZ16;
-  return us_linear_bwd(X, W1, dZ, dXin, dW1, T, d, f, op, op, gr, US_F16, 0.0f, 0.0f, US_EPI_RESIDUAL, (float)sqrt((double)tau),
-                       Gskip, nullptr, workspace, workspace_bytes, stream);
+  for (int pass = 0; pass < 2; ++pass) {
+    const bool go = pass == 1;
+    // the branch sees the incoming gradient unscaled: layer 2 backward exactly as in us_ffn_bwd
+    us_status s = linear_bwd_impl(H, W2, G, dZ16, dW2, T, f, d, op, op, gr, US_F16, 0.0f, 0.0f,
+                                  (us_epilogue)(US_EPI_GELU_GRAD | ready), 0.0f, Z, fp8 ? dZ8 : nullptr, workspace, workspace_bytes,
+                                  stream, nullptr, go);
+    if (s != US_OK) return s;
+    // layer 1 backward; grad_X leaves the branch through the interpolation with the skip path's gradient
+    s = linear_bwd_impl(X, W1, dZ, dXin, dW1, T, d, f, op, op, gr, US_F16, 0.0f, 0.0f, US_EPI_RESIDUAL, (float)sqrt((double)tau),
+                        Gskip, nullptr, workspace, workspace_bytes, stream, nullptr, go);
+    if (s != US_OK) return s;
+  }
+  return US_OK;
 }
 
 size_t us_ffn_workspace_bytes(long T, long d, long f) {
@@ -358,53 +388,73 @@ us_status us_ffn_fwd(const void* X, const void* W1, const void* W2, void* Z, voi
 
 us_status us_ffn_bias_fwd(const void* X, const void* W1, const void* b1, const void* W2, const void* b2, void* Z, void* H,
                           void* Y, long T, long d, long f, int mode, void* workspace, size_t workspace_bytes, void* stream) {
+  begin_launch_record();
   const bool fp8 = (mode & US_FFN_FP8) != 0;
   const int ready = (mode & US_FFN_TABLES_READY) ? US_EPI_TABLES_READY : 0;
   const us_dtype op = fp8 ? US_E4M3 : US_F16;
-  // layer 1 with the GELU fused: Z = d^-1/2 X W1 (FP16), H = 1.7009 gelu(Z) as FP16 or as E4M3 codes
-  us_status s = us_linear_bias_fwd(X, W1, b1, Z, T, d, f, op, op, US_F16, 0.0f, (us_epilogue)(US_EPI_GELU | ready), 0.0f,
-                                   fp8 ? nullptr : H, fp8 ? H : nullptr, workspace, workspace_bytes, stream);
-  if (s != US_OK) return s;
-  // layer 2: Y = f^-1/2 H W2 (+ b2)
-  return us_linear_bias_fwd(H, W2, b2, Y, T, f, d, op, op, US_F16, 0.0f, US_EPI_NONE, 0.0f, nullptr, nullptr, nullptr, 0, stream);
+  for (int pass = 0; pass < 2; ++pass) {      // pass 0 checks both products, pass 1 launches them
+    const bool go = pass == 1;
+    // layer 1 with the GELU fused: Z = d^-1/2 X W1 (FP16), H = 1.7009 gelu(Z) as FP16 or as E4M3 codes
+    us_status s = linear_fwd_impl(X, W1, b1, Z, T, d, f, op, op, US_F16, 0.0f, (us_epilogue)(US_EPI_GELU | ready), 0.0f,
+                                  fp8 ? nullptr : H, fp8 ? H : nullptr, workspace, workspace_bytes, stream, go);
+    if (s != US_OK) return s;
+    // layer 2: Y = f^-1/2 H W2 (+ b2)
+    s = linear_fwd_impl(H, W2, b2, Y, T, f, d, op, op, US_F16, 0.0f, US_EPI_NONE, 0.0f, nullptr, nullptr, nullptr, 0, stream, go);
+    if (s != US_OK) return s;
+  }
+  return US_OK;
 }
 
-// us_ffn_bwd; dz_colsum as in linear_bwd_impl (column sums of dZ per 32-row block, FP32 [ceil(T / 32)][f]) or NULL
+// us_ffn_bwd; dz_colsum as in linear_bwd_impl (column sums of dZ per 32-row block, FP32 [ceil(T / 32)][f]) or NULL;
+// launch = false: the argument checks of both layers only
 static us_status ffn_bwd_impl(const void* X, const void* W1, const void* W2, const void* Z, const void* H, const void* G,
                               void* dZ16, void* dZ8, void* dX, void* dW1, void* dW2, long T, long d, long f, int mode,
-                              void* workspace, size_t workspace_bytes, void* stream, void* dz_colsum) {
+                              void* workspace, size_t workspace_bytes, void* stream, void* dz_colsum, bool launch) {
   const bool fp8 = (mode & US_FFN_FP8) != 0;
   const int ready = (mode & US_FFN_TABLES_READY) ? US_EPI_TABLES_READY : 0;
   const us_dtype op = fp8 ? US_E4M3 : US_F16;
   const us_dtype gr = fp8 ? US_E5M2 : US_F16;
   if (fp8 ? !dZ8 : !dZ16) return US_ERR_NULL;
-  // layer 2 backward: dH = d^-1/2 G W2^T, fused with GELU' -> dZ (FP16 + E5M2 copy); dW2 = T^-1/2 H^T G
-  us_status s = linear_bwd_impl(H, W2, G, dZ16, dW2, T, f, d, op, op, gr, US_F16, 0.0f, 0.0f,
-                                (us_epilogue)(US_EPI_GELU_GRAD | ready), 0.0f, Z,
-                                fp8 ? dZ8 : nullptr, workspace, workspace_bytes, stream, dz_colsum);
-  if (s != US_OK) return s;
-  // layer 1 backward: dX = f^-1/2 dZ W1^T; dW1 = T^-1/2 X^T dZ
   const void* dZ = fp8 ? dZ8 : dZ16;
-  return us_linear_bwd(X, W1, dZ, dX, dW1, T, d, f, op, op, gr, US_F16, 0.0f, 0.0f, US_EPI_NONE, 0.0f, nullptr, nullptr,
-                       workspace, workspace_bytes, stream);
+  for (int pass = 0; pass < (launch ? 2 : 1); ++pass) {
+    const bool go = pass == 1;
+    // layer 2 backward: dH = d^-1/2 G W2^T, fused with GELU' -> dZ (FP16 + E5M2 copy); dW2 = T^-1/2 H^T G
+    us_status s = linear_bwd_impl(H, W2, G, dZ16, dW2, T, f, d, op, op, gr, US_F16, 0.0f, 0.0f,
+                                  (us_epilogue)(US_EPI_GELU_GRAD | ready), 0.0f, Z,
+                                  fp8 ? dZ8 : nullptr, workspace, workspace_bytes, stream, dz_colsum, go);
+    if (s != US_OK) return s;
+    // layer 1 backward: dX = f^-1/2 dZ W1^T; dW1 = T^-1/2 X^T dZ
+    s = linear_bwd_impl(X, W1, dZ, dX, dW1, T, d, f, op, op, gr, US_F16, 0.0f, 0.0f, US_EPI_NONE, 0.0f, nullptr, nullptr,
+                        workspace, workspace_bytes, stream, nullptr, go);
+    if (s != US_OK) return s;
+  }
+  return US_OK;
 }
 
 us_status us_ffn_bwd(const void* X, const void* W1, const void* W2, const void* Z, const void* H, const void* G,
                      void* dZ16, void* dZ8, void* dX, void* dW1, void* dW2, long T, long d, long f, int mode,
                      void* workspace, size_t workspace_bytes, void* stream) {
-  return ffn_bwd_impl(X, W1, W2, Z, H, G, dZ16, dZ8, dX, dW1, dW2, T, d, f, mode, workspace, workspace_bytes, stream, nullptr);
+  begin_launch_record();
+  return ffn_bwd_impl(X, W1, W2, Z, H, G, dZ16, dZ8, dX, dW1, dW2, T, d, f, mode, workspace, workspace_bytes, stream, nullptr,
+                      true);
 }
 
-us_status us_bias_grad(const void* G, us_dtype g_dt, void* dc, long b, long n, float beta_c, void* workspace,
-                       size_t workspace_bytes, void* stream) {
+static us_status bias_grad_impl(const void* G, us_dtype g_dt, void* dc, long b, long n, float beta_c, void* workspace,
+                                size_t workspace_bytes, void* stream, bool launch) {
   if (g_dt != US_F16 && g_dt != US_E4M3 && g_dt != US_E5M2) return US_ERR_DTYPE;
   if (b < 0 || n < 0 || !mult16(n)) return US_ERR_SHAPE;
   if (n == 0) return US_OK;
   if (!dc || (b > 0 && !G)) return US_ERR_NULL;
   if (!aligned16(G) || !aligned16(dc) || !aligned16(workspace)) return US_ERR_ALIGN;
   if (b > 0 && (!workspace || workspace_bytes < bias_grad_workspace_bytes(b, n))) return US_ERR_WORKSPACE;
+  if (!launch) return US_OK;
   const float beta = (beta_c > 0.0f) ? beta_c : (float)(1.0 / sqrt((double)(b > 0 ? b : 1)));
   return from_hip(launch_bias_grad(G, g_dt, dc, b, n, beta, workspace, as_stream(stream)));
+}
+
+us_status us_bias_grad(const void* G, us_dtype g_dt, void* dc, long b, long n, float beta_c, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  return bias_grad_impl(G, g_dt, dc, b, n, beta_c, workspace, workspace_bytes, stream, true);
 }
 
 size_t us_bias_grad_workspace_bytes(long b, long n) { return bias_grad_workspace_bytes(b, n); }
@@ -412,10 +462,12 @@ size_t us_bias_grad_workspace_bytes(long b, long n) { return bias_grad_workspace
 us_status us_ffn_bias_bwd(const void* X, const void* W1, const void* W2, const void* Z, const void* H, const void* G,
                           const void* G16, void* dZ16, void* dZ8, void* dX, void* dW1, void* dW2, void* db1, void* db2,
                           long T, long d, long f, int mode, void* workspace, size_t workspace_bytes, void* stream) {
+  begin_launch_record();
   // the bias gradients are sums of the FP16 gradients (the FP8 copies feed the matmuls only)
   if (db2 && !G16) return US_ERR_NULL;
-  if ((mode & US_FFN_FP8) ? !dZ8 : !dZ16) return US_ERR_NULL;     // the operand of the layer-1 products (before any launch)
+  if ((mode & US_FFN_FP8) ? !dZ8 : !dZ16) return US_ERR_NULL;     // the operand of the layer-1 products
   if (T < 0 || d < 0 || f < 0) return US_ERR_SHAPE;
+  if (!aligned16(db1) || !aligned16(db2)) return US_ERR_ALIGN;
   // workspace: what us_ffn_bwd uses (tables, grad_W slices), then the area of the column sums
   const size_t base = (us_ffn_workspace_bytes(T, d, f) + 255) & ~(size_t)255;
   char* scratch = workspace ? (char*)workspace + base : nullptr;
@@ -423,19 +475,26 @@ us_status us_ffn_bias_bwd(const void* X, const void* W1, const void* W2, const v
     if (!workspace || workspace_bytes < us_ffn_bias_workspace_bytes(T, d, f)) return US_ERR_WORKSPACE;
   }
   const size_t scratch_bytes = workspace_bytes > base ? workspace_bytes - base : 0;
-  us_status s = US_OK;
-  if (db2) {     // first: the area is free until the matmul below fills it
-    s = us_bias_grad(G16, US_F16, db2, T, d, 0.0f, scratch, scratch_bytes, stream);
-    if (s != US_OK) return s;
-  }
   // db1: the epilogue that produces dZ adds up its columns per 32-row block on the way (whether or not the FP16 dZ is
   // stored), the sum over the blocks follows the matmuls
   const bool fused = db1 && T > 0 && f > 0;
+  // every argument of every step is checked before the first launch
+  us_status s = US_OK;
+  if (db2) {
+    s = bias_grad_impl(G16, US_F16, db2, T, d, 0.0f, scratch, scratch_bytes, stream, false);
+    if (s != US_OK) return s;
+  }
   s = ffn_bwd_impl(X, W1, W2, Z, H, G, dZ16, dZ8, dX, dW1, dW2, T, d, f, mode, workspace, workspace_bytes, stream,
-                   fused ? scratch : nullptr);
+                   fused ? scratch : nullptr, false);
+  if (s != US_OK) return s;
+  if (db2) {     // first: the area is free until the matmul below fills it
+    s = bias_grad_impl(G16, US_F16, db2, T, d, 0.0f, scratch, scratch_bytes, stream, true);
+    if (s != US_OK) return s;
+  }
+  s = ffn_bwd_impl(X, W1, W2, Z, H, G, dZ16, dZ8, dX, dW1, dW2, T, d, f, mode, workspace, workspace_bytes, stream,
+                   fused ? scratch : nullptr, true);
   if (s != US_OK) return s;
   if (db1 && f > 0) {
-    if (!aligned16(db1)) return US_ERR_ALIGN;
     const float beta = (float)(1.0 / sqrt((double)(T > 0 ? T : 1)));
     s = from_hip(launch_bias_grad_reduce(scratch, db1, T > 0 ? (T + 31) / 32 : 0, f, beta, as_stream(stream)));
   }
@@ -476,8 +535,8 @@ us_status us_softmax_xent(const void* X, const int* target, float* loss, void* d
   return from_hip(launch_softmax_xent(X, target, loss, dX, rows, s, s1 > 0.0f ? s1 : 1.0f, b, as_stream(stream)));
 }
 
-us_status us_matmul_batched(const void* A, const void* B, void* C, long batch, long M, long N, long K, int trans_a, int trans_b,
-                            us_dtype a_dt, us_dtype b_dt, us_dtype c_dt, float scale, void* stream) {
+static us_status matmul_batched_impl(const void* A, const void* B, void* C, long batch, long M, long N, long K, int trans_a,
+                                     int trans_b, us_dtype a_dt, us_dtype b_dt, us_dtype c_dt, float scale, void* stream) {
   if ((trans_a != 0 && trans_a != 1) || (trans_b != 0 && trans_b != 1) || (trans_a && trans_b)) return US_ERR_SHAPE;
   const bool f16 = (a_dt == US_F16 && b_dt == US_F16);
   // the FP8 pairs are those of the three layer products: forward E4M3 x E4M3, grad_X E5M2 x E4M3, grad_W E4M3 x E5M2
@@ -507,36 +566,50 @@ us_status us_matmul_batched(const void* A, const void* B, void* C, long batch, l
   return from_hip(launch_gemm(p, as_stream(stream)));
 }
 
+us_status us_matmul_batched(const void* A, const void* B, void* C, long batch, long M, long N, long K, int trans_a, int trans_b,
+                            us_dtype a_dt, us_dtype b_dt, us_dtype c_dt, float scale, void* stream) {
+  begin_launch_record();
+  return matmul_batched_impl(A, B, C, batch, M, N, K, trans_a, trans_b, a_dt, b_dt, c_dt, scale, stream);
+}
+
 us_status us_attention_fwd(const void* Q, const void* K, const void* V, void* A, void* P, void* O, long heads, long s, long d,
                            void* stream) {
-  if (heads < 0 || s < 0 || d < 0 || !mult16(s) || !mult16(d) || s > US_SOFTMAX_MAX) return US_ERR_SHAPE;
+  begin_launch_record();
+  // everything the three steps below check is checked here first: a failing call launches nothing
+  if (heads < 0 || heads > 65535 || s < 0 || d < 0 || !mult16(s) || !mult16(d) || s > US_SOFTMAX_MAX) return US_ERR_SHAPE;
   if (heads == 0 || s == 0 || d == 0) return US_OK;
   if (!Q || !K || !V || !A || !P || !O) return US_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(A) || !aligned16(P) || !aligned16(O)) return US_ERR_ALIGN;
   const float rs = (float)(1.0 / sqrt((double)s)), rd = (float)(1.0 / sqrt((double)d));
   // scores A = d^-1/2 Q K^T, probabilities P = s softmax(A), output O = s^-1/2 P V
-  us_status st = us_matmul_batched(Q, K, A, heads, s, s, d, 0, 1, US_F16, US_F16, US_F16, rd, stream);
+  us_status st = matmul_batched_impl(Q, K, A, heads, s, s, d, 0, 1, US_F16, US_F16, US_F16, rd, stream);
   if (st != US_OK) return st;
   st = us_softmax_fwd(A, P, heads * s, s, 0.0f, 0.0f, stream);
   if (st != US_OK) return st;
-  return us_matmul_batched(P, V, O, heads, s, d, s, 0, 0, US_F16, US_F16, US_F16, rs, stream);
+  return matmul_batched_impl(P, V, O, heads, s, d, s, 0, 0, US_F16, US_F16, US_F16, rs, stream);
 }
 
 us_status us_attention_bwd(const void* Q, const void* K, const void* V, const void* A, const void* P, const void* dO, void* dP,
                            void* dA, void* dQ, void* dK, void* dV, long heads, long s, long d, void* stream) {
-  if (heads < 0 || s < 0 || d < 0 || !mult16(s) || !mult16(d) || s > US_SOFTMAX_MAX) return US_ERR_SHAPE;
+  begin_launch_record();
+  // everything the five steps below check is checked here first: a failing call launches nothing
+  if (heads < 0 || heads > 65535 || s < 0 || d < 0 || !mult16(s) || !mult16(d) || s > US_SOFTMAX_MAX) return US_ERR_SHAPE;
   if (heads == 0 || s == 0 || d == 0) return US_OK;
   if (!Q || !K || !V || !A || !P || !dO || !dP || !dA || !dQ || !dK || !dV) return US_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(A) || !aligned16(P) || !aligned16(dO) || !aligned16(dP) ||
+      !aligned16(dA) || !aligned16(dQ) || !aligned16(dK) || !aligned16(dV))
+    return US_ERR_ALIGN;
   const float rs = (float)(1.0 / sqrt((double)s)), rd = (float)(1.0 / sqrt((double)d));
   // dV = s^-1/2 P^T dO;  dP = d^-1/2 dO V^T;  dA = s * softmax'(A)(dP);  dQ = s^-1/2 dA K;  dK = s^-1/2 dA^T Q
-  us_status st = us_matmul_batched(P, dO, dV, heads, s, d, s, 1, 0, US_F16, US_F16, US_F16, rs, stream);
+  us_status st = matmul_batched_impl(P, dO, dV, heads, s, d, s, 1, 0, US_F16, US_F16, US_F16, rs, stream);
   if (st != US_OK) return st;
-  st = us_matmul_batched(dO, V, dP, heads, s, s, d, 0, 1, US_F16, US_F16, US_F16, rd, stream);
+  st = matmul_batched_impl(dO, V, dP, heads, s, s, d, 0, 1, US_F16, US_F16, US_F16, rd, stream);
   if (st != US_OK) return st;
   st = us_softmax_bwd(A, dP, dA, heads * s, s, 0.0f, 0.0f, stream);
   if (st != US_OK) return st;
-  st = us_matmul_batched(dA, K, dQ, heads, s, d, s, 0, 0, US_F16, US_F16, US_F16, rs, stream);
+  st = matmul_batched_impl(dA, K, dQ, heads, s, d, s, 0, 0, US_F16, US_F16, US_F16, rs, stream);
   if (st != US_OK) return st;
-  return us_matmul_batched(dA, Q, dK, heads, s, d, s, 1, 0, US_F16, US_F16, US_F16, rs, stream);
+  return matmul_batched_impl(dA, Q, dK, heads, s, d, s, 1, 0, US_F16, US_F16, US_F16, rs, stream);
 }
 
 us_status us_sum_fwd(const void* X, void* Y, long rows, long n, float alpha, void* stream) {

@@ -39,6 +39,7 @@ struct GemmArgs {
   float* colsum;         // EPI_GELU_GRAD / _TAB: optional FP32 [ceil(M / 32)][N], column sums of the FP16 result per 32-row block
   int xcd_gm, xcd_gn;    // XCD rectangle split of the tile grid (0,0 = one rectangle)
   int grp_w;             // width of the column bands the rectangle is walked in
+  int nxcd;              // XCDs of the device (workgroup id modulo this = the XCD a workgroup runs on)
 };
 
 // Problem number blockIdx.z of a batch of equally shaped, independent products (plain-store epilogue only).
@@ -73,18 +74,18 @@ __device__ __forceinline__ v16f mfma_fp8(v8i a, v8i b, v16f c) {
 }
 
 // ---- workgroup -> output tile ------------------------------------------------------------------------
-// Workgroups are handed to the 8 XCDs round-robin by linear id, and every XCD has its own L2.  When
+// Workgroups are handed to the device's XCDs round-robin by linear id, and every XCD has its own L2.  When
 // the tile grid divides evenly (host: choose_xcd_grid), XCD x gets a compact rectangle of
 // (tiles_m/gm) x (tiles_n/gn) tiles; with gm == 0 the whole grid is one rectangle.  Inside a
 // rectangle the tiles are walked in column bands `grp_w` tiles wide, N-fastest within a band, so the
 // ~32-64 workgroups that run at the same time on one XCD form a compact block and share the A and B
 // panels they stream through that XCD's L2.
-__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int gm, int gn, int grp_w, int& tm,
-                                              int& tn) {
+__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int gm, int gn, int grp_w, int nxcd,
+                                              int& tm, int& tn) {
   int rm = tiles_m, rn = tiles_n, base_m = 0, base_n = 0, idx = bid;
   if (gm != 0) {
-    const int xcd = bid & 7;
-    idx = bid >> 3;
+    const int xcd = bid % nxcd;
+    idx = bid / nxcd;
     rm = tiles_m / gm;
     rn = tiles_n / gn;
     base_m = (xcd % gm) * rm;
@@ -97,14 +98,15 @@ __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n,
   tn = base_n + band * grp_w + r % w;
 }
 
-// Host side: the split gm x gn = 8 that divides the tile grid and minimises the number of operand
+// Host side: the split gm x gn = number of XCDs that divides the tile grid and minimises the number of operand
 // panels one XCD touches; gm = gn = 0 when the grid does not divide.
-inline void choose_xcd_grid(long tiles_m, long tiles_n, int& gm, int& gn) {
+inline void choose_xcd_grid(long tiles_m, long tiles_n, int nxcd, int& gm, int& gn) {
   gm = gn = 0;
-  if ((tiles_m * tiles_n) % 8 != 0) return;
+  if (nxcd < 2 || (tiles_m * tiles_n) % nxcd != 0) return;
   long best = -1;
-  for (int c = 1; c <= 8; c <<= 1) {
-    const int cm = c, cn = 8 / c;
+  for (int c = 1; c <= nxcd; ++c) {
+    if (nxcd % c) continue;
+    const int cm = c, cn = nxcd / c;
     if (tiles_m % cm || tiles_n % cn) continue;
     const long cost = tiles_m / cm + tiles_n / cn;
     if (best < 0 || cost < best) { best = cost; gm = cm; gn = cn; }

@@ -214,7 +214,7 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs& g, int bid, lon
 
   const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
   int tm, tn;
-  tile_of_block(bid, tiles_m, tiles_n, g.xcd_gm, g.xcd_gn, g.grp_w, tm, tn);
+  tile_of_block(bid, tiles_m, tiles_n, g.xcd_gm, g.xcd_gn, g.grp_w, g.nxcd, tm, tn);
   const long m0 = (long)tm * BM, n0 = (long)tn * BN;
   const long k_begin = split * g.k_per_split;
   const long k_end = (k_begin + g.k_per_split < g.K) ? k_begin + g.k_per_split : g.K;
@@ -441,11 +441,13 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_direct_kernel(Ge
 // epilogues (GELU' over a large output: a burst of HBM reads, vector ALU work, HBM writes) no longer
 // hit every CU at the same moment, while launched on their own all CUs run in lockstep.  (Interleaving
 // A and B tiles more finely was measured to be slower than either.)
-// nb must be a multiple of 8, so that both problems keep their XCD-aware tile walk.
+// nb must be a multiple of the number of XCDs, so that both problems keep their XCD-aware tile walk.
 template <class Cfg, bool FP8, int FA, int FB, bool A_KC, bool B_KC, int EPI, bool WIDE>
 struct GemmKind {
   using Tile = DirectTile<Cfg, FP8, A_KC, B_KC, WIDE, EPI>;
   static constexpr int THREADS = Cfg::THREADS, BM = Cfg::BM, BN = Cfg::BN;
+  static constexpr int WAVES_K = Cfg::WAVES_K, NST = Cfg::NST, EPI_ = EPI;
+  static constexpr bool IS_FP8 = FP8, A_KC_ = A_KC, B_KC_ = B_KC;
   __device__ static __forceinline__ void run(const GemmArgs& g, int bid, uint8_t* lds) {
     gemm_direct_tile<Cfg, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(g, bid, 0, lds);
   }

@@ -28,20 +28,23 @@ using CfgW128 = GemmCfg<128, 128, 2, 2, 128, 4, 1, 2>;
 
 inline long ceil_div(long a, long b) { return (a + b - 1) / b; }
 
-// The large tile needs the output to cover the 256 CUs about one and a half times, or at most once with three
-// quarters of them busy (BERT-base: 4096 x 3072 -> 192 tiles; backward of layer 2 there 67 -> 62 us); in between the
-// small tile (two workgroups per CU, four times as many tiles) keeps more of the chip busy.
+// All windows below are stated in units of the device's CU count (MI355X: 256), read from the device.
+inline long cu_count() { return device_info().cus; }
+
+// The large tile needs the output to cover the CUs about one and a half times, or at most once with three
+// quarters of them busy (BERT-base on 256 CUs: 4096 x 3072 -> 192 tiles; backward of layer 2 there 67 -> 62 us); in
+// between the small tile (two workgroups per CU, four times as many tiles) keeps more of the chip busy.
 inline bool use_big_tile(long M, long N, int splits) {
-  const long t = ceil_div(M, 256) * ceil_div(N, 256) * splits;
-  return t >= 384 || (t >= 192 && t <= 256);
+  const long t = ceil_div(M, 256) * ceil_div(N, 256) * splits, cu = cu_count();
+  return 2 * t >= 3 * cu || (4 * t >= 3 * cu && t <= cu);
 }
 
 // grad_W whose 128 x 128 tiles just about cover the CUs once (C3: 4096 x 1024 -> 256 tiles): instead of
 // cutting the long token reduction into slices that travel through HBM, two wave groups of one
 // workgroup share it and add up in LDS.
 inline bool use_wave_split_tile(long M, long N, long K) {
-  const long tiles = ceil_div(M, 128) * ceil_div(N, 128);
-  return !use_big_tile(M, N, 1) && K >= 1024 && K % 256 == 0 && tiles >= 128 && tiles <= 256;
+  const long tiles = ceil_div(M, 128) * ceil_div(N, 128), cu = cu_count();
+  return !use_big_tile(M, N, 1) && K >= 1024 && K % 256 == 0 && 2 * tiles >= cu && tiles <= cu;
 }
 
 inline GemmArgs make_args(const GemmProblem& p, long k_per_split, int BM, int BN) {
@@ -69,7 +72,8 @@ inline GemmArgs make_args(const GemmProblem& p, long k_per_split, int BM, int BN
     g.batch_b = p.batch_b * es;
     g.batch_c = p.batch_c * (p.c_dt == US_F32 ? 4 : 2);
   }
-  choose_xcd_grid(ceil_div(p.M, BM), ceil_div(p.N, BN), g.xcd_gm, g.xcd_gn);
+  g.nxcd = device_info().xcds;
+  choose_xcd_grid(ceil_div(p.M, BM), ceil_div(p.N, BN), g.nxcd, g.xcd_gm, g.xcd_gn);
   // bands 8 tiles wide: the 32 (one per CU) or 64 (two per CU) tiles that run together on an XCD form 4 x 8 or 8 x 8.
   // (Measured for the large tile: 4 wide was 3 us slower on the 8192 x 4096 x 1024 product with the GELU epilogue,
   // 16 and 32 equal to 8; the other tile shapes show no difference between 2 and 16.)
@@ -86,12 +90,9 @@ hipError_t launch_one(const GemmProblem& p, int splits, long k_per_split, hipStr
   void (*kern)(GemmArgs);
   if constexpr (DIRECT) kern = gemm_direct_kernel<Cfg, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>;
   else kern = gemm_staged_kernel<Cfg, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>;
-  static bool configured = false;  // raising the dynamic-LDS limit is a per-function, once-only call
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  note_gemm_launch(DIRECT ? "direct" : "staged", Cfg::BM, Cfg::BN, Cfg::WAVES_K, Cfg::NST, FP8, A_KC, B_KC, EPI, WIDE, splits);
+  static FuncConfig cfg;           // raising the dynamic-LDS limit: once per function and device
+  if (hipError_t e = cfg.ensure((const void*)kern, LDS); e != hipSuccess) return e;
   const GemmArgs g = make_args(p, k_per_split, Cfg::BM, Cfg::BN);
   const long tiles = ceil_div(p.M, Cfg::BM) * ceil_div(p.N, Cfg::BN);
   dim3 grid((unsigned)tiles, (unsigned)splits, (unsigned)(p.batch > 1 ? p.batch : 1));
@@ -109,14 +110,14 @@ hipError_t launch_sized(const GemmProblem& p, int splits, long k_per_split, hipS
     return launch_one<true, CfgD256, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
   if (batched) return launch_one<true, CfgD128, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
   if constexpr (FP8 && (A_KC || B_KC) && (EPI == EPI_STORE || EPI == EPI_RESIDUAL) && !WIDE) {
-    // an output of about 256 tiles of 256 x 128 (BERT-large: Linear 2, 8192 x 1024): one tile per CU, two wave groups
+    // an output of about one tile of 256 x 128 per CU (BERT-large: Linear 2, 8192 x 1024 -> 256): two wave groups
     // (40 against 43 us forward, 35 against 37 us in the grad_X layout; FP8 only, not measured for FP16)
     const long t_mid = ceil_div(p.M, 256) * ceil_div(p.N, 128);
-    if (splits == 1 && t_mid >= 192 && t_mid <= 256 && p.K >= 1024)
+    if (splits == 1 && 4 * t_mid >= 3 * cu_count() && t_mid <= cu_count() && p.K >= 1024)
       return launch_one<true, CfgM256, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
   }
   if constexpr ((A_KC || B_KC) && (EPI == EPI_STORE || EPI == EPI_RESIDUAL) && !WIDE) {
-    if (splits == 1 && ceil_div(p.M, 128) * ceil_div(p.N, 128) <= 256 && p.K >= 1024)
+    if (splits == 1 && ceil_div(p.M, 128) * ceil_div(p.N, 128) <= cu_count() && p.K >= 1024)
       return launch_one<true, CfgW128, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
   }
   if constexpr (!A_KC && !B_KC && EPI == EPI_STORE) {

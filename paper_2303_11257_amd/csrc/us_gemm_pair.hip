@@ -9,12 +9,10 @@ namespace {
 template <class KA, class KB>
 hipError_t launch_pair(const GemmProblem& dx, const GemmProblem& dw, hipStream_t st) {
   constexpr int LDS = KA::Tile::LDS_BYTES > KB::Tile::LDS_BYTES ? KA::Tile::LDS_BYTES : KB::Tile::LDS_BYTES;
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_pair_kernel<KA, KB>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  note_gemm_launch("pair", KA::BM, KA::BN, KA::WAVES_K, KA::NST, KA::IS_FP8, KA::A_KC_, KA::B_KC_, KA::EPI_, false, 1);
+  note_gemm_launch("pair", KB::BM, KB::BN, KB::WAVES_K, KB::NST, KB::IS_FP8, KB::A_KC_, KB::B_KC_, KB::EPI_, false, 1);
+  static FuncConfig cfg;
+  if (hipError_t e = cfg.ensure((const void*)gemm_pair_kernel<KA, KB>, LDS); e != hipSuccess) return e;
   const GemmArgs a = make_args(dx, dx.K, KA::BM, KA::BN);
   const GemmArgs b = make_args(dw, dw.K, KB::BM, KB::BN);
   const long tiles_a = ceil_div(dx.M, KA::BM) * ceil_div(dx.N, KA::BN), tiles_b = ceil_div(dw.M, KB::BM) * ceil_div(dw.N, KB::BN);
@@ -28,21 +26,22 @@ hipError_t launch_pair(const GemmProblem& dx, const GemmProblem& dw, hipStream_t
 // when it would have ended with grad_W spread over all CUs, minus the CU time saved.  With fewer than 112 tiles the
 // long tiles outlast the rest of the launch (BERT-base, 72 tiles: measured slower).
 bool long_tile_ok(const GemmProblem& dw) {
-  const long t = ceil_div(dw.M, 256) * ceil_div(dw.N, 128);
-  return t >= 112 && t <= 128 && t % 8 == 0;
+  const long t = ceil_div(dw.M, 256) * ceil_div(dw.N, 128), cu = cu_count();
+  return 16 * t >= 7 * cu && 2 * t <= cu && t % device_info().xcds == 0;
 }
 
 // grad_X without an activation derivative whose 256 x 256 tiles, together with grad_W's long tiles, give every CU one
 // tile of about the same length (BERT-large layer 1: 128 + 128)
 bool one_round_ok(const GemmProblem& dx, const GemmProblem& dw) {
   const long t = ceil_div(dx.M, 256) * ceil_div(dx.N, 256) + ceil_div(dw.M, 256) * ceil_div(dw.N, 128);
-  return long_tile_ok(dw) && (dx.epi == US_EPI_NONE || dx.epi == US_EPI_RESIDUAL) && t >= 224 && t <= 256 && dx.K >= 2048;
+  return long_tile_ok(dw) && (dx.epi == US_EPI_NONE || dx.epi == US_EPI_RESIDUAL) && 8 * t >= 7 * cu_count() && t <= cu_count() &&
+         dx.K >= 2048;
 }
 
 // grad_X without an epilogue on so few 128 x 128 tiles that the CUs get at most one each (wave-split small tile)
 bool small_tile_ok(const GemmProblem& dx) {
   const long t = ceil_div(dx.M, 128) * ceil_div(dx.N, 128);
-  return dx.epi == US_EPI_NONE && t <= 256 && dx.K >= 1024 && !use_big_tile(dx.M, dx.N, 1);
+  return dx.epi == US_EPI_NONE && t <= cu_count() && dx.K >= 1024 && !use_big_tile(dx.M, dx.N, 1);
 }
 
 template <bool FP8, class KW>
@@ -80,7 +79,7 @@ hipError_t launch_pair_typed(const GemmProblem& dx, const GemmProblem& dw, hipSt
 // grad_X without an epilogue whose 256 x 128 tiles cover the CUs about once
 bool mid_tile_ok(const GemmProblem& dx) {
   const long t = ceil_div(dx.M, 256) * ceil_div(dx.N, 128);
-  return (dx.epi == US_EPI_NONE || dx.epi == US_EPI_RESIDUAL) && t >= 192 && t <= 320;
+  return (dx.epi == US_EPI_NONE || dx.epi == US_EPI_RESIDUAL) && 4 * t >= 3 * cu_count() && 4 * t <= 5 * cu_count();
 }
 
 }  // namespace
@@ -94,13 +93,13 @@ bool gemm_pair_applicable(const GemmProblem& dx, const GemmProblem& dw) {
   const bool big = use_big_tile(dx.M, dx.N, 1);
   const long t_mid = ceil_div(dx.M, 256) * ceil_div(dx.N, 128);
   // grad_X with the arithmetic activation-derivative epilogue on 256 x 128 tiles (an output too small for the large tile)
-  const bool mid_act = dx.epi == US_EPI_GELU_GRAD && !big && t_mid >= 192 && t_mid <= 512;
+  const bool mid_act = dx.epi == US_EPI_GELU_GRAD && !big && 4 * t_mid >= 3 * cu_count() && t_mid <= 2 * cu_count();
   const bool small_pair = (small_tile_ok(dx) && !mid_tile_ok(dx)) || mid_act;
   if (dx.K <= 0 || dx.K % bk || !(big || mid_tile_ok(dx) || small_pair || one_round_ok(dx, dw))) return false;
   if (dx.epi == US_EPI_GELU_GRAD && big && (!dx.table || dx.act != 0)) return false;   // large tile: table-driven epilogue only
   if (dx.epi != US_EPI_NONE && dx.epi != US_EPI_GELU_GRAD && dx.epi != US_EPI_RESIDUAL) return false;
   if (!use_wave_split_tile(dw.M, dw.N, dw.K)) return false;
-  return long_tile_ok(dw) || (ceil_div(dw.M, 128) * ceil_div(dw.N, 128)) % 8 == 0;
+  return long_tile_ok(dw) || (ceil_div(dw.M, 128) * ceil_div(dw.N, 128)) % device_info().xcds == 0;
 }
 
 hipError_t launch_gemm_pair(const GemmProblem& dx, const GemmProblem& dw, hipStream_t st) {

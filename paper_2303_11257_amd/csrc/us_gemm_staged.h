@@ -128,7 +128,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::MINB) gemm_staged_kernel(Ge
 
   const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
   int tm, tn;
-  tile_of_block((int)blockIdx.x, tiles_m, tiles_n, g.xcd_gm, g.xcd_gn, g.grp_w, tm, tn);
+  tile_of_block((int)blockIdx.x, tiles_m, tiles_n, g.xcd_gm, g.xcd_gn, g.grp_w, g.nxcd, tm, tn);
   const long m0 = (long)tm * BM, n0 = (long)tn * BN;
   const long split = blockIdx.y;
   const long k_begin = split * g.k_per_split;

@@ -5,9 +5,44 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 
+#include <mutex>
+
 #include "../../include/us.h"
 
 namespace us {
+
+// What the tile-shape windows and the workgroup -> tile walk need to know about the current device: the number of
+// compute units and of XCDs (accelerator dies, each with its own L2; workgroups go to them round-robin).  Queried
+// once per device; MI355X's figures (256, 8) when no device can be asked (host-only use of the size functions).
+struct DeviceInfo {
+  int cus;
+  int xcds;
+};
+constexpr int kMaxDevices = 64;
+const DeviceInfo& device_info();
+
+// Raising a kernel's dynamic-LDS limit is a once-per-function-and-device call: one object of this type per kernel
+// instantiation (a function-local static), safe against host threads that enter the same launch together.
+struct FuncConfig {
+  std::once_flag once[kMaxDevices];
+  hipError_t err[kMaxDevices];
+  hipError_t ensure(const void* fn, int lds_bytes) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::call_once(once[dev], [&] { err[dev] = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes); });
+    return err[dev];
+  }
+};
+
+// Diagnostics: which GEMM kernel(s) the calling host thread's most recent matmul call launched (tile shape, wave
+// groups, stages, operand layouts, epilogue), as text.  note_gemm_launch() appends one kernel to the record that
+// begin_launch_record() cleared.
+void begin_launch_record();
+void note_gemm_launch(const char* kind, int bm, int bn, int waves_k, int nst, bool fp8, bool a_kc, bool b_kc, int epi, bool wide,
+                      int splits);
+const char* last_launch_record();
 
 hipError_t launch_cast(const void* src, us_dtype src_dt, void* dst, us_dtype dst_dt, size_t n, float scale,
                        us_cast_stats* stats, hipStream_t stream);

@@ -209,12 +209,8 @@ template <int NCH>
 static hipError_t launch_bwd(const _Float16* x, const _Float16* w, const _Float16* g, _Float16* dx, float* partial, long b, int n,
                              float eps, int nblocks, int rows_per_block, hipStream_t st) {
   const int lds = (kLnThreads / 64) * 2 * n * (int)sizeof(float);
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)ln_bwd_kernel<NCH>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static FuncConfig cfg;
+  if (hipError_t e = cfg.ensure((const void*)ln_bwd_kernel<NCH>, 160 * 1024); e != hipSuccess) return e;
   ln_bwd_kernel<NCH><<<nblocks, kLnThreads, lds, st>>>(x, w, g, dx, partial, b, n, eps, rows_per_block);
   return hipGetLastError();
 }

@@ -257,12 +257,8 @@ hipError_t launch_softmax_bwd(const void* X, const void* G, void* dX, long rows,
 
 hipError_t launch_softmax_xent(const void* X, const int* target, float* loss, void* dX, long rows, long s, float s1, float beta,
                                hipStream_t st) {
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)xent_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static FuncConfig cfg;
+  if (hipError_t e = cfg.ensure((const void*)xent_kernel, 128 * 1024); e != hipSuccess) return e;
   const int grid = (int)(rows < 256 * 8 ? rows : 256 * 8);
   xent_kernel<<<grid, kThreads, (size_t)s * 2, st>>>((const _Float16*)X, target, loss, (_Float16*)dX, rows, (int)s, s1, beta);
   return hipGetLastError();

@@ -61,6 +61,30 @@ def normal(seed: int, tensor: int, shape, sigma: float = 1.0, dtype=np.float16, 
     return out.reshape(shape)
 
 
+def outlier_positions(seed: int, tensor: int, count: int, one_in: int = 1000):
+    """Which of ``count`` elements are outliers, and their signs: element i is one iff word(i) % one_in == 0; its sign
+    is the word's top bit.  Returns (indices, signs as +-1.0 float32)."""
+    idx, sgn = [], []
+    chunk = 1 << 22
+    for lo in range(0, count, chunk):
+        n = min(chunk, count - lo)
+        w = _stream(seed, tensor, 2, lo, n)
+        hit = np.nonzero((w % np.uint64(one_in)) == 0)[0]
+        idx.append(hit + lo)
+        sgn.append(np.where((w[hit] >> np.uint64(63)) == 1, -1.0, 1.0).astype(np.float32))
+    return np.concatenate(idx), np.concatenate(sgn)
+
+
+def place_outliers(base: np.ndarray, sigma: float, positions, outlier: float = 1000.0) -> np.ndarray:
+    """``base`` (FP32 draws of N(0,1)) scaled by ``sigma`` with +-outlier written at ``positions`` (from
+    outlier_positions): for a sigma that is a power of two this is normal_with_outliers(seed, tensor, shape, sigma)
+    without drawing the normals again (the scaling is exact)."""
+    a = (base.astype(np.float32) * np.float32(sigma)).reshape(-1)
+    idx, sgn = positions
+    a[idx] = sgn * np.float32(outlier)
+    return a.reshape(base.shape)
+
+
 def normal_with_outliers(seed: int, tensor: int, shape, sigma: float, outlier: float = 1000.0,
                          one_in: int = 1000, dtype=np.float32):
     """N(0, sigma^2) with one element in ``one_in`` replaced by +-outlier (range-stress inputs).
@@ -69,18 +93,9 @@ def normal_with_outliers(seed: int, tensor: int, shape, sigma: float, outlier: f
     sign is the word's top bit.
     """
     a = normal(seed, tensor, shape, sigma, np.float32).reshape(-1)
-    count = a.size
-    n_out = 0
-    chunk = 1 << 22
-    for lo in range(0, count, chunk):
-        n = min(chunk, count - lo)
-        w = _stream(seed, tensor, 2, lo, n)
-        is_out = (w % np.uint64(one_in)) == 0
-        sign = np.where((w >> np.uint64(63)) == 1, -1.0, 1.0).astype(np.float32)
-        seg = a[lo:lo + n]
-        seg[is_out] = (sign * np.float32(outlier))[is_out]
-        n_out += int(is_out.sum())
-    return a.astype(dtype).reshape(shape), n_out
+    idx, sgn = outlier_positions(seed, tensor, a.size, one_in)
+    a[idx] = sgn * np.float32(outlier)
+    return a.astype(dtype).reshape(shape), int(idx.size)
 
 
 def small_ints(seed: int, tensor: int, shape, lo: int = -2, hi: int = 2, dtype=np.float16) -> np.ndarray:

@@ -8,6 +8,23 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+TESTS = os.path.dirname(os.path.abspath(__file__))
+if TESTS not in sys.path:
+    sys.path.insert(0, TESTS)
+
+
+@pytest.fixture(autouse=True)
+def _parity_figures(request, record_property):
+    """GPU tests: every assert_close records its gated, un-floored and RMS error as properties of the running test."""
+    if "gpu" not in request.keywords:
+        yield
+        return
+    import gpu_util
+    gpu_util._record = record_property
+    yield
+    gpu_util._record = None
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (runs the HIP library through its C ABI)")
 

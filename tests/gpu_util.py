@@ -6,6 +6,7 @@ import numpy as np
 import torch
 
 import paper_2303_11257_amd as us
+import parity
 
 DEV = "cuda:0"
 _TORCH = {np.dtype(np.float16): torch.float16, np.dtype(np.float32): torch.float32, np.dtype(np.uint8): torch.uint8}
@@ -88,19 +89,22 @@ def linear_bwd(X, W, G, x_dt, w_dt, g_dt, beta_x=0.0, beta_w=0.0, out_dt=us.F16,
     return (to_np(dX) if dX is not None else None, to_np(dW) if do_dw else None, to_np(a8) if want8 else None)
 
 
-# ---- error metric for matmul / GELU outputs ---------------------------------------------------------
-TAU = 0.25      # floor of the relative-error denominator; outputs are unit-scale by construction
-RTOL = 2e-3
+# ---- error metric for matmul / GELU outputs (tests/parity.py) ------------------------------------------
+TAU = parity.TAU
+RTOL = parity.RTOL
+_record = None        # the running test's record_property (set by conftest.py), so every comparison leaves its figures
 
 
-def rel_err(gpu: np.ndarray, ref: np.ndarray) -> float:
-    g, r = gpu.astype(np.float64), ref.astype(np.float64)
-    both_inf = np.isinf(g) & np.isinf(r) & (np.sign(g) == np.sign(r))
-    d = np.where(both_inf, 0.0, np.abs(g - r))
-    return float(np.max(d / np.maximum(np.abs(r), TAU)))
+def rel_err(gpu: np.ndarray, ref: np.ndarray, fp8: bool = False, scale: float = 1.0) -> float:
+    return parity.errors(gpu, ref, fp8, scale)["gated"]
 
 
-def assert_close(gpu, ref, what=""):
-    e = rel_err(gpu, ref)
-    assert e <= RTOL, f"{what}: max relative error {e:.3e} > {RTOL}"
-    return e
+def assert_close(gpu, ref, what="", fp8=False, scale=1.0, tau=parity.TAU, allow=None):
+    """fp8: the compared value comes out of a product of FP8 operands (absolute floor of the matrix core's adder)."""
+    e = parity.errors(gpu, ref, fp8, scale, tau, allow)
+    if _record is not None:
+        for k in ("gated", "unfloored_max", "rms"):
+            _record(f"{what or 'tensor'}:{k}", e[k])
+    print(f"parity {what}: gated {e['gated']:.2e}  un-floored max {e['unfloored_max']:.2e}  rms {e['rms']:.2e}")
+    assert e["gated"] <= RTOL, f"{what}: max relative error {e['gated']:.3e} > {RTOL} (un-floored {e['unfloored_max']:.3e}, rms {e['rms']:.3e})"
+    return e["gated"]

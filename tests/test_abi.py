@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported():
             "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd", "us_layer_norm_fwd", "us_layer_norm_bwd",
             "us_layer_norm_workspace_bytes", "us_exponent_histogram", "us_cast_snr", "us_linear_bias_fwd", "us_bias_grad",
             "us_bias_grad_workspace_bytes", "us_ffn_bias_fwd", "us_ffn_bias_bwd", "us_ffn_bias_workspace_bytes", "us_softmax_fwd", "us_softmax_bwd", "us_softmax_xent", "us_matmul_batched",
-            "us_attention_fwd", "us_attention_bwd", "us_sum_fwd", "us_sum_bwd"} <= set(names)
+            "us_attention_fwd", "us_attention_bwd", "us_sum_fwd", "us_sum_bwd", "us_last_launch"} <= set(names)
     L = ctypes.CDLL(us.library_path())
     for n in names:
         assert hasattr(L, n), n
@@ -137,6 +137,7 @@ def test_argument_errors_are_detected_on_the_host():
         with pytest.raises(us.UsError) as e:
             fn()
         assert e.value.status == status, (status, e.value)
+
     with pytest.raises(us.UsError) as e:
         us.cast_fp8_batch([16] * 9, [32] * 9, [4] * 9, [E4] * 9)         # more than US_CAST_BATCH_MAX tensors
     assert e.value.status == 2
@@ -155,3 +156,30 @@ def test_argument_errors_are_detected_on_the_host():
     us.bias_grad(None, F16, None, 0, 0)
     us.softmax_fwd(None, None, 0, 64)
     us.softmax_xent(None, None, None, None, 0, 64)
+
+
+def test_composite_calls_check_every_product_before_the_first_launch():
+    """A bad argument of a LATER product of a composite call is reported with its own status.  Had the first product
+    been enqueued before that check, this GPU-less container would answer "launch failed" (6) instead -- and on a GPU
+    the failing call would already have written into its outputs."""
+    ws, wsb = 256, 1 << 30
+    cases = [
+        (lambda: us.ffn_fwd(16, 16, 16, 16, 16, 24, 16, 16, 16, 0, ws, wsb), 3),                         # Y misaligned
+        (lambda: us.ffn_fwd(16, 16, 16, 16, 16, None, 16, 16, 16, us.FFN_FP8, ws, wsb), 1),
+        (lambda: us.ffn_bwd(16, 16, 16, 16, 16, 16, 16, 16, 16, 24, 16, 16, 16, 16, 0, ws, wsb), 3),     # dW1 misaligned
+        (lambda: us.ffn_bwd(16, 16, 16, 16, 16, 16, 16, 16, 24, 16, 16, 16, 16, 16, us.FFN_FP8, ws, wsb), 3),   # dX misaligned
+        (lambda: us.ffn_res_fwd(16, 16, 16, 16, 16, 16, 24, 16, 16, 16, 0.5, 0, ws, wsb), 3),            # Out misaligned
+        (lambda: us.ffn_res_fwd(None, 16, 16, 16, 16, 16, 16, 16, 16, 16, 0.5, 0, ws, wsb), 1),          # no skip input
+        (lambda: us.ffn_res_bwd(16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 24, 16, 16, 16, 16, 0.5, 0, ws, wsb), 3),   # dW1
+        (lambda: us.ffn_res_bwd(16, 16, 16, 16, 16, None, 16, 16, 16, 16, 16, 16, 16, 16, 16, 0.5, 0, ws, wsb), 1), # no Gskip
+        (lambda: us.ffn_bias_fwd(16, 16, 16, 16, 24, 16, 16, 16, 16, 16, 16, 0, ws, wsb), 3),            # b2 misaligned
+        (lambda: us.ffn_bias_bwd(16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 24, 16, 16, 16, 16, 0, ws, wsb), 3),   # db1
+        (lambda: us.ffn_bias_bwd(16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 24, 16, 16, 16, 16, 16, 16, 0, ws, wsb), 3),   # dW1
+        (lambda: us.attention_fwd(16, 16, 16, 16, 16, 24, 2, 64, 64), 3),                                # O misaligned
+        (lambda: us.attention_bwd(16, 16, 16, 16, 16, 16, 16, 16, 16, 24, 16, 2, 64, 64), 3),            # dK misaligned
+        (lambda: us.attention_fwd(16, 16, 16, 16, 16, 16, 70000, 64, 64), 2),
+    ]
+    for fn, status in cases:
+        with pytest.raises(us.UsError) as e:
+            fn()
+        assert e.value.status == status, (status, e.value)

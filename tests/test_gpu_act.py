@@ -84,7 +84,7 @@ def test_fused_activation_epilogues(fp8, gk, ok, flag, shape):
     a, bsc = O.act_scales(ok)
     Z, H16, H8 = linear_fwd(Xo, Wo, gdt[0], gdt[1], epi=us.EPI_GELU | flag, want16=True, want8=True,
                             workspace_bytes=us.workspace_bytes(b, m, n))          # a workspace must not switch on gelu's table
-    assert_close(Z, O.linear_fwd(Xo, Wo, m ** -0.5, odt[0], odt[1]), "Z")
+    assert_close(Z, O.linear_fwd(Xo, Wo, m ** -0.5, odt[0], odt[1]), "Z", fp8=fp8)
     ref = O.act_fwd(Z, ok, a)
     assert _ulps(H16, ref) <= 1 and np.mean(H16 != ref) < 0.02
     assert np.array_equal(H8, O.cast_fp8(H16, O.E4M3)[0])
@@ -94,7 +94,7 @@ def test_fused_activation_epilogues(fp8, gk, ok, flag, shape):
     # (the plain and the fused grad_X may come from different tile shapes, i.e. other summation orders: dH agrees to
     # the matmul tolerance, not to the bit, so the product is compared the same way)
     ref = O.act_bwd(Zpre, dH, ok, bsc)
-    assert_close(dZ, ref, "dZ")
+    assert_close(dZ, ref, "dZ", fp8=fp8)
     assert np.mean(dZ != ref) < 0.05
     assert np.array_equal(dZ8, O.cast_fp8(dZ, O.E5M2)[0])
     # variance: unit after the scaled activation, forward and backward

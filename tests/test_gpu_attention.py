@@ -56,7 +56,7 @@ def test_matmul_batched_fp8_pairs_and_fp32_output(mode):
     A8, B8 = O.cast_fp8(A16, fa)[0], O.cast_fp8(B16, fb)[0]
     C = _batched(A8, B8, 1 / 16, ta, tb, a_dt=fa, b_dt=fb, out=np.float32)
     ref = O.matmul_batched(A8, B8, 1 / 16, ta, tb, fa, fb, O.F32)
-    assert_close(C, ref, mode)
+    assert_close(C, ref, mode, fp8=True)
 
 
 def test_matmul_batched_exact_integers_and_independent_items():

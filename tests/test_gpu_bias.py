@@ -50,7 +50,7 @@ def test_linear_bias_fwd_against_the_oracle(shape, fp8):
     Y, _, _ = _fwd(X, W, dt, bias)
     odt = O.E4M3 if fp8 else O.F16
     ref = O.linear_fwd(X, W, O.linear_scales(b, m, n)[0], odt, odt, bias=bias)
-    assert_close(Y, ref, f"Y {shape}")
+    assert_close(Y, ref, f"Y {shape}", fp8=fp8)
     # without the bias the call is us_linear_fwd bit for bit, and a zero bias changes nothing either
     Y0, _, _ = _fwd(X, W, dt, None)
     Yz, _, _ = _fwd(X, W, dt, np.zeros(n, np.float16))
@@ -92,7 +92,7 @@ def test_gelu_and_residual_epilogues_act_on_the_biased_output(fp8):
     odt = O.E4M3 if fp8 else O.F16
     bias = synth.normal(73, 9, (n,), sigma=0.75)
     Z, H16, H8 = _fwd(X, W, dt, bias, epi=us.EPI_GELU, want16=True, want8=fp8)
-    assert_close(Z, O.linear_fwd(X, W, O.linear_scales(b, m, n)[0], odt, odt, bias=bias), "Z")
+    assert_close(Z, O.linear_fwd(X, W, O.linear_scales(b, m, n)[0], odt, odt, bias=bias), "Z", fp8=fp8)
     Href = O.gelu_fwd(Z, O.gelu_scales()[0])
     assert np.max(np.abs(_bits(H16).astype(np.int64) - _bits(Href).astype(np.int64))) <= 1
     if fp8:
@@ -114,7 +114,7 @@ def test_table_driven_gelu_with_bias_matches_the_arithmetic_epilogue():
     assert np.array_equal(_bits(Zt), _bits(Za)) and np.array_equal(Ht, Ha)
     rows = np.arange(0, b, 97)
     ref = O.linear_fwd(X[rows], W, O.linear_scales(b, m, n)[0], O.E4M3, O.E4M3, bias=bias)
-    assert_close(Zt[rows], ref, "Z (table path)")
+    assert_close(Zt[rows], ref, "Z (table path)", fp8=True)
 
 
 def _sum_close(gpu, ref):
@@ -207,22 +207,22 @@ def test_ffn_with_biases_small_ragged_shape(fp8):
     a1, bx1, bw1 = O.linear_scales(T, d, f)
     a2, bx2, bw2 = O.linear_scales(T, f, d)
     ag, bg = O.gelu_scales()
-    assert_close(g["Z"], O.linear_fwd(g["Xop"], g["W1op"], a1, op, op, bias=host["b1"]), "Z")
+    assert_close(g["Z"], O.linear_fwd(g["Xop"], g["W1op"], a1, op, op, bias=host["b1"]), "Z", fp8=fp8)
     Href = O.gelu_fwd(g["Z"], ag)
     if fp8:    # only the codes are stored: one code off where the FP32 GELU moved the FP16 value across an FP8 boundary
         diff = np.abs(g["H"].astype(np.int32) - O.cast_fp8(Href, O.E4M3)[0].astype(np.int32))
         assert diff.max() <= 1 and np.mean(diff != 0) < 1e-3
     else:
         assert_close(g["H"], Href, "H")
-    assert_close(g["Y"], O.linear_fwd(g["H"], g["W2op"], a2, op, op, bias=host["b2"]), "Y")
+    assert_close(g["Y"], O.linear_fwd(g["H"], g["W2op"], a2, op, op, bias=host["b2"]), "Y", fp8=fp8)
     dH = O.linear_bwd_dx(g["Gop"], g["W2op"], bx2, gr, op)
-    assert_close(g["dZ16"], O.gelu_bwd(g["Z"], dH, bg), "dZ")
+    assert_close(g["dZ16"], O.gelu_bwd(g["Z"], dH, bg), "dZ", fp8=fp8)
     assert _sum_close(g["db2"], O.bias_grad(host["G"], O.bias_scale(T)))
     assert _sum_close(g["db1"], O.bias_grad(g["dZ16"], O.bias_scale(T)))
     dZop = g["dZ8"] if fp8 else g["dZ16"]
-    assert_close(g["dX"], O.linear_bwd_dx(dZop, g["W1op"], bx1, gr, op), "dX")
-    assert_close(g["dW1"], O.linear_bwd_dw(g["Xop"], dZop, bw1, op, gr), "dW1")
-    assert_close(g["dW2"], O.linear_bwd_dw(g["H"], g["Gop"], bw2, op, gr), "dW2")
+    assert_close(g["dX"], O.linear_bwd_dx(dZop, g["W1op"], bx1, gr, op), "dX", fp8=fp8)
+    assert_close(g["dW1"], O.linear_bwd_dw(g["Xop"], dZop, bw1, op, gr), "dW1", fp8=fp8)
+    assert_close(g["dW2"], O.linear_bwd_dw(g["H"], g["Gop"], bw2, op, gr), "dW2", fp8=fp8)
 
 
 @pytest.mark.parametrize("shape,tables", [((272, 144, 400), False), ((1024, 256, 2048), True), ((4096, 1024, 3072), True),
@@ -248,8 +248,8 @@ def test_ffn_with_biases_at_the_bert_large_shape_sampled():
     W1op, W2op = dev["W1op"].cpu().numpy(), dev["W2op"].cpu().numpy()
     a1, a2 = O.linear_scales(T, d, f)[0], O.linear_scales(T, f, d)[0]
     Zr = dev["Z"][ridx].cpu().numpy()
-    assert_close(Zr, O.linear_fwd(dev["Xop"][ridx].cpu().numpy(), W1op, a1, O.E4M3, O.E4M3, bias=host["b1"]), "Z rows")
-    assert_close(dev["Y"][ridx].cpu().numpy(), O.linear_fwd(dev["H"][ridx].cpu().numpy(), W2op, a2, O.E4M3, O.E4M3, bias=host["b2"]), "Y rows")
+    assert_close(Zr, O.linear_fwd(dev["Xop"][ridx].cpu().numpy(), W1op, a1, O.E4M3, O.E4M3, bias=host["b1"]), "Z rows", fp8=True)
+    assert_close(dev["Y"][ridx].cpu().numpy(), O.linear_fwd(dev["H"][ridx].cpu().numpy(), W2op, a2, O.E4M3, O.E4M3, bias=host["b2"]), "Y rows", fp8=True)
     assert _sum_close(dev["db2"].cpu().numpy(), O.bias_grad(host["G"], O.bias_scale(T)))
     assert _sum_close(dev["db1"].cpu().numpy(), O.bias_grad(dev["dZ16"].cpu().numpy(), O.bias_scale(T)))
     # unit variance of the bias gradients (b^-1/2 on a sum of T unit-scale rows); dZ has variance ~1 only where gelu' does

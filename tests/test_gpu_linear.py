@@ -30,9 +30,9 @@ def test_c1_linear_fwd_bwd(fp8):
     assert (a, bx, bw) == (1 / 16, 1 / 32, 1 / 16)
     Y = linear_fwd(X, W, gdt[0], gdt[1])                               # default alpha = m^-1/2
     dX, dW, _ = linear_bwd(X, W, G, *gdt)
-    assert_close(Y, O.linear_fwd(X, W, a, odt[0], odt[1]), "Y")
-    assert_close(dX, O.linear_bwd_dx(G, W, bx, odt[2], odt[1]), "dX")
-    assert_close(dW, O.linear_bwd_dw(X, G, bw, odt[0], odt[2]), "dW")
+    assert_close(Y, O.linear_fwd(X, W, a, odt[0], odt[1]), "Y", fp8=fp8)
+    assert_close(dX, O.linear_bwd_dx(G, W, bx, odt[2], odt[1]), "dX", fp8=fp8)
+    assert_close(dW, O.linear_bwd_dw(X, G, bw, odt[0], odt[2]), "dW", fp8=fp8)
     for t in (Y, dX, dW):
         assert abs(np.var(t.astype(np.float64)) - 1.0) < 0.05
 
@@ -46,10 +46,10 @@ def test_ragged_shapes(fp8, shape):
     b, m, n = shape
     (X, W, G), gdt, odt = _operands(b, m, n, 101 + b, fp8)
     a, bx, bw = us.linear_scales(b, m, n)
-    assert_close(linear_fwd(X, W, gdt[0], gdt[1]), O.linear_fwd(X, W, a, odt[0], odt[1]), "Y")
+    assert_close(linear_fwd(X, W, gdt[0], gdt[1]), O.linear_fwd(X, W, a, odt[0], odt[1]), "Y", fp8=fp8)
     dX, dW, _ = linear_bwd(X, W, G, *gdt)
-    assert_close(dX, O.linear_bwd_dx(G, W, bx, odt[2], odt[1]), "dX")
-    assert_close(dW, O.linear_bwd_dw(X, G, bw, odt[0], odt[2]), "dW")
+    assert_close(dX, O.linear_bwd_dx(G, W, bx, odt[2], odt[1]), "dX", fp8=fp8)
+    assert_close(dW, O.linear_bwd_dw(X, G, bw, odt[0], odt[2]), "dW", fp8=fp8)
 
 
 @pytest.mark.parametrize("fp8", [False, True])
@@ -96,7 +96,7 @@ def test_split_k_reduction_of_grad_w():
     for fp8 in (False, True):
         (X, W, G), gdt, odt = _operands(b, m, n, 107, fp8)
         _, dW, _ = linear_bwd(X, None, G, *gdt, do_dx=False)
-        assert_close(dW, O.linear_bwd_dw(X, G, b ** -0.5, odt[0], odt[2]), "dW split")
+        assert_close(dW, O.linear_bwd_dw(X, G, b ** -0.5, odt[0], odt[2]), "dW split", fp8=fp8)
         _, dW2, _ = linear_bwd(X, None, G, *gdt, do_dx=False)
         assert np.array_equal(dW, dW2)                          # run-to-run bit identical
 
@@ -109,7 +109,7 @@ def test_grad_w_wave_split_reduction(fp8):
     assert us.workspace_bytes(b, m, n) == us.TABLE_AREA_BYTES        # the table area only: no K slices
     (X, W, G), gdt, odt = _operands(b, m, n, 109, fp8)
     _, dW, _ = linear_bwd(X, None, G, *gdt, do_dx=False)
-    assert_close(dW, O.linear_bwd_dw(X, G, b ** -0.5, odt[0], odt[2]), "dW wave split")
+    assert_close(dW, O.linear_bwd_dw(X, G, b ** -0.5, odt[0], odt[2]), "dW wave split", fp8=fp8)
     # exact integers: both halves of every stage must land in the right sum
     Xi, Gi = synth.small_ints(113, 1, (b, m)), synth.small_ints(113, 4, (b, n))
     if fp8:
@@ -128,7 +128,7 @@ def test_fused_gelu_epilogues(fp8):
     ag, bg = O.gelu_scales()
     a, bx, _ = us.linear_scales(b, m, n)
     Z, H16, H8 = linear_fwd(X, W, gdt[0], gdt[1], epi=us.EPI_GELU, want16=True, want8=True)
-    assert_close(Z, O.linear_fwd(X, W, a, odt[0], odt[1]), "Z")
+    assert_close(Z, O.linear_fwd(X, W, a, odt[0], odt[1]), "Z", fp8=fp8)
     assert np.array_equal(Z, linear_fwd(X, W, gdt[0], gdt[1]))             # same Z with and without the epilogue
     assert_close(H16, O.gelu_fwd(Z, ag), "H")
     assert np.array_equal(H8, O.cast_fp8(H16, O.E4M3)[0])
@@ -138,9 +138,9 @@ def test_fused_gelu_epilogues(fp8):
     # grad_X with GELU': Zpre has the shape of dX, i.e. [b, m]
     Zpre = synth.normal(113, 7, (b, m))
     dH, _, _ = linear_bwd(None, W, G, *gdt, do_dw=False)
-    assert_close(dH, O.linear_bwd_dx(G, W, bx, odt[2], odt[1]), "dH")
+    assert_close(dH, O.linear_bwd_dx(G, W, bx, odt[2], odt[1]), "dH", fp8=fp8)
     dZ, _, dZ8 = linear_bwd(None, W, G, *gdt, epi=us.EPI_GELU_GRAD, Zpre=Zpre, want8=True, do_dw=False)
-    assert_close(dZ, O.gelu_bwd(Zpre, dH, bg), "dZ")
+    assert_close(dZ, O.gelu_bwd(Zpre, dH, bg), "dZ")      # GELU' of the GPU's own dH: no matmul between the two
     assert np.array_equal(dZ8, O.cast_fp8(dZ, O.E5M2)[0])
     # codes only (no FP16 dZ stored): the same codes
     none16, _, dZ8b = linear_bwd(None, W, G, *gdt, epi=us.EPI_GELU_GRAD, Zpre=Zpre, want8=True, do_dw=False, store_dx=False)
@@ -222,7 +222,7 @@ def test_table_driven_gelu_epilogues_equal_the_arithmetic_ones():
     dH = O.linear_bwd_dx(G[rows], W, n ** -0.5, O.E5M2, O.E4M3)
     ref = O.gelu_bwd(Zpre[rows], dH, O.gelu_scales()[1])
     fin = np.isfinite(ref.astype(np.float32))
-    assert_close(np.where(fin, dZ1[rows], 0), np.where(fin, ref, 0), "dZ (table)")
+    assert_close(np.where(fin, dZ1[rows], 0), np.where(fin, ref, 0), "dZ (table)", fp8=True)
 
 
 def test_table_driven_gelu_fp16_output_equals_the_arithmetic_one():
@@ -286,13 +286,13 @@ def test_paired_grad_x_grad_w_launch_equals_separate_launches(fp8, shape):
             if c8 is not None:
                 assert np.array_equal(c8, c81)
         else:      # the paired grad_X adds its k-steps in two interleaved halves: same sum, another order
-            assert_close(dX, dX1, "dX paired vs separate")
+            assert_close(dX, dX1, "dX paired vs separate", fp8=fp8)
             assert np.mean(dX.view(np.uint16) != dX1.view(np.uint16)) < 0.2
             if c8 is not None:     # the codes are those of this launch's own FP16 result
                 assert np.array_equal(c8, O.cast_fp8(dX, O.E5M2)[0])
-        assert_close(dW, dW1, "dW paired vs separate")
+        assert_close(dW, dW1, "dW paired vs separate", fp8=fp8)
         assert np.mean(dW.view(np.uint16) != dW1.view(np.uint16)) < 0.2
     rows, cols = [0, 1, 4097, 8191], [0, 5, 1023]
-    assert_close(dW[:, cols], O.linear_bwd_dw(X, np.ascontiguousarray(G[:, cols]), b ** -0.5, odt[0], odt[2]), "dW paired")
+    assert_close(dW[:, cols], O.linear_bwd_dw(X, np.ascontiguousarray(G[:, cols]), b ** -0.5, odt[0], odt[2]), "dW paired", fp8=fp8)
     dH = O.linear_bwd_dx(G[rows], W, n ** -0.5, odt[2], odt[1])
-    assert_close(dX[rows], O.gelu_bwd(Zpre[rows], dH, O.gelu_scales()[1]), "dZ paired")
+    assert_close(dX[rows], O.gelu_bwd(Zpre[rows], dH, O.gelu_scales()[1]), "dZ paired", fp8=fp8)

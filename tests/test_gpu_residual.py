@@ -8,6 +8,7 @@ import torch
 import oracle
 import paper_2303_11257_amd as us
 import synth
+from parity import FP8_ABS
 from gpu_util import DEV, RTOL, TAU, assert_close, cast_fp8, empty, linear_bwd, linear_fwd, ptr, stream, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
@@ -110,7 +111,7 @@ def test_small_residual_layer_against_the_oracle_chain(fp8):
     gact, ggrad = (us.E4M3, us.E5M2) if fp8 else (us.F16, us.F16)
     # forward: branch output from the GPU's stored H and W2 operand, then the oracle's interpolation
     Ybranch = linear_fwd(g("H"), g("W2op"), gact, gact)
-    assert_close(Ybranch, O.linear_fwd(g("H"), g("W2op"), f ** -0.5, act, act), "branch output")
+    assert_close(Ybranch, O.linear_fwd(g("H"), g("W2op"), f ** -0.5, act, act), "branch output", fp8=fp8)
     ref = O.weighted_add2(X, Ybranch, skip, w)
     assert _ulps(g("Out"), ref) <= 1
     # backward: dZ as in the plain FFN (checked there); grad_X of the branch from the GPU's stored dZ operand
@@ -140,7 +141,9 @@ def test_c3_residual_layer_fp8_sampled_and_variances():
     # operands: the GPU's value may sit within the matmul tolerance of it, and that error enters the output times w.
     def close(got, skip_in, branch_ref, what):
         ref = O.weighted_add2(skip_in, branch_ref, skip, w).astype(np.float64)
-        tol = float(w) * RTOL * np.maximum(np.abs(branch_ref.astype(np.float64)), TAU) + 2.0 ** -10 * np.maximum(np.abs(ref), TAU)
+        # (FP8 operands: the matrix core's absolute floor joins the matmul part, as in parity.errors)
+        tol = (float(w) * (RTOL * np.maximum(np.abs(branch_ref.astype(np.float64)), TAU) + FP8_ABS)
+               + 2.0 ** -10 * np.maximum(np.abs(ref), TAU))
         assert np.all(np.abs(got.astype(np.float64) - ref) <= tol), what
     Yb = O.linear_fwd(H_r, W2op, f ** -0.5, O.E4M3, O.E4M3)
     close(run.dev["Out"][idx].cpu().numpy(), X[rows], Yb, "Out rows")

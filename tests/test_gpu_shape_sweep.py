@@ -81,9 +81,9 @@ def test_forward_and_backward(shape, fp8):
                        None, 0, st)
     torch.cuda.synchronize()
     Yref = O.linear_fwd(Xr, W, a, od[0], od[1], bias=bias)
-    assert_close(Y[ridx].cpu().numpy(), Yref, "Y + bias")
+    assert_close(Y[ridx].cpu().numpy(), Yref, "Y + bias", fp8=fp8)
     Zr = Z[ridx].cpu().numpy()
-    assert_close(Zr, O.linear_fwd(Xr, W, a, od[0], od[1]), "Z")
+    assert_close(Zr, O.linear_fwd(Xr, W, a, od[0], od[1]), "Z", fp8=fp8)
     Hr = H16[ridx].cpu().numpy()
     assert_close(Hr, O.gelu_fwd(Zr, ag), "H")
     if fp8:
@@ -101,16 +101,16 @@ def test_forward_and_backward(shape, fp8):
                   ptr(dZ8) if fp8 else None, ptr(ws), wsb, st)
     torch.cuda.synchronize()
     dXref = O.linear_bwd_dx(Gr, W, bx, od[2], od[1])
-    assert_close(dX[ridx].cpu().numpy(), dXref, "dX")
+    assert_close(dX[ridx].cpu().numpy(), dXref, "dX", fp8=fp8)
     dXg_r = dXg[ridx].cpu().numpy()
-    assert_close(dXg_r, O.gelu_bwd(Zpre[rows], dX[ridx].cpu().numpy(), bg), "dX with GELU'")
+    assert_close(dXg_r, O.gelu_bwd(Zpre[rows], dX[ridx].cpu().numpy(), bg), "dX with GELU'", fp8=fp8)   # the two grad_X launches may use different tiles
     if fp8:
         assert np.array_equal(dZ8[ridx].cpu().numpy(), O.cast_fp8(dXg_r, O.E5M2)[0])
     wr = _sample(rng, m)                      # rows of dW = columns of X
     widx = torch.as_tensor(wr, device=DEV)
     dWref = O.linear_bwd_dw(np.ascontiguousarray(X[:, wr]), G, bw, od[0], od[2])
-    assert_close(dW[widx].cpu().numpy(), dWref, "dW")
+    assert_close(dW[widx].cpu().numpy(), dWref, "dW", fp8=fp8)
     # grad_W has its own kernel alone and another in a paired launch (whether a pair forms depends on grad_X's epilogue
     # too): the same sum added in another order, so nearly every FP16 result is the same and the rest a rounding apart
-    assert_close(dW2[widx].cpu().numpy(), dWref, "dW next to GELU'")
+    assert_close(dW2[widx].cpu().numpy(), dWref, "dW next to GELU'", fp8=fp8)
     assert (dW != dW2).float().mean().item() < 0.2
