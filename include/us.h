@@ -179,6 +179,30 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
 size_t us_workspace_bytes(long b, long m, long n);
 
 /*
+ * us_linear_bwd for callers that cannot allocate device memory or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without the workspace), same kernels, same
+ * results bit for bit as us_linear_bwd given a workspace of us_workspace_bytes(b, m, n) bytes without
+ * US_EPI_TABLES_READY (that flag is ignored here: each call rebuilds the table it uses).
+ *
+ * The workspace is a static device array inside the library, US_NOALLOC_SCRATCH_BYTES (16.25 MiB) on every GPU the
+ * library runs on, held until the process ends.  The call allocates and frees nothing.  A shape whose grad_W needs
+ * more slice memory than that (us_workspace_bytes(b, m, n) > US_NOALLOC_SCRATCH_BYTES: few output tiles and many
+ * tokens, e.g. 4096 tokens into a 512 x 2048 weight) is refused with US_ERR_WORKSPACE before anything is launched;
+ * use us_linear_bwd with a workspace of the caller's for those.
+ *
+ * All calls on one GPU share that GPU's array, which keeps the previous call's contents; nothing in it needs to start
+ * at zero (tables and slices are written completely before they are read).  Two calls whose kernels may overlap on one
+ * GPU (different streams, or graphs replayed side by side) race on it: serialise them.
+ */
+#define US_NOALLOC_SCRATCH_BYTES (US_TABLE_AREA_BYTES + (16u << 20))
+us_status us_linear_bwd_noalloc(const void* X, const void* W, const void* G, void* dX, void* dW,
+                                long b, long m, long n,
+                                us_dtype x_dt, us_dtype w_dt, us_dtype g_dt, us_dtype out_dt,
+                                float beta_x, float beta_w, us_epilogue epi, float epi_scale,
+                                const void* Zpre, void* aux8, void* stream);
+size_t us_noalloc_scratch_bytes(void);
+
+/*
  * Fill the table area of a workspace (its first US_TABLE_AREA_BYTES; workspace_bytes must be at least
  * that) with all GELU tables for the factors alpha_g / beta_g (<= 0: 1.7009 / 1.4811, Table A.2).  The
  * tables depend on nothing else, so a training loop calls this once and then passes

@@ -55,6 +55,9 @@ def lib() -> ctypes.CDLL:
     L.us_linear_fwd.argtypes = [vp, vp, vp, l, l, l, i, i, i, f, i, f, vp, vp, vp, sz, vp]
     L.us_linear_bwd.argtypes = [vp, vp, vp, vp, vp, l, l, l, i, i, i, i, f, f, i, f, vp, vp, vp, sz, vp]
     L.us_workspace_bytes.argtypes = [l, l, l]
+    L.us_linear_bwd_noalloc.argtypes = [vp, vp, vp, vp, vp, l, l, l, i, i, i, i, f, f, i, f, vp, vp, vp]
+    L.us_noalloc_scratch_bytes.argtypes = []
+    L.us_noalloc_scratch_bytes.restype = sz
     L.us_gelu_tables.argtypes = [vp, sz, f, f, vp]
     L.us_weighted_add.argtypes = [vp, vp, vp, sz, i, f, f, vp]
     L.us_layer_norm_fwd.argtypes = [vp, vp, vp, vp, l, l, f, vp]
@@ -90,7 +93,7 @@ def lib() -> ctypes.CDLL:
     L.us_ffn_bias_bwd.argtypes = [vp] * 14 + [l, l, l, i, vp, sz, vp]
     L.us_ffn_bias_workspace_bytes.argtypes = [l, l, l]
     L.us_ffn_bias_workspace_bytes.restype = sz
-    for name in ("us_linear_scales", "us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_gelu_fwd", "us_gelu_bwd",
+    for name in ("us_linear_scales", "us_cast_fp8", "us_cast_fp8_batch", "us_linear_fwd", "us_linear_bwd", "us_linear_bwd_noalloc", "us_gelu_fwd", "us_gelu_bwd",
                  "us_gelu_tables", "us_ffn_fwd", "us_ffn_bwd", "us_weighted_add", "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd", "us_layer_norm_fwd", "us_layer_norm_bwd", "us_exponent_histogram", "us_cast_snr",
                  "us_linear_bias_fwd", "us_bias_grad", "us_ffn_bias_fwd", "us_ffn_bias_bwd", "us_softmax_fwd", "us_softmax_bwd",
                  "us_softmax_xent", "us_matmul_batched", "us_attention_fwd", "us_attention_bwd", "us_sum_fwd", "us_sum_bwd"):
@@ -141,6 +144,16 @@ def linear_bwd(X, W, G, dX, dW, b, m, n, x_dt, w_dt, g_dt, out_dt=F16, beta_x=0.
                epi_scale=0.0, Zpre=None, aux8=None, workspace=None, workspace_bytes=0, stream=None):
     _check(lib().us_linear_bwd(X, W, G, dX, dW, b, m, n, x_dt, w_dt, g_dt, out_dt, beta_x, beta_w, epi, epi_scale, Zpre,
                                aux8, workspace, workspace_bytes, stream), "us_linear_bwd")
+
+
+def linear_bwd_noalloc(X, W, G, dX, dW, b, m, n, x_dt, w_dt, g_dt, out_dt=F16, beta_x=0.0, beta_w=0.0, epi=EPI_NONE,
+                       epi_scale=0.0, Zpre=None, aux8=None, stream=None):
+    _check(lib().us_linear_bwd_noalloc(X, W, G, dX, dW, b, m, n, x_dt, w_dt, g_dt, out_dt, beta_x, beta_w, epi, epi_scale, Zpre,
+                                       aux8, stream), "us_linear_bwd_noalloc")
+
+
+def noalloc_scratch_bytes() -> int:
+    return int(lib().us_noalloc_scratch_bytes())
 
 
 def workspace_bytes(b: int, m: int, n: int) -> int:

@@ -3,6 +3,7 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
 
 #include "us_device.h"
 #include "us_launch.h"
@@ -21,6 +22,33 @@ inline float skip_weight(float w) { return (float)sqrt(1.0 - (double)w * (double
 inline bool residual_weight_ok(float w) { return w > 0.0f && w <= 1.0f; }
 
 }  // namespace
+
+// ---- scratch of the entry point that allocates nothing (us_linear_bwd_noalloc) -----------------------------------
+// One array per GPU the library runs on, held until the process ends: the table area of the table-driven GELU'
+// epilogue, then room for grad_W's FP32 K slices.  Host code never uses the array's name as an address: its device
+// address is looked up once per device (with that device current) and kept.
+static __device__ __align__(256) unsigned char scratch[US_NOALLOC_SCRATCH_BYTES];
+
+struct ScratchAddress {
+  std::once_flag once[kMaxDevices];
+  hipError_t err[kMaxDevices];
+  void* ptr[kMaxDevices];
+  // the current device's copy of `scratch`, or NULL with *e set
+  void* get(hipError_t* e) {
+    int dev = 0;
+    *e = hipGetDevice(&dev);
+    if (*e != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) { *e = hipErrorInvalidDevice; return nullptr; }
+    std::call_once(once[dev], [&] {
+      void* p = nullptr;
+      err[dev] = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      ptr[dev] = (err[dev] == hipSuccess) ? p : nullptr;
+    });
+    *e = err[dev];
+    return ptr[dev];
+  }
+};
+static ScratchAddress g_scratch;
 
 extern "C" {
 
@@ -256,6 +284,34 @@ us_status us_linear_bwd(const void* X, const void* W, const void* G, void* dX, v
   begin_launch_record();
   return linear_bwd_impl(X, W, G, dX, dW, b, m, n, x_dt, w_dt, g_dt, out_dt, beta_x, beta_w, epi, epi_scale, Zpre, aux8,
                          workspace, workspace_bytes, stream, nullptr);
+}
+
+size_t us_noalloc_scratch_bytes(void) { return (size_t)US_NOALLOC_SCRATCH_BYTES; }
+
+us_status us_linear_bwd_noalloc(const void* X, const void* W, const void* G, void* dX, void* dW, long b, long m, long n,
+                                us_dtype x_dt, us_dtype w_dt, us_dtype g_dt, us_dtype out_dt, float beta_x, float beta_w,
+                                us_epilogue epi, float epi_scale, const void* Zpre, void* aux8, void* stream) {
+  begin_launch_record();
+  // the tables in the scratch belong to whichever call used it last: every call rebuilds the one it needs
+  epi = (us_epilogue)((int)epi & ~US_EPI_TABLES_READY);
+  // what us_linear_bwd would want as workspace for this shape must fit the static array (decided on the host, before
+  // any device call)
+  const size_t need = (b > 0 && m > 0 && n > 0) ? us_workspace_bytes(b, m, n) : 0;
+  if (need > (size_t)US_NOALLOC_SCRATCH_BYTES) return US_ERR_WORKSPACE;
+  // a placeholder address stands in for the scratch while the arguments are checked: nothing is looked up or launched
+  // for a call that fails
+  us_status s = linear_bwd_impl(X, W, G, dX, dW, b, m, n, x_dt, w_dt, g_dt, out_dt, beta_x, beta_w, epi, epi_scale, Zpre, aux8,
+                                reinterpret_cast<void*>(uintptr_t{256}), (size_t)US_NOALLOC_SCRATCH_BYTES, stream, nullptr, false);
+  if (s != US_OK) return s;
+  if (b <= 0 || m <= 0 || n <= 0) {      // degenerate shapes: nothing reads the scratch
+    return linear_bwd_impl(X, W, G, dX, dW, b, m, n, x_dt, w_dt, g_dt, out_dt, beta_x, beta_w, epi, epi_scale, Zpre, aux8, nullptr,
+                           0, stream, nullptr, true);
+  }
+  hipError_t e = hipSuccess;
+  void* const ws = g_scratch.get(&e);
+  if (!ws) return US_ERR_LAUNCH;
+  return linear_bwd_impl(X, W, G, dX, dW, b, m, n, x_dt, w_dt, g_dt, out_dt, beta_x, beta_w, epi, epi_scale, Zpre, aux8, ws,
+                         (size_t)US_NOALLOC_SCRATCH_BYTES, stream, nullptr, true);
 }
 
 us_status us_act_fwd(const void* z, void* h, size_t n, us_dtype dt, us_activation kind, float s1, float scale, void* stream) {

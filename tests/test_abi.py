@@ -24,7 +24,8 @@ def test_every_declared_symbol_is_exported():
             "us_ffn_res_fwd", "us_ffn_res_bwd", "us_act_fwd", "us_act_bwd", "us_layer_norm_fwd", "us_layer_norm_bwd",
             "us_layer_norm_workspace_bytes", "us_exponent_histogram", "us_cast_snr", "us_linear_bias_fwd", "us_bias_grad",
             "us_bias_grad_workspace_bytes", "us_ffn_bias_fwd", "us_ffn_bias_bwd", "us_ffn_bias_workspace_bytes", "us_softmax_fwd", "us_softmax_bwd", "us_softmax_xent", "us_matmul_batched",
-            "us_attention_fwd", "us_attention_bwd", "us_sum_fwd", "us_sum_bwd", "us_last_launch"} <= set(names)
+            "us_attention_fwd", "us_attention_bwd", "us_sum_fwd", "us_sum_bwd", "us_last_launch", "us_linear_bwd_noalloc",
+            "us_noalloc_scratch_bytes"} <= set(names)
     L = ctypes.CDLL(us.library_path())
     for n in names:
         assert hasattr(L, n), n
@@ -178,6 +179,10 @@ def test_composite_calls_check_every_product_before_the_first_launch():
         (lambda: us.attention_fwd(16, 16, 16, 16, 16, 24, 2, 64, 64), 3),                                # O misaligned
         (lambda: us.attention_bwd(16, 16, 16, 16, 16, 16, 16, 16, 16, 24, 16, 2, 64, 64), 3),            # dK misaligned
         (lambda: us.attention_fwd(16, 16, 16, 16, 16, 16, 70000, 64, 64), 2),
+        # the entry point without a workspace: a shape whose slices exceed its static scratch, and ordinary argument errors
+        (lambda: us.linear_bwd_noalloc(16, 16, 16, 16, 16, 4096, 512, 2048, us.F16, us.F16, us.F16), 5),
+        (lambda: us.linear_bwd_noalloc(16, 16, 16, 16, 24, 1040, 2048, 1008, us.F16, us.F16, us.F16), 3),
+        (lambda: us.linear_bwd_noalloc(16, 16, None, 16, 16, 1040, 2048, 1008, us.F16, us.F16, us.F16), 1),
     ]
     for fn, status in cases:
         with pytest.raises(us.UsError) as e:
