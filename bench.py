@@ -7,7 +7,7 @@ FP8 casts of X, W1, W2 (E4M3) and G (E5M2), Linear+GELU, Linear, and the four ba
 (tokens 8192 = 64 x 128, d_model 1024, d_ff 4096); the FP16 BERT-base FFN and the cast kernel's
 bandwidth are reported beside it.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3|C2|C5] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3|C2|C5] [--no-cpu-baseline] [--no-secondary]
 """
 from __future__ import annotations
 
@@ -109,6 +109,25 @@ class Ffn:
         us.ffn_bwd(p(X), p(W1), p(W2), p(self.Z), p(self.H), p(G), p(self.dZ16), p(self.dZ8), p(self.dX), p(self.dW1),
                    p(self.dW2), T, d, f, self.mode, p(self.ws), self.wsb, st)
 
+    def step_act_casts_only(self):
+        """The step of a training loop with gradient accumulation (App. J.2: the weights change once per many
+        micro-batches): only the activation X and the gradient G are cast, the E4M3 weights are reused."""
+        us, p, st = self.us, self.p, self.torch.cuda.current_stream().cuda_stream
+        T, d, f = self.T, self.d, self.f
+        us.cast_fp8_batch([p(self.X), p(self.G)], [p(self.X8), p(self.G8)], [self.X.numel(), self.G.numel()], [us.E4M3, us.E5M2], st)
+        us.ffn_fwd(p(self.X8), p(self.W1_8), p(self.W2_8), p(self.Z), p(self.H), p(self.Y), T, d, f, self.mode, p(self.ws), self.wsb, st)
+        us.ffn_bwd(p(self.X8), p(self.W1_8), p(self.W2_8), p(self.Z), p(self.H), p(self.G8), p(self.dZ16), p(self.dZ8), p(self.dX),
+                   p(self.dW1), p(self.dW2), T, d, f, self.mode, p(self.ws), self.wsb, st)
+
+    def weight_casts(self):
+        us, p, st = self.us, self.p, self.torch.cuda.current_stream().cuda_stream
+        us.cast_fp8_batch([p(self.W1), p(self.W2)], [p(self.W1_8), p(self.W2_8)], [self.W1.numel(), self.W2.numel()], [us.E4M3, us.E4M3], st)
+
+    def all_casts(self):
+        us, p, st = self.us, self.p, self.torch.cuda.current_stream().cuda_stream
+        us.cast_fp8_batch([p(self.X), p(self.W1), p(self.W2), p(self.G)], [p(self.X8), p(self.W1_8), p(self.W2_8), p(self.G8)],
+                          [self.X.numel(), self.W1.numel(), self.W2.numel(), self.G.numel()], [us.E4M3, us.E4M3, us.E4M3, us.E5M2], st)
+
     def step_residual(self, tau=0.5):
         """The same step for the residual layer out = sqrt(1-tau) x + sqrt(tau) FFN(x) (interpolation fused into the
         second projection and into grad_X of the first): a side measurement, not `value`."""
@@ -146,6 +165,60 @@ class Ffn:
                         self.wsb, st)
         us.ffn_bias_bwd(p(X), p(W1), p(W2), p(self.Z), p(self.H), p(G), p(self.G), p(self.dZ16), p(self.dZ8), p(self.dX), p(self.dW1),
                         p(self.dW2), p(self.db1), p(self.db2), T, d, f, self.mode, p(self.ws), self.wsb, st)
+
+
+class ClockSampler:
+    """Samples the GPU's shader clock (the line marked '*' of the driver's pp_dpm_sclk file) from a host thread while a
+    measurement runs.  mean() is None when the file cannot be read."""
+
+    def __init__(self, period_s=0.001):
+        import glob
+        import threading
+        self.paths = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+        self.period, self.samples, self._stop = period_s, [], threading.Event()
+        self._thread = threading.Thread(target=self._run, daemon=True)
+
+    def _read(self):
+        for path in self.paths:
+            try:
+                for line in open(path):
+                    if "*" in line:
+                        return float(line.split(":")[1].lower().split("mhz")[0])
+            except (OSError, ValueError, IndexError):
+                pass
+        return None
+
+    def _run(self):
+        while not self._stop.is_set():
+            v = self._read()
+            if v is not None:
+                self.samples.append(v)
+            time.sleep(self.period)
+
+    def __enter__(self):
+        if self.paths:
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        if self.paths:
+            self._thread.join()
+
+    def mean(self):
+        return sum(self.samples) / len(self.samples) if self.samples else None
+
+
+def measure_clock(torch, fn, seconds=0.3):
+    """Mean shader clock (MHz) while `fn` runs back to back for `seconds` (the timed loop itself can be a few
+    milliseconds long, too short for a host-side sampler)."""
+    with ClockSampler() as cs:
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(20):
+                fn()
+            torch.cuda.synchronize()
+    return cs.mean(), len(cs.samples)
 
 
 def ramp_up(torch, fn, seconds=0.15):
@@ -261,6 +334,49 @@ def pytorch_reference(torch, T, d, f, steps=100, warmup=20):
     except Exception as e:          # an op or type this build lacks: the comparison is simply left out
         return {"unavailable": repr(e)[:200]}
 
+def range_stress(torch, us, steps=30):
+    """Config "FP8 range-stress GEMM sweep": square M = N = K in {2048, 4096, 8192}; X and W are N(0,1) in FP32 with one entry
+    in 1000 replaced by +-1000; each run is a scaled cast of both operands to E4M3 (s = 1) followed by the matmul with
+    alpha = K^-1/2.  Timed with the operands resident in HBM; the matmul alone and the cast + matmul run."""
+    dev, st = "cuda:0", torch.cuda.current_stream().cuda_stream
+    out = {}
+    for N in (2048, 4096, 8192):
+        g = torch.Generator(device=dev)
+        g.manual_seed(20230314 + N)
+        ops = []
+        for _ in range(2):
+            a = torch.randn((N, N), generator=g, device=dev, dtype=torch.float32)
+            hit = torch.rand((N, N), generator=g, device=dev) < 1e-3
+            sign = torch.where(torch.rand((N, N), generator=g, device=dev) < 0.5, -1000.0, 1000.0)
+            ops.append(torch.where(hit, sign, a))
+        X8, W8 = (torch.empty((N, N), dtype=torch.uint8, device=dev) for _ in range(2))
+        Y = torch.empty((N, N), dtype=torch.float16, device=dev)
+        stats = torch.zeros(4, dtype=torch.int64, device=dev)
+
+        def casts():
+            us.cast_fp8(ops[0].data_ptr(), us.F32, X8.data_ptr(), us.E4M3, N * N, 1.0, stats.data_ptr(), st)
+            us.cast_fp8(ops[1].data_ptr(), us.F32, W8.data_ptr(), us.E4M3, N * N, 1.0, stats.data_ptr(), st)
+
+        def gemm():
+            us.linear_fwd(X8.data_ptr(), W8.data_ptr(), Y.data_ptr(), N, N, N, us.E4M3, us.E4M3, us.F16, 0.0, us.EPI_NONE, 0.0, None, None, None, 0, st)
+
+        def both():
+            casts()
+            gemm()
+        casts()
+        ramp_up(torch, gemm, 0.05)
+        ms_g = time_steps(torch, gemm, steps, 5)
+        ms_b = time_steps(torch, both, steps, 5)
+        ms_c = time_steps(torch, casts, steps, 5)
+        flop = 2.0 * N ** 3
+        out[str(N)] = {"matmul_ms": ms_g, "matmul_TFLOPs": flop / (ms_g * 1e-3) * 1e-12, "frac_of_mfma_peak": flop / (ms_g * 1e-3) * 1e-12 / PEAK_TFLOPS["fp8"],
+                       "cast_plus_matmul_ms": ms_b, "cast_plus_matmul_TFLOPs": flop / (ms_b * 1e-3) * 1e-12,
+                       "casts_GBps": 2 * 5.0 * N * N / (ms_c * 1e-3) * 1e-9, "kernel": us.last_launch()}
+        del ops, X8, W8, Y
+    out["what"] = "scaled cast FP32 -> E4M3 (5 B / element, with counters) of both operands, then Y = K^-1/2 X W; N(0,1) with 0.1 % +-1000 outliers"
+    return out
+
+
 def cpu_baseline(ffn, sample_tokens):
     """The oracle, as it stands, on the first `sample_tokens` tokens of the same tensors (all of d and f)."""
     import numpy as np
@@ -299,7 +415,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="time HIP-graph replays of the captured step instead of eager launches")
     ap.add_argument("--no-secondary", action="store_true", help="skip the FP16 BERT-base side measurement")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens the oracle is timed on (0: all of the workload's, capped at 8192)")
+    ap.add_argument("--vendor-reference", action="store_true",
+                    help="also time the same FFN written with PyTorch ops / the vendor's FP8 GEMM (context; off by default)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 256 MiB FP16 copy kernel (y = x + 0): the known-size reference for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -337,6 +455,7 @@ def main():
     tflops = ffn.flop / (ms_step * 1e-3) * 1e-12
     dt_key = "fp8" if w["fp8"] else "f16"
 
+    clock_mhz, clock_samples = measure_clock(torch, ffn.step)
     per_call = time_calls(torch, ffn.calls(), args.steps)
     gemms = [c for c in per_call if c["kind"] == "gemm"]
     casts = [c for c in per_call if c["kind"] == "cast"]
@@ -346,6 +465,11 @@ def main():
                 peak=PEAK_TFLOPS[dt_key], unit="TFLOP/s", traffic=measured_traffic(args.workload))
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["ms"] = dom["ms"]
+    if clock_mhz:
+        # the published peak is at the nominal 2400 MHz; under MFMA load the chip runs below it (power)
+        roof["shader_clock_mhz"] = clock_mhz
+        roof["peak_at_measured_clock"] = roof["peak"] * clock_mhz / 2400.0
+        roof["frac_at_measured_clock"] = roof["achieved"] / roof["peak_at_measured_clock"]
     roof["all_gemms_achieved"] = sum(c["flop"] for c in gemms) / (gemm_ms * 1e-3) * 1e-12
     out = {
         "metric": "unit-scaled FFN fwd+bwd TFLOP/s",
@@ -356,15 +480,34 @@ def main():
                    "step": "one batched cast of X,W1,W2,G + Linear+GELU + Linear + 4 backward matmuls (GELU' fused; stored: Z16, H8, Y16, dZ8, dX16, dW16)" if w["fp8"]
                            else "Linear+GELU + Linear + 4 backward matmuls (GELU' fused)"},
         "frac_of_mfma_peak": tflops / PEAK_TFLOPS[dt_key],
+        "shader_clock": {"mhz_during_the_step_loop": clock_mhz, "samples": clock_samples, "nominal_mhz": 2400.0,
+                         "frac_of_mfma_peak_at_measured_clock": (tflops / (PEAK_TFLOPS[dt_key] * clock_mhz / 2400.0)) if clock_mhz else None,
+                         "how": "pp_dpm_sclk sampled every ms from a host thread while the step runs back to back for 0.3 s"},
         "launch": "hip-graph replay of the captured step" if args.graph else "eager",
         "roofline": roof,
         "calls_ms": {c["name"]: round(c["ms"], 5) for c in per_call},
         "calls_tflops": {c["name"]: round(c["flop"] / (c["ms"] * 1e-3) * 1e-12, 1) for c in gemms},
     }
     if casts:
+        # kernel rate: the batched cast launched back to back (launch gaps hidden by the queue), which is what rocprofv3
+        # reports as the kernel's duration; the in-step figure brackets ONE launch with events inside the running step
+        # and so includes the gap to the neighbouring launches
         cb, cm = sum(c["bytes"] for c in casts), sum(c["ms"] for c in casts)
-        out["cast"] = {"GBps": cb / (cm * 1e-3) * 1e-9, "frac_of_hbm_peak": cb / (cm * 1e-3) * 1e-9 / PEAK_HBM_GBS,
-                       "bytes_per_elem": 3}
+        ms_k = time_steps(torch, ffn.all_casts, max(args.steps, 50), 10)
+        out["cast"] = {"GBps": cb / (ms_k * 1e-3) * 1e-9, "frac_of_hbm_peak": cb / (ms_k * 1e-3) * 1e-9 / PEAK_HBM_GBS,
+                       "ms_back_to_back": ms_k, "bytes_per_elem": 3, "bytes_per_launch": cb,
+                       "in_step_event_bracket": {"ms": cm, "GBps": cb / (cm * 1e-3) * 1e-9,
+                                                 "what": "events around the one cast launch inside the step: includes the launch gap"}}
+        ms_act = time_steps(torch, ffn.step_act_casts_only, args.steps, args.warmup)
+        ms_wc = time_steps(torch, ffn.weight_casts, max(args.steps, 50), 10)
+        out["step_with_activation_and_gradient_casts_only"] = {
+            "what": "the step with the E4M3 weights reused (gradient accumulation: the weights change once per many micro-batches); "
+                    "the weight casts are their own figure",
+            "ms_per_step": ms_act, "TFLOPs": ffn.flop / (ms_act * 1e-3) * 1e-12,
+            "frac_of_mfma_peak": ffn.flop / (ms_act * 1e-3) * 1e-12 / PEAK_TFLOPS[dt_key],
+            "weight_casts_ms": ms_wc, "weight_casts_GBps": 3.0 * (ffn.W1.numel() + ffn.W2.numel()) / (ms_wc * 1e-3) * 1e-9}
+        out["gemm_kernels_only"] = {"ms": gemm_ms, "TFLOPs": roof["all_gemms_achieved"], "frac_of_mfma_peak": roof["all_gemms_achieved"] / PEAK_TFLOPS[dt_key],
+                                    "what": "sum of the four matmul launches' event-bracketed durations inside the step"}
     if not args.no_secondary:
         ms_res = time_steps(torch, ffn.step_residual, args.steps, args.warmup)
         out["residual_layer"] = {"what": "same workload with the fixed(tau=0.5) residual interpolation fused into the step "
@@ -456,8 +599,10 @@ def main():
                             "ms_per_step": ms_a, "TFLOPs": a_flop / (ms_a * 1e-3) * 1e-12,
                             "score_tensor_GBps": a_bytes / (ms_a * 1e-3) * 1e-9}
         del aq, ak, av, ado, aA, aP, adP, adA, aO, adQ, adK, adV
-    if not args.no_secondary and w["fp8"]:
+    if args.vendor_reference and w["fp8"]:
         out["pytorch_reference"] = pytorch_reference(torch, w["T"], w["d"], w["f"])
+    if not args.no_secondary:
+        out["range_stress"] = range_stress(torch, us)
     if not args.no_secondary and args.workload != "C2":
         w2 = WORKLOADS["C2"]
         f2 = Ffn(torch, us, synth, w2["T"], w2["d"], w2["f"], False, synth.BASE_SEED + 1)
@@ -477,7 +622,8 @@ def main():
         out["fp8_large"] = {"workload": "C5: " + w5["desc"], "ms_per_step": ms5, "TFLOPs": t5, "frac_of_mfma_peak": t5 / PEAK_TFLOPS["fp8"]}
         del f5
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(ffn, min(args.cpu_sample_tokens, w["T"]))
+        n_cpu = args.cpu_sample_tokens if args.cpu_sample_tokens > 0 else min(w["T"], 8192)
+        out["cpu_baseline"] = cpu_baseline(ffn, min(n_cpu, w["T"]))
     print(json.dumps(out))
 
 

@@ -33,6 +33,37 @@ __device__ __forceinline__ _Float16 to_half(float x) {
   return (_Float16)x;
 }
 
+// ---- FP32 x FP16 -> FP16 with one rounding ---------------------------------------------------------------
+// fp16(t * y) for an FP32 factor t and the FP16 value in half SRC_HI of the pair `ypair`, written into half DST_HI of
+// `dst` (the other half of dst is kept): one v_fma_mix instruction, which rounds the exact product once.  Its addend
+// is -0, so that a zero product keeps its sign ((-0) + (-0) = -0, (+0) + (-0) = +0) and every other product is unchanged.
+template <int SRC_HI, int DST_HI>
+__device__ __forceinline__ void mul_to_half(uint32_t& dst, float t, uint32_t ypair) {
+  const float neg_zero = -0.0f;
+  if constexpr (DST_HI == 0) {
+    if constexpr (SRC_HI == 0)
+      asm volatile("v_fma_mixlo_f16 %0, %1, %2, %3 op_sel:[0,0,0] op_sel_hi:[0,1,0]" : "+v"(dst) : "v"(t), "v"(ypair), "v"(neg_zero));
+    else
+      asm volatile("v_fma_mixlo_f16 %0, %1, %2, %3 op_sel:[0,1,0] op_sel_hi:[0,1,0]" : "+v"(dst) : "v"(t), "v"(ypair), "v"(neg_zero));
+  } else {
+    if constexpr (SRC_HI == 0)
+      asm volatile("v_fma_mixhi_f16 %0, %1, %2, %3 op_sel:[0,0,0] op_sel_hi:[0,1,0]" : "+v"(dst) : "v"(t), "v"(ypair), "v"(neg_zero));
+    else
+      asm volatile("v_fma_mixhi_f16 %0, %1, %2, %3 op_sel:[0,1,0] op_sel_hi:[0,1,0]" : "+v"(dst) : "v"(t), "v"(ypair), "v"(neg_zero));
+  }
+}
+// the same for one value
+__device__ __forceinline__ _Float16 mul_to_half(float t, _Float16 y) {
+  unsigned short yb;
+  __builtin_memcpy(&yb, &y, 2);
+  uint32_t d = 0;
+  mul_to_half<0, 0>(d, t, (uint32_t)yb);
+  const unsigned short r = (unsigned short)d;
+  _Float16 h;
+  __builtin_memcpy(&h, &r, 2);
+  return h;
+}
+
 // ---- FP32 -> FP8 (E4M3: max 448, one NaN, no inf; E5M2: max 57344) -------------------------------
 // The hardware converter rounds to nearest-even and handles subnormals; it turns overflow into
 // NaN/inf, so the value is first clipped to the finite range (that also maps +-inf to +-max).
@@ -112,12 +143,18 @@ __device__ __forceinline__ float gelu_slope_abs(float az, float beta_g) {
   GaussTerms g = gauss_terms(az);
   return beta_g * __builtin_fmaf(az, g.pdf, g.Phi);
 }
-// beta_g * gelu'(z) * gh.  Negative arguments use gelu'(-x) = 1 - gelu'(x), so that the function of
-// |z| can also be tabulated (see the table-driven GEMM epilogue); +-inf and NaN give NaN.
-__device__ __forceinline__ float gelu_grad_scaled(float z, float gh, float beta_g) {
+// beta_g * gelu'(z).  Negative arguments use gelu'(-x) = 1 - gelu'(x), so that the function of |z| can also be
+// tabulated (see the table-driven GEMM epilogue); +-inf and NaN give NaN.
+__device__ __forceinline__ float gelu_slope_scaled(float z, float beta_g) {
   const float t = gelu_slope_abs(__builtin_fabsf(z), beta_g);
-  const float r = (__builtin_signbit(z)) ? beta_g - t : t;
-  return r * gh;
+  return (__builtin_signbit(z)) ? beta_g - t : t;
+}
+// beta_g * gelu'(z) * gh in FP32
+__device__ __forceinline__ float gelu_grad_scaled(float z, float gh, float beta_g) { return gelu_slope_scaled(z, beta_g) * gh; }
+// fp16(beta_g * gelu'(z) * gh) for FP16 z and gh: the FP32 slope times gh, rounded once (what the table-driven epilogue
+// computes from its table of slopes)
+__device__ __forceinline__ _Float16 gelu_grad_half(_Float16 z, _Float16 gh, float beta_g) {
+  return mul_to_half(gelu_slope_scaled((float)z, beta_g), gh);
 }
 
 // ---- the other activations of Table A.2 ---------------------------------------------------------------
@@ -158,20 +195,25 @@ __device__ __forceinline__ float act_scaled(int kind, float x, float scale) {
   }
   return gelu_scaled(x, scale);
 }
-// scale * f'(z) * gh   (relu'(0) = 0)
-__device__ __forceinline__ float act_grad_scaled(int kind, float z, float gh, float scale) {
-  if (kind == 1) return (z > 0.0f ? scale : 0.0f) * gh;
+// scale * f'(z)   (relu'(0) = 0)
+__device__ __forceinline__ float act_slope_scaled(int kind, float z, float scale) {
+  if (kind == 1) return z > 0.0f ? scale : 0.0f;
   if (kind == 2) {                                    // sech^2 = 4u / (1 + u)^2, u = exp(-2|z|)
     const float u = exp_neg(2.0f * __builtin_fabsf(z));
     const float r = __builtin_amdgcn_rcpf(1.0f + u);
-    return scale * (4.0f * u * r * r) * gh;
+    return scale * (4.0f * u * r * r);
   }
   if (kind == 3) {                                    // s (1 - s) = u / (1 + u)^2, u = exp(-|z|)
     const float u = exp_neg(__builtin_fabsf(z));
     const float r = __builtin_amdgcn_rcpf(1.0f + u);
-    return scale * (u * r * r) * gh;
+    return scale * (u * r * r);
   }
-  return gelu_grad_scaled(z, gh, scale);
+  return gelu_slope_scaled(z, scale);
+}
+// scale * f'(z) * gh in FP32, and rounded once to FP16 for an FP16 gh (the form every FP16 backward path uses)
+__device__ __forceinline__ float act_grad_scaled(int kind, float z, float gh, float scale) { return act_slope_scaled(kind, z, scale) * gh; }
+__device__ __forceinline__ _Float16 act_grad_half(int kind, float z, _Float16 gh, float scale) {
+  return mul_to_half(act_slope_scaled(kind, z, scale), gh);
 }
 
 // ---- tables over the FP16 pre-activation (65536 possible inputs) ----------------------------------------

@@ -164,18 +164,26 @@ __global__ void __launch_bounds__(kThreads) gelu_kernel(const T* z, const T* gh,
     vec_t o;
 #pragma unroll
     for (int k = 0; k < V; ++k) {
-      const float r = BWD ? gelu_grad_scaled((float)zv[k], (float)gv[k], s) : gelu_scaled((float)zv[k], s);
-      if constexpr (sizeof(T) == 2) o[k] = to_half(r);
-      else o[k] = r;
+      if constexpr (sizeof(T) == 2 && BWD) {
+        o[k] = gelu_grad_half(zv[k], gv[k], s);        // the same function as the matmul epilogues' GELU'
+      } else {
+        const float r = BWD ? gelu_grad_scaled((float)zv[k], (float)gv[k], s) : gelu_scaled((float)zv[k], s);
+        if constexpr (sizeof(T) == 2) o[k] = to_half(r);
+        else o[k] = r;
+      }
     }
     *reinterpret_cast<vec_t*>(out + v * V) = o;
   }
   const size_t tail0 = nvec * V;
   if (tid < n - tail0) {
     const float zi = (float)z[tail0 + tid];
-    const float r = BWD ? gelu_grad_scaled(zi, (float)gh[tail0 + tid], s) : gelu_scaled(zi, s);
-    if constexpr (sizeof(T) == 2) out[tail0 + tid] = to_half(r);
-    else out[tail0 + tid] = r;
+    if constexpr (sizeof(T) == 2 && BWD) {
+      out[tail0 + tid] = gelu_grad_half(z[tail0 + tid], gh[tail0 + tid], s);
+    } else {
+      const float r = BWD ? gelu_grad_scaled(zi, (float)gh[tail0 + tid], s) : gelu_scaled(zi, s);
+      if constexpr (sizeof(T) == 2) out[tail0 + tid] = to_half(r);
+      else out[tail0 + tid] = r;
+    }
   }
 }
 
@@ -284,9 +292,13 @@ __global__ void __launch_bounds__(kThreads) act_kernel(const T* z, const T* gh, 
   const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
   const size_t nthr = (size_t)gridDim.x * kThreads;
   auto one = [&](T zi, T gi) -> T {
-    const float r = BWD ? act_grad_scaled(kind, s1 * (float)zi, (float)gi, scale) : act_scaled(kind, s1 * (float)zi, scale);
-    if constexpr (sizeof(T) == 2) return to_half(r);
-    else return r;
+    if constexpr (sizeof(T) == 2 && BWD) {
+      return act_grad_half(kind, s1 * (float)zi, gi, scale);
+    } else {
+      const float r = BWD ? act_grad_scaled(kind, s1 * (float)zi, (float)gi, scale) : act_scaled(kind, s1 * (float)zi, scale);
+      if constexpr (sizeof(T) == 2) return to_half(r);
+      else return r;
+    }
   };
   for (size_t v = tid; v < nvec; v += nthr) {
     const vec_t zv = *reinterpret_cast<const vec_t*>(z + v * V);

@@ -166,16 +166,39 @@ __device__ __forceinline__ v8h epilogue_row8(const GemmArgs& g, long idx, v8h y,
     return r;
   }
   if (EPI == EPI_GELU_GRAD_TAB) {
-    v8h r;
+    // r = fp16(slope(z) * y), slope = table[|z|] for z >= 0 and epi_scale - table[|z|] for z < 0 (FP32), the product
+    // rounded once.  Two elements per 32-bit word throughout: packed mask / clamp of the table index, and the
+    // mixed-precision multiply writes each FP16 result straight into its half of the output word.
+    typedef unsigned short v2us __attribute__((ext_vector_type(2)));
+    v4i zw, yw, rw = {0, 0, 0, 0};
+    __builtin_memcpy(&zw, &z, 16);
+    __builtin_memcpy(&yw, &y, 16);
+    const v2us last2 = {(unsigned short)kGeluSlopeLast, (unsigned short)kGeluSlopeLast};
+    v2us amax = {0, 0};
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const uint32_t zb = half_bits(z[k]);
-      const uint32_t a = zb & 0x7fffu;
-      const uint32_t i = a < (uint32_t)kGeluSlopeLast ? a : (uint32_t)kGeluSlopeLast;
-      float t = *US_LDS_PTR(const float, lut + i * 4);
-      t = (zb & 0x8000u) ? g.epi_scale - t : t;
-      t = (a >= 0x7c00u) ? __builtin_nanf("") : t;       // +-inf and NaN, as the arithmetic form gives
-      r[k] = to_half(t * (float)y[k]);
+    for (int q = 0; q < 4; ++q) {
+      const uint32_t zq = (uint32_t)zw[q];
+      const uint32_t a2 = zq & 0x7fff7fffu;                                    // |z| bits of both elements
+      v2us av;
+      __builtin_memcpy(&av, &a2, 4);
+      amax = __builtin_elementwise_max(amax, av);
+      const v2us iv = __builtin_elementwise_min(av, last2);                    // beyond 8 the slope is exactly epi_scale
+      float t0 = *US_LDS_PTR(const float, lut + (uint32_t)iv.x * 4);
+      float t1 = *US_LDS_PTR(const float, lut + (uint32_t)iv.y * 4);
+      t0 = (zq & 0x8000u) ? g.epi_scale - t0 : t0;
+      t1 = ((int)zq < 0) ? g.epi_scale - t1 : t1;
+      uint32_t d = 0;
+      mul_to_half<0, 0>(d, t0, (uint32_t)yw[q]);
+      mul_to_half<1, 1>(d, t1, (uint32_t)yw[q]);
+      rw[q] = (int)d;
+    }
+    v8h r;
+    __builtin_memcpy(&r, &rw, 16);
+    // +-inf and NaN pre-activations give NaN, as the arithmetic form does: rare, so the wave looks for one first
+    if (__builtin_amdgcn_ballot_w64(amax.x >= 0x7c00u || amax.y >= 0x7c00u) != 0) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if ((half_bits(z[k]) & 0x7fffu) >= 0x7c00u) r[k] = half_from_bits(0x7e00u);
     }
     if (g.C) store_grad(g, idx, r);
     if (g.aux8) {
@@ -218,10 +241,10 @@ __device__ __forceinline__ v8h epilogue_row8(const GemmArgs& g, long idx, v8h y,
     for (int k = 0; k < 8; ++k) r[k] = half_from_bits(0);
     if (g.act == 0) {
 #pragma unroll
-      for (int k = 0; k < 8; ++k) r[k] = to_half(gelu_grad_scaled((float)z[k], (float)y[k], g.epi_scale));
+      for (int k = 0; k < 8; ++k) r[k] = gelu_grad_half(z[k], y[k], g.epi_scale);
     } else {
 #pragma unroll
-      for (int k = 0; k < 8; ++k) r[k] = to_half(act_grad_scaled(g.act, (float)z[k], (float)y[k], g.epi_scale));
+      for (int k = 0; k < 8; ++k) r[k] = act_grad_half(g.act, (float)z[k], y[k], g.epi_scale);
     }
     if (g.C) store_grad(g, idx, r);      // optional: the FP8 copy may be all that is wanted
   }
