@@ -108,7 +108,7 @@ __device__ __forceinline__ uint32_t cvt_pk_fp8_from_half(v2h h) {
 // Q(x) = P(N(0,1) > x) for x >= 0 is evaluated as exp(-x^2/2) * t*(c0 + c1 t + ... + c5 t^5) with
 // t = 1/(1 + p x): a fit of the scaled complementary error function erfcx(x/sqrt2)/2 whose relative
 // error stays below 4e-6 on [0, 14], so Phi keeps relative accuracy in the negative tail too
-// (fitted offline by reweighted least squares against a double-precision erfcx).
+// (coefficients from fit_gauss_tail.py beside this header: reweighted least squares against a double-precision erfcx).
 struct GaussTerms {
   float Phi;  // standard normal CDF at z
   float pdf;  // standard normal density at z
