@@ -24,7 +24,8 @@ def errors(gpu: np.ndarray, ref: np.ndarray, fp8: bool = False, scale: float = 1
     g, r = np.asarray(gpu).astype(np.float64), np.asarray(ref).astype(np.float64)
     same_inf = np.isinf(g) & np.isinf(r) & (np.sign(g) == np.sign(r))
     both_nan = np.isnan(g) & np.isnan(r)
-    d = np.where(same_inf | both_nan, 0.0, np.abs(g - r))
+    with np.errstate(invalid="ignore"):                        # inf - inf on one side only is handled below
+        d = np.where(same_inf | both_nan, 0.0, np.abs(g - r))
     d = np.where(np.isnan(d), np.inf, d)                       # NaN on one side only, or inf of opposite signs
     a = FP8_ABS * scale if fp8 else 0.0
     if allow is not None:
