@@ -24,13 +24,16 @@ def errors(gpu: np.ndarray, ref: np.ndarray, fp8: bool = False, scale: float = 1
     g, r = np.asarray(gpu).astype(np.float64), np.asarray(ref).astype(np.float64)
     same_inf = np.isinf(g) & np.isinf(r) & (np.sign(g) == np.sign(r))
     both_nan = np.isnan(g) & np.isnan(r)
-    with np.errstate(invalid="ignore"):                        # inf - inf on one side only is handled below
-        d = np.where(same_inf | both_nan, 0.0, np.abs(g - r))
-    d = np.where(np.isnan(d), np.inf, d)                       # NaN on one side only, or inf of opposite signs
+    agree = same_inf | both_nan                                # compared by class: no error
+    with np.errstate(invalid="ignore"):
+        d = np.where(agree, 0.0, np.abs(g - r))
+    d = np.where(np.isnan(d), np.inf, d)                       # NaN or inf on one side only, or inf of opposite signs
     a = FP8_ABS * scale if fp8 else 0.0
     if allow is not None:
         a = a + np.asarray(allow, np.float64)
-    gated = float(np.max(np.maximum(d - a, 0.0) / np.maximum(np.abs(r), tau * scale))) if d.size else 0.0
+    den = np.where(np.isfinite(r), np.maximum(np.abs(r), tau * scale), 1.0)
+    excess = np.where(np.isinf(d), np.inf, np.maximum(d - a, 0.0))
+    gated = float(np.max(excess / den)) if d.size else 0.0
     nz = (r != 0) & np.isfinite(r)
     unfloored = float(np.max(d[nz] / np.abs(r[nz]))) if nz.any() else 0.0
     fin = np.isfinite(d)
