@@ -33,6 +33,27 @@ __device__ __forceinline__ _Float16 to_half(float x) {
   return (_Float16)x;
 }
 
+// ---- write-through global stores ------------------------------------------------------------------------------
+// A plain (or non-temporal) store leaves its line dirty in the XCD's L2 until it is evicted or until the write-back
+// that ends the kernel; with tens of MB written per launch every launch then ends with a burst of up to 32 MB that
+// nothing overlaps (measured with an idle kernel that only writes: 1.2 us between launches without writes, 4.0 us with
+// 32 MB or more of plain or non-temporal stores, 1.2 us again with the stores below).  sc0 sc1 sends the data on to
+// memory at once, where the next launch finds it (its own L2 starts empty either way).  8 or 16 bytes per lane; the
+// s_nop covers the store-data hazard that the compiler cannot see through the asm statement.
+template <class V>
+__device__ __forceinline__ void wt_store(V* p, V v) {
+  static_assert(sizeof(V) == 16 || sizeof(V) == 8, "");
+  if constexpr (sizeof(V) == 16) {
+    v4i w;
+    __builtin_memcpy(&w, &v, 16);
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" ::"v"(p), "v"(w) : "memory");
+  } else {
+    v2i w;
+    __builtin_memcpy(&w, &v, 8);
+    asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1\n\ts_nop 1" ::"v"(p), "v"(w) : "memory");
+  }
+}
+
 // ---- FP32 x FP16 -> FP16 with one rounding ---------------------------------------------------------------
 // fp16(t * y) for an FP32 factor t and the FP16 value in half SRC_HI of the pair `ypair`, written into half DST_HI of
 // `dst` (the other half of dst is kept): one v_fma_mix instruction, which rounds the exact product once.  Its addend

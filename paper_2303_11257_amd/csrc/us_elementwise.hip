@@ -66,7 +66,7 @@ __global__ void __launch_bounds__(kThreads) cast_kernel(const SrcT* __restrict__
         count_one<FMT>(p3, w >> 24, c);
       }
     }
-    *reinterpret_cast<v4i*>(dst + v * 16) = out;
+    wt_store(reinterpret_cast<v4i*>(dst + v * 16), out);
   };
   // two vectors per thread and step, both requested before the first is used (the counting variant runs on few
   // blocks, so the bytes in flight have to come from each thread)
@@ -139,7 +139,7 @@ __device__ __forceinline__ void cast_run_half(const _Float16* __restrict__ src, 
         out[q] = (int)(cvt_pk_fp8_from_half<FMT>(p0) | (cvt_pk_fp8_from_half<FMT>(p1) << 16));
         out[2 + q] = (int)(cvt_pk_fp8_from_half<FMT>(p2) | (cvt_pk_fp8_from_half<FMT>(p3) << 16));
       }
-      *reinterpret_cast<v4i*>(dst + v * 16) = out;
+      wt_store(reinterpret_cast<v4i*>(dst + v * 16), out);
     }
   }
   // the last n % 16 elements, by the block that owns the end of the tensor
