@@ -185,7 +185,7 @@ __global__ void __launch_bounds__(kThreads) gelu_kernel(const T* z, const T* gh,
         else o[k] = r;
       }
     }
-    *reinterpret_cast<vec_t*>(out + v * V) = o;
+    wt_store(reinterpret_cast<vec_t*>(out + v * V), o);
   }
   const size_t tail0 = nvec * V;
   if (tid < n - tail0) {
@@ -324,7 +324,7 @@ __global__ void __launch_bounds__(kThreads) act_kernel(const T* z, const T* gh, 
     vec_t o;
 #pragma unroll
     for (int k = 0; k < V; ++k) o[k] = one(zv[k], gv[k]);
-    *reinterpret_cast<vec_t*>(out + v * V) = o;
+    wt_store(reinterpret_cast<vec_t*>(out + v * V), o);
   }
   const size_t tail0 = nvec * V;
   if (tid < n - tail0) out[tail0 + tid] = one(z[tail0 + tid], BWD ? gh[tail0 + tid] : z[tail0 + tid]);
@@ -363,7 +363,7 @@ __global__ void __launch_bounds__(kThreads) weighted_add_kernel(const T* a, cons
     vec_t o;
 #pragma unroll
     for (int k = 0; k < V; ++k) o[k] = one(av[k], bv[k]);
-    *reinterpret_cast<vec_t*>(out + v * V) = o;
+    wt_store(reinterpret_cast<vec_t*>(out + v * V), o);
   }
   const size_t tail0 = nvec * V;
   if (tid < n - tail0) out[tail0 + tid] = one(a[tail0 + tid], b[tail0 + tid]);

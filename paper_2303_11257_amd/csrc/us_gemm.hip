@@ -53,10 +53,10 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
   for (int k = 1; k < splits; ++k) s += *reinterpret_cast<const v4f*>(partial + (size_t)k * total + i4);
   s *= scale;
   if (out_is_f32) {
-    *reinterpret_cast<v4f*>((float*)out + i4) = s;
+    wt_store(reinterpret_cast<v4f*>((float*)out + i4), s);
   } else {
     v4h o = {to_half(s.x), to_half(s.y), to_half(s.z), to_half(s.w)};
-    *reinterpret_cast<v4h*>((_Float16*)out + i4) = o;
+    wt_store(reinterpret_cast<v4h*>((_Float16*)out + i4), o);
   }
 }
 

@@ -58,7 +58,7 @@ __global__ void __launch_bounds__(kLnThreads) ln_fwd_kernel(const _Float16* X, c
 #pragma unroll
         for (int e = 0; e < 8; ++e)
           o[e] = to_half(__builtin_fmaf(((float)x.v[k][e] - mean) * rstd, (float)wr.v[k][e], (float)cr.v[k][e]));
-        *reinterpret_cast<v8h*>(Y + row * n + col) = o;
+        wt_store(reinterpret_cast<v8h*>(Y + row * n + col), o);
       }
     }
   }
@@ -124,7 +124,7 @@ __global__ void __launch_bounds__(kLnThreads) ln_bwd_kernel(const _Float16* X, c
           const float gh = (float)g.v[k][e] * (float)wr.v[k][e];
           o[e] = to_half(rstd * (gh - m1 - xh * m2));
         }
-        *reinterpret_cast<v8h*>(dX + row * n + col) = o;
+        wt_store(reinterpret_cast<v8h*>(dX + row * n + col), o);
       }
     }
   }

@@ -60,7 +60,7 @@ __global__ void __launch_bounds__(kThreads) softmax_fwd_kernel(const _Float16* X
         v8h o;
 #pragma unroll
         for (int q = 0; q < 8; ++q) o[q] = to_half(e[k][q] * inv);
-        *reinterpret_cast<v8h*>(Y + row * s + col) = o;
+        wt_store(reinterpret_cast<v8h*>(Y + row * s + col), o);
       }
     }
   }
@@ -92,7 +92,7 @@ __global__ void __launch_bounds__(kThreads) softmax_bwd_kernel(const _Float16* X
         v8h o;
 #pragma unroll
         for (int q = 0; q < 8; ++q) o[q] = to_half(c * e[k][q] * ((float)g.v[k][q] - dot));
-        *reinterpret_cast<v8h*>(dX + row * s + col) = o;
+        wt_store(reinterpret_cast<v8h*>(dX + row * s + col), o);
       }
     }
   }
@@ -175,7 +175,7 @@ __global__ void __launch_bounds__(kThreads) xent_kernel(const _Float16* X, const
           const float p = __builtin_amdgcn_exp2f((s1 * (float)v[q] - m) * kLog2e) * inv;
           o[q] = to_half(bs * (p - ((i * 8 + q) == c ? 1.0f : 0.0f)));
         }
-        *reinterpret_cast<v8h*>(dX + r * s + i * 8) = o;
+        wt_store(reinterpret_cast<v8h*>(dX + r * s + i * 8), o);
       }
     }
     __syncthreads();                                    // the row in LDS is free for the next one
