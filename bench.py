@@ -394,6 +394,22 @@ def cpu_baseline(ffn, sample_tokens):
                 sample=f"first {n} of {ffn.T} tokens, full d_model and d_ff, every stage (casts, 6 matmuls, GELU fwd/bwd)")
 
 
+def cpu_range_stress(N=2048):
+    """The oracle on one run of the range-stress sweep: both scaled casts (FP32 -> E4M3 with counters) and the product."""
+    import numpy as np
+    import oracle
+    import synth
+    seed = synth.C4_SEED + N
+    ops = [synth.place_outliers(synth.normal(seed, t, (N, N), 1.0, np.float32), 1.0, synth.outlier_positions(seed, t, N * N))
+           for t in (synth.T_X, synth.T_W1)]
+    t0 = time.perf_counter()
+    codes = [oracle.cast_fp8(a, oracle.E4M3, 1.0)[0] for a in ops]
+    oracle.linear_fwd(codes[0], codes[1], float(N) ** -0.5, oracle.E4M3, oracle.E4M3)
+    dt = time.perf_counter() - t0
+    return dict(value=2.0 * N ** 3 / dt * 1e-12, unit="TFLOP/s", cores=oracle.cpu_threads(), kind="oracle", seconds=dt,
+                sample=f"range stress, M = N = K = {N}, sigma = 1, s = 1: two casts with counters and the matmul")
+
+
 def measured_traffic(workload):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (None if absent)."""
     path = os.path.join(ROOT, "profiles", f"ffn_bwd_layer2_{workload.lower()}_hbm_traffic.md")
@@ -611,6 +627,8 @@ def main():
         t2 = f2.flop / (ms2 * 1e-3) * 1e-12
         out["fp16_bert_base"] = {"workload": "C2: " + w2["desc"], "ms_per_step": ms2, "TFLOPs": t2,
                                  "frac_of_mfma_peak": t2 / PEAK_TFLOPS["f16"]}
+        if not args.no_cpu_baseline:
+            out["fp16_bert_base"]["cpu_baseline"] = cpu_baseline(f2, w2["T"])
         del f2
     if not args.no_secondary and args.workload == "C3":
         # the same step at a size where the main loops dominate (reduction lengths 4096 / 16384 / 32768)
@@ -620,7 +638,11 @@ def main():
         ms5 = time_steps(torch, f5.step, 10, 2)
         t5 = f5.flop / (ms5 * 1e-3) * 1e-12
         out["fp8_large"] = {"workload": "C5: " + w5["desc"], "ms_per_step": ms5, "TFLOPs": t5, "frac_of_mfma_peak": t5 / PEAK_TFLOPS["fp8"]}
+        if not args.no_cpu_baseline:
+            out["fp8_large"]["cpu_baseline"] = cpu_baseline(f5, 256)
         del f5
+    if not args.no_cpu_baseline and not args.no_secondary:
+        out["range_stress"]["cpu_baseline"] = cpu_range_stress(2048)
     if not args.no_cpu_baseline:
         n_cpu = args.cpu_sample_tokens if args.cpu_sample_tokens > 0 else min(w["T"], 8192)
         out["cpu_baseline"] = cpu_baseline(ffn, min(n_cpu, w["T"]))

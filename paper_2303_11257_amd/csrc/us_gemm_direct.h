@@ -61,8 +61,12 @@ __device__ __forceinline__ int swz(int row) {
     static_assert(PITCH == 128 || PITCH == 256, "K-strided FP8 pitch");
     return PITCH == 256 ? ((row & 7) << 1) : (((row >> 1) & 3) << 1);
   } else {
-    static_assert(PITCH == 256 || PITCH == 512, "K-strided FP16 pitch");
-    return (row & 3) << 2;
+    static_assert(PITCH == 256 || PITCH == 384 || PITCH == 512, "K-strided FP16 pitch");
+    // The 32 lanes a transposing read serves together touch 64 contiguous bytes in each of four consecutive k-rows.
+    // Pitches of 256 / 512 B put those rows on the same banks: each row moves by a different multiple of 64 B.  A pitch of
+    // 384 B (a tile 192 values wide) already alternates between two bank halves, so one more bit separates rows 0, 1
+    // from rows 2, 3 (flipping bit 2 of the chunk index stays inside the row: 24 chunks are three groups of eight).
+    return PITCH == 384 ? ((row >> 1) & 1) << 2 : (row & 3) << 2;
   }
 }
 

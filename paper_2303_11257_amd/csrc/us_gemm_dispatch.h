@@ -5,6 +5,7 @@
 #include "us_gemm_direct.h"
 #include "us_gemm_staged.h"
 #include "us_launch.h"
+#include <cstdlib>
 
 namespace us {
 
@@ -26,6 +27,13 @@ using CfgM256 = GemmCfg<256, 128, 2, 2, 128, 3, 1, 2>;
 //         on the tile, two groups sharing the k-steps of each stage, four stages; 10-16 % faster than D128 there
 using CfgW128 = GemmCfg<128, 128, 2, 2, 128, 4, 1, 2>;
 
+//   E192: 256 x 192 tile, 8 waves (4 x 2, 64 x 96 accumulators per wave), FP16 only: outputs that make one tile per CU
+//         this way and only three quarters as many 256 x 256 tiles (BERT-base: 4096 x 3072 -> 16 x 16 = 256 instead of 192)
+using CfgE192 = GemmCfg<256, 192, 4, 2, 128, 2, 1>;
+//   H256: 128 x 256 tile, 8 waves (2 x 4, 64 x 64 per wave): the table-driven GELU' next to grad_W tiles in a paired launch
+//         whose large tiles would not fit one round
+using CfgH256 = GemmCfg<128, 256, 2, 4, 128, 2, 1>;
+
 inline long ceil_div(long a, long b) { return (a + b - 1) / b; }
 
 // All windows below are stated in units of the device's CU count (MI355X: 256), read from the device.
@@ -37,6 +45,13 @@ inline long cu_count() { return device_info().cus; }
 inline bool use_big_tile(long M, long N, int splits) {
   const long t = ceil_div(M, 256) * ceil_div(N, 256) * splits, cu = cu_count();
   return 2 * t >= 3 * cu || (4 * t >= 3 * cu && t <= cu);
+}
+
+// FP16 products whose output is covered exactly by 256 x 192 tiles, at most one per CU and at least seven eighths of
+// the CUs busy
+inline bool use_wide_tile(long M, long N) {
+  const long t = ceil_div(M, 256) * ceil_div(N, 192), cu = cu_count();
+  return N % 192 == 0 && t <= cu && 8 * t >= 7 * cu;
 }
 
 // grad_W whose 128 x 128 tiles just about cover the CUs once (C3: 4096 x 1024 -> 256 tiles): instead of
@@ -106,6 +121,10 @@ hipError_t launch_sized(const GemmProblem& p, int splits, long k_per_split, hipS
   const bool direct_ok = p.K > 0 && p.K % bk == 0;      // slice lengths are multiples of 128 already
   if (!direct_ok) return launch_one<false, CfgS128, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
   const bool batched = p.batch > 1;      // the tile count that decides is the whole batch's
+  if constexpr (!FP8 && (A_KC || B_KC) && EPI == EPI_STORE && !WIDE) {
+    if (splits == 1 && !batched && use_wide_tile(p.M, p.N))
+      return launch_one<true, CfgE192, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
+  }
   if (use_big_tile(p.M, p.N, splits * (int)(batched ? p.batch : 1)) && (!batched || (p.M >= 256 && p.N >= 256)))
     return launch_one<true, CfgD256, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
   if (batched) return launch_one<true, CfgD128, FP8, FA, FB, A_KC, B_KC, EPI, WIDE>(p, splits, k_per_split, st);
@@ -133,6 +152,11 @@ template <bool FP8>
 inline bool table_path_ok(const GemmProblem& p) {
   const long bk = FP8 ? 128 : 64;
   return p.table != nullptr && p.act == 0 && p.K > 0 && p.K % bk == 0 && use_big_tile(p.M, p.N, 1);   // the tables are gelu's
+}
+
+// ... and for the 256 x 192 tile (FP16, no column sums: a lane of its epilogue does not keep to the same columns)
+inline bool wide_table_path_ok(const GemmProblem& p) {
+  return p.table != nullptr && p.act == 0 && p.K > 0 && p.K % 64 == 0 && p.colsum == nullptr && use_wide_tile(p.M, p.N);
 }
 
 // Plain store epilogue: FP16 or FP32 output.

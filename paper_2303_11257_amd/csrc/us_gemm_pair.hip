@@ -44,6 +44,23 @@ bool small_tile_ok(const GemmProblem& dx) {
   return dx.epi == US_EPI_NONE && t <= cu_count() && dx.K >= 1024 && !use_big_tile(dx.M, dx.N, 1);
 }
 
+// grad_X without an epilogue whose 256 x 128 tiles, together with grad_W's tiles, give every CU at most one tile
+// (BERT-base layer 1: 96 + 144): one round instead of 192 + 144 small tiles in one and a third
+bool mid_one_round_ok(const GemmProblem& dx, const GemmProblem& dw) {
+  const long tw = long_tile_ok(dw) ? ceil_div(dw.M, 256) * ceil_div(dw.N, 128) : ceil_div(dw.M, 128) * ceil_div(dw.N, 128);
+  const long t = ceil_div(dx.M, 256) * ceil_div(dx.N, 128) + tw;
+  return (dx.epi == US_EPI_NONE || dx.epi == US_EPI_RESIDUAL) && t <= cu_count() && 8 * t >= 7 * cu_count() && dx.K >= 2048;
+}
+
+// grad_X with the table-driven GELU' whose large tiles fit one round on their own but not next to grad_W's tiles
+// (BERT-base layer 2: 192 + 144 on 256 CUs): twice as many tiles of 128 x 256 fill the second round's gaps
+// (FP16: 62.7 -> 59.5 us, same box)
+bool half_tile_ok(const GemmProblem& dx, const GemmProblem& dw) {
+  const long tw = long_tile_ok(dw) ? ceil_div(dw.M, 256) * ceil_div(dw.N, 128) : ceil_div(dw.M, 128) * ceil_div(dw.N, 128);
+  const long t = ceil_div(dx.M, 256) * ceil_div(dx.N, 256);
+  return t <= cu_count() && t + tw > cu_count();
+}
+
 template <bool FP8, class KW>
 hipError_t launch_pair_kw(const GemmProblem& dx, const GemmProblem& dw, hipStream_t st) {
   constexpr int FG = FP8 ? 1 : 0;                     // gradient operand format (E5M2) where it applies
@@ -56,6 +73,8 @@ hipError_t launch_pair_kw(const GemmProblem& dx, const GemmProblem& dw, hipStrea
       hipError_t e = launch_gelu_slope_table(q.table, dx.epi_scale, st);
       if (e != hipSuccess) return e;
     }
+    if (half_tile_ok(dx, dw))
+      return launch_pair<GemmKind<CfgH256, FP8, FG, 0, true, true, EPI_GELU_GRAD_TAB, false>, KW>(q, dw, st);
     return launch_pair<GemmKind<CfgD256, FP8, FG, 0, true, true, EPI_GELU_GRAD_TAB, false>, KW>(q, dw, st);
   }
   // the large tile also when it and grad_W's long tiles fill the CUs exactly once
@@ -65,6 +84,8 @@ hipError_t launch_pair_kw(const GemmProblem& dx, const GemmProblem& dw, hipStrea
     return launch_pair<GemmKind<CfgM256, FP8, FG, 0, true, true, EPI_RESIDUAL, false>, KW>(dx, dw, st);
   }
   if (big) return launch_pair<GemmKind<CfgD256, FP8, FG, 0, true, true, EPI_STORE, false>, KW>(dx, dw, st);
+  if (mid_one_round_ok(dx, dw))
+    return launch_pair<GemmKind<CfgM256, FP8, FG, 0, true, true, EPI_STORE, false>, KW>(dx, dw, st);
   if (small_tile_ok(dx)) return launch_pair<GemmKind<CfgW128, FP8, FG, 0, true, true, EPI_STORE, false>, KW>(dx, dw, st);
   return launch_pair<GemmKind<CfgM256, FP8, FG, 0, true, true, EPI_STORE, false>, KW>(dx, dw, st);
 }
@@ -95,7 +116,7 @@ bool gemm_pair_applicable(const GemmProblem& dx, const GemmProblem& dw) {
   // grad_X with the arithmetic activation-derivative epilogue on 256 x 128 tiles (an output too small for the large tile)
   const bool mid_act = dx.epi == US_EPI_GELU_GRAD && !big && 4 * t_mid >= 3 * cu_count() && t_mid <= 2 * cu_count();
   const bool small_pair = (small_tile_ok(dx) && !mid_tile_ok(dx)) || mid_act;
-  if (dx.K <= 0 || dx.K % bk || !(big || mid_tile_ok(dx) || small_pair || one_round_ok(dx, dw))) return false;
+  if (dx.K <= 0 || dx.K % bk || !(big || mid_tile_ok(dx) || small_pair || one_round_ok(dx, dw) || mid_one_round_ok(dx, dw))) return false;
   if (dx.epi == US_EPI_GELU_GRAD && big && (!dx.table || dx.act != 0)) return false;   // large tile: table-driven epilogue only
   if (dx.epi != US_EPI_NONE && dx.epi != US_EPI_GELU_GRAD && dx.epi != US_EPI_RESIDUAL) return false;
   if (!use_wave_split_tile(dw.M, dw.N, dw.K)) return false;

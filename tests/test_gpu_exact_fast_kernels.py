@@ -23,7 +23,9 @@ pytestmark = pytest.mark.gpu
 # are compared too; they take the plain 128 x 128 tile wherever the FP16 result takes a wave-group tile.)
 CASES = [
     # forward 192 large tiles, one stage pair of reduction; grad_X few small tiles with two wave groups; grad_W K slices
-    dict(shape=(4096, 256, 3072), fwd="direct:256x256:wk1", dx="direct:128x128:wk2:st4", dw="direct:128x128:wk1:st2:{p}:TN:partial:f32:s8",
+    # (FP16: the 4096 x 3072 output on 16 x 16 tiles of 256 x 192, one per CU, instead of 192 of 256 x 256)
+    dict(shape=(4096, 256, 3072), fwd={"fp8": "direct:256x256:wk1", "f16": "direct:256x192:wk1:st2:f16:NN"}, dx="direct:128x128:wk2:st4",
+         dw="direct:128x128:wk1:st2:{p}:TN:partial:f32:s8",
          both=None),
     # forward: 256 tiles of 256 x 128 (FP8) / plain small tiles (FP16); backward pair: wave-split small grad_X + long grad_W tiles
     dict(shape=(2048, 1024, 4096), fwd={"fp8": "direct:256x128:wk2:st3", "f16": "direct:128x128:wk1:st2"}, dx="direct:128x128:wk2:st4",
@@ -38,6 +40,9 @@ CASES = [
     # grad_X on 192 tiles of 256 x 128 next to a wave-split grad_W of 192 small tiles
     dict(shape=(3072, 2048, 1536), fwd="direct:128x128:wk1:st2", dx={"fp8": "direct:256x128:wk2:st3", "f16": "direct:128x128:wk1:st2"},
          dw="direct:128x128:wk2:st2:{p}:TN", both="pair:256x128:wk2:st3:{p}:NT:store:s1 + pair:128x128:wk2:st2:{p}:TN", stride=5),
+    # the BERT-base layer-1 backward shape: grad_X on 96 tiles of 256 x 128 + grad_W on 144 wave-split small tiles, one round
+    dict(shape=(4096, 768, 3072), fwd={"fp8": "direct:256x256:wk1", "f16": "direct:256x192:wk1:st2:f16:NN"}, dx="direct:128x128:wk2:st4", dw="direct:128x128:wk2:st2:{p}:TN",
+         both="pair:256x128:wk2:st3:{p}:NT:store:s1 + pair:128x128:wk2:st2:{p}:TN", stride=11),
     # both on 128 x 128 tiles with two wave groups
     dict(shape=(1024, 2048, 1536), fwd="direct:128x128:wk2:st4", dx="direct:128x128:wk2:st4", dw="direct:128x128:wk2:st2:{p}:TN",
          both="pair:128x128:wk2:st4:{p}:NT:store:s1 + pair:128x128:wk2:st2:{p}:TN"),
@@ -141,6 +146,8 @@ def test_integer_operands_on_the_fast_kernels(case, fp8):
 @pytest.mark.parametrize("fshape,shape,both", [
     ((4096, 256, 3072), (6144, 4096, 1024), "pair:256x256:wk1:st2:{p}:NT:gelu_grad_tab:s1 + pair:256x128:wk2:st3:{p}:TN"),
     (None, (3072, 2048, 1536), "pair:256x128:wk2:st3:{p}:NT:act_grad:s1 + pair:128x128:wk2:st2:{p}:TN"),
+    # the BERT-base layer-2 backward shape: grad_X on 384 tiles of 128 x 256 next to 144 grad_W tiles
+    (None, (4096, 3072, 768), "pair:128x256:wk1:st2:{p}:NT:gelu_grad_tab:s1 + pair:128x128:wk2:st2:{p}:TN"),
 ])
 def test_integer_operands_through_the_fused_epilogues(fshape, shape, both, fp8):
     """The activation epilogues on the same exact products.  Forward: the stored pre-activation Z must be the exact
@@ -157,7 +164,7 @@ def test_integer_operands_through_the_fused_epilogues(fshape, shape, both, fp8):
         H16 = empty((b, n), np.float16) if not fp8 else None
         H8 = empty((b, n), np.uint8) if fp8 else None
         Z = F.fwd(alpha, us.F16, epi=us.EPI_GELU, aux16=H16, aux8=H8, workspace=True)
-        rec = _launched(f"direct:256x256:wk1:st2:{p}:NN:gelu_tab", "forward with GELU")
+        rec = _launched(f"direct:{'256x256' if fp8 else '256x192'}:wk1:st2:{p}:NN:gelu_tab", "forward with GELU")
         assert np.array_equal(_take(Z, rf), O.linear_fwd(F.X[rf], F.W, alpha, F.odt[0], F.odt[1], O.F16)), f"Z ({rec})"
         del F, Z, H16, H8
     b, m, n = shape
@@ -170,7 +177,7 @@ def test_integer_operands_through_the_fused_epilogues(fshape, shape, both, fp8):
     tZ = to_dev(Zpre)
     dZ8 = empty((b, m), np.uint8) if fp8 else None
     dZ, dW = L.bwd(bx, bw, us.F16, epi=us.EPI_GELU_GRAD, epi_scale=1.0, Zpre=tZ, aux8=dZ8)
-    rec = _launched(both.replace("{p}", p), "backward with the activation derivative")
+    rec = _launched(_want(both, fp8), "backward with the activation derivative")
     dH = O.linear_bwd_dx(G[rb], W, bx, og, ow, O.F16)
     ref = O.gelu_bwd(Zpre[rb], dH, 1.0)
     assert np.array_equal(ref, np.where(sign[rb] > 0, dH, np.float16(0)))          # the oracle agrees that this case is exact
