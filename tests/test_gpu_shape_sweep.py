@@ -28,6 +28,9 @@ BASE = [
     (6000, 2048, 1008),   # forward: 192 tiles of 256 x 128 with two wave groups, ragged in both dimensions
     (2304, 4000, 1024),   # paired backward with grad_W on 128 long (256 x 128) tiles, ragged; grad_X on 256 x 128 tiles
     (7936, 1008, 4096),   # paired backward as one round: 124 large grad_X tiles + 128 long grad_W tiles, both ragged
+    (4000, 192, 3072),    # forward (FP16): 16 x 16 tiles of 256 x 192, the last row of tiles ragged
+    (4096, 752, 3072),    # paired backward as one round: 96 grad_X tiles of 256 x 128 (ragged) + 144 wave-split grad_W tiles
+    (4096, 3056, 768),    # paired backward: GELU' on 128 x 256 tiles (ragged) next to 144 grad_W tiles
 ]
 
 
