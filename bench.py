@@ -391,7 +391,7 @@ def cpu_baseline(ffn, sample_tokens):
     dt = time.perf_counter() - t0
     flop = 12.0 * n * ffn.d * ffn.f
     return dict(value=flop / dt * 1e-12, unit="TFLOP/s", cores=oracle.cpu_threads(), kind="oracle", seconds=dt,
-                sample=f"first {n} of {ffn.T} tokens, full d_model and d_ff, every stage (casts, 6 matmuls, GELU fwd/bwd)")
+                sample=f"first {n} of {ffn.T} tokens, full d_model and d_ff, every stage ({'casts, ' if ffn.fp8 else ''}6 matmuls, GELU fwd/bwd)")
 
 
 def cpu_range_stress(N=2048):
