@@ -1,6 +1,6 @@
 """GPU parity over a seeded sweep of shapes placed around the limits where the library changes kernel, tile shape or
 launch form (register-staged / direct loads, 128 x 128 / 256 x 256 / wave-split tiles, K slices, paired backward
-launch), with ragged edges.  Forward (plain, GELU, residual, with and without bias and workspace) and backward
+launch), with ragged edges, and over 24 seeded random shapes.  Forward (plain, GELU, residual, with and without bias and workspace) and backward
 (grad_X and grad_W in one call, with and without GELU'), FP16 and FP8, against the oracle on sampled rows."""
 import numpy as np
 import pytest
@@ -41,6 +41,16 @@ def _shapes():
         out.append((b, m, n))
         jitter = lambda v: int(max(16, v + 16 * rng.integers(-2, 3)))
         out.append((jitter(b), jitter(m), jitter(n)))
+    # ... and shapes nobody chose: every dimension a seeded draw, half of them multiples of 128 or 192 (so that the
+    # direct-to-LDS kernels and their tile choices are reached), the rest multiples of 16 (ragged tiles, staged kernel)
+    rng = np.random.default_rng(20230317)
+
+    def draw(lo, hi):
+        kind = rng.integers(0, 4)
+        unit = (16, 16, 128, 192)[kind]
+        return int(unit * rng.integers(max(1, lo // unit), hi // unit + 1))
+    for _ in range(24):
+        out.append((draw(256, 6144), draw(128, 4224), draw(128, 4224)))
     return out
 
 
