@@ -98,9 +98,9 @@ __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n,
   tn = base_n + band * grp_w + r % w;
 }
 
-// Host side: the split gm x gn = number of XCDs that divides the tile grid and minimises the number of operand
-// panels one XCD touches; gm = gn = 0 when the grid does not divide.
-inline void choose_xcd_grid(long tiles_m, long tiles_n, int nxcd, int& gm, int& gn) {
+// Host side: the split gm x gn = number of XCDs that divides the tile grid and minimises the operand bytes one XCD
+// touches (bm, bn: the tile's rows of A and of B); gm = gn = 0 when the grid does not divide.
+inline void choose_xcd_grid(long tiles_m, long tiles_n, int nxcd, int bm, int bn, int& gm, int& gn) {
   gm = gn = 0;
   if (nxcd < 2 || (tiles_m * tiles_n) % nxcd != 0) return;
   long best = -1;
@@ -108,7 +108,7 @@ inline void choose_xcd_grid(long tiles_m, long tiles_n, int nxcd, int& gm, int& 
     if (nxcd % c) continue;
     const int cm = c, cn = nxcd / c;
     if (tiles_m % cm || tiles_n % cn) continue;
-    const long cost = tiles_m / cm + tiles_n / cn;
+    const long cost = tiles_m / cm * bm + tiles_n / cn * bn;     // rows of A plus rows of B that one XCD reads
     if (best < 0 || cost < best) { best = cost; gm = cm; gn = cn; }
   }
 }

@@ -88,12 +88,11 @@ inline GemmArgs make_args(const GemmProblem& p, long k_per_split, int BM, int BN
     g.batch_c = p.batch_c * (p.c_dt == US_F32 ? 4 : 2);
   }
   g.nxcd = device_info().xcds;
-  choose_xcd_grid(ceil_div(p.M, BM), ceil_div(p.N, BN), g.nxcd, g.xcd_gm, g.xcd_gn);
+  choose_xcd_grid(ceil_div(p.M, BM), ceil_div(p.N, BN), g.nxcd, BM, BN, g.xcd_gm, g.xcd_gn);
   // bands 8 tiles wide: the 32 (one per CU) or 64 (two per CU) tiles that run together on an XCD form 4 x 8 or 8 x 8.
   // (Measured for the large tile: 4 wide was 3 us slower on the 8192 x 4096 x 1024 product with the GELU epilogue,
   // 16 and 32 equal to 8; the other tile shapes show no difference between 2 and 16.)
   g.grp_w = 8;
-  (void)BM;
   return g;
 }
 
