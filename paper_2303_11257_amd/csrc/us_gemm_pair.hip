@@ -54,7 +54,7 @@ bool mid_one_round_ok(const GemmProblem& dx, const GemmProblem& dw) {
 
 // grad_X with the table-driven GELU' whose large tiles fit one round on their own but not next to grad_W's tiles
 // (BERT-base layer 2: 192 + 144 on 256 CUs): twice as many tiles of 128 x 256 fill the second round's gaps
-// (FP16: 62.7 -> 59.5 us, same box)
+// (FP16: 62.7 -> 59.5 us; FP8 operands at the same shape: 46.6 -> 43.1 us; same box each)
 bool half_tile_ok(const GemmProblem& dx, const GemmProblem& dw) {
   const long tw = long_tile_ok(dw) ? ceil_div(dw.M, 256) * ceil_div(dw.N, 128) : ceil_div(dw.M, 128) * ceil_div(dw.N, 128);
   const long t = ceil_div(dx.M, 256) * ceil_div(dx.N, 256);
